@@ -1,0 +1,218 @@
+/*
+ * bita.h -- C ABI of the MI355X (gfx950) tree-verify step of BiTA
+ * (Bi-directional Tuning for lossless Acceleration, arXiv 2401.12522).
+ *
+ * One decode step of the paper's streamlined generation-and-verification loop
+ * (Sec. 3.2, Appendix B, Algorithm 1) is four calls on one HIP stream:
+ *
+ *   bita_build_tree   candidates of the previous pass -> token of every row
+ *   bita_verify_step  one decoder forward F(T, O, C, M; P) over the flattened
+ *                     token tree plus mask tokens, under tree-based attention
+ *   bita_accept       greedy verification walk (Algorithm 1, inner loops)
+ *   bita_compact_kv   commit the accepted rows' K/V to the cache
+ *
+ * Conventions
+ *   - Every call returns an int status: BITA_OK or a negative BITA_ERR_* code;
+ *     bita_last_error() returns a human-readable message for the calling thread.
+ *     Nothing aborts or throws.
+ *   - Pointers named d_* (and every pointer inside bita_weights / bita_kv) are
+ *     DEVICE pointers BORROWED from the caller; the library never frees them.
+ *     Pointers without the prefix are HOST pointers, read during the call only.
+ *   - `stream` is a hipStream_t passed as void*.  The four step calls only
+ *     enqueue work: no allocation, no host synchronisation, no host read of
+ *     device memory.  Results are valid once the caller has synchronised the
+ *     stream.  They may be captured into a HIP graph by the caller.
+ *   - Row layout of a pass ("template"): R rows per sequence.  Row 0 is the root
+ *     (the last emitted token, whose K/V is not cached yet), rows 1..T-1 the
+ *     draft-token tree flattened in level order (Sec. 3.2), rows T..R-1 mask
+ *     tokens.  A group of n mask tokens attached to node v is the parent chain
+ *     v -> m_1 -> ... -> m_n, so one parent array covers both kinds of row.
+ *   - All floating-point tensors are bf16 unless stated; accumulation, the
+ *     residual stream, softmax and logits are fp32.
+ */
+#ifndef BITA_H
+#define BITA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define BITA_OK               0
+#define BITA_ERR_INVALID_ARG -1   /* null pointer, non-positive size, misaligned shape        */
+#define BITA_ERR_BAD_TREE    -2   /* parent[i] >= i, root not row 0, mask groups malformed    */
+#define BITA_ERR_CAPACITY    -3   /* KV cache, rotary table or workspace too small            */
+#define BITA_ERR_UNSUPPORTED -4   /* shape outside what the kernels are built for             */
+#define BITA_ERR_HIP         -5   /* a HIP runtime call failed; see bita_last_error()         */
+
+#define BITA_MAX_ROWS   512      /* R limit of one template                                   */
+#define BITA_MAX_TOPK    64      /* kmax limit                                                */
+
+/* Decoder shape.  LLaMA-2 architecture (the paper's base models, Sec. 4.1.2):
+ * RMSNorm, rotary embeddings in the half-split pairing (i, i + head_dim/2),
+ * SwiGLU, grouped-query attention, no biases, untied LM head.
+ * Supported: head_dim 64 or 128; d_model, d_ffn multiples of 8; (n_heads +
+ * 2 n_kv_heads) * head_dim, d_model, d_ffn and vocab multiples of 16. */
+typedef struct bita_config {
+    int32_t n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab;
+    int32_t n_prompt;   /* P: prompt-prefix tokens per layer (may be 0)             */
+    int32_t n_mask;     /* n: mask tokens per group                                 */
+    int32_t max_pos;    /* rotary table covers positions 0 .. max_pos-1             */
+    float   rms_eps, rope_theta;
+} bita_config;
+
+/* Device weight table.  The four matrices of a layer are given PACKED (see
+ * bita_pack_weight); everything else is plain row-major bf16.
+ *   wqkv[l]     packed rows: Wq (n_heads*hd), then Wk, then Wv (n_kv_heads*hd each), K = d_model
+ *   wo[l]       packed [d_model] x K = n_heads*hd
+ *   w_gate_up[l] packed, 16-row tiles interleaved: tile 2j = rows 16j.. of W_gate,
+ *               tile 2j+1 = rows 16j.. of W_up; K = d_model
+ *   w_down[l]   packed [d_model] x K = d_ffn
+ *   lm_head     packed [vocab] x K = d_model
+ *   prompt_k/v[l] [n_kv_heads][P][head_dim]: per-layer prompt prefix, used as
+ *               stored (no rotary, no projection), visible to mask rows only
+ *               (Sec. 3.1 and the tree-based attention of Sec. 3.2).
+ * The per-layer members are HOST arrays of n_layers device pointers. */
+typedef struct bita_weights {
+    const void *tok_emb;      /* [vocab][d_model]  */
+    const void *mask_emb;     /* [n_mask][d_model] (Sec. 3.1, mask tokens) */
+    const void *final_norm;   /* [d_model] */
+    const void *lm_head;      /* packed */
+    const void *const *attn_norm, *const *ffn_norm;            /* [d_model] each */
+    const void *const *wqkv, *const *wo, *const *w_gate_up, *const *w_down;
+    const void *const *prompt_k, *const *prompt_v;
+} bita_weights;
+
+/* KV state, all device memory owned by the caller.
+ *   k_cache, v_cache [n_layers][batch][n_kv_heads][smax][head_dim]: K/V of the
+ *       tokens of the result sequence; slots < ctx_len are never written by
+ *       bita_verify_step.
+ *   k_tree, v_tree   [n_layers][batch][n_kv_heads][rows][head_dim]: K/V of the R
+ *       rows of the current pass (scratch; only accepted rows are ever committed).
+ *   ctx_hint: HOST upper bound on every sequence's ctx_len for this call, used
+ *       only to size launches and to check capacity without reading device memory. */
+typedef struct bita_kv {
+    void *k_cache, *v_cache;
+    void *k_tree, *v_tree;
+    int32_t smax, rows, batch, ctx_hint;
+} bita_kv;
+
+typedef struct bita_model bita_model;                 /* opaque */
+typedef struct bita_tree_template bita_tree_template; /* opaque */
+
+/* Bytes needed for the packed form of an [N][K] matrix (N, K as given to
+ * bita_pack_weight; N multiple of 16, K multiple of 8). */
+size_t bita_packed_bytes(int64_t n_rows, int64_t k);
+
+/* Re-lay rows of a row-major bf16 matrix d_src[N][K] (y = x W^T convention) into
+ * the streaming order of the skinny-GEMM kernel: the destination is a sequence
+ * of 16-row tiles, each holding its K range (zero-padded to a multiple of 32) as
+ * 1 KiB blocks in MFMA operand order.  Source tile j is written to destination
+ * tile dst_tile0 + j*dst_tile_stride, which lets several matrices share one
+ * packed buffer (QKV concatenation, gate/up interleave).  A pure permutation of
+ * bits.  d_dst must hold bita_packed_bytes(total rows, K). */
+int bita_pack_weight(const void *d_src, int64_t n_rows, int64_t k, void *d_dst,
+                     int64_t dst_tile0, int64_t dst_tile_stride, void *stream);
+
+/* Create a model handle: copies the pointer table and builds the rotary
+ * cos/sin table (allocates device memory once; freed by bita_model_destroy). */
+int  bita_model_create(const bita_config *cfg, const bita_weights *w, bita_model **out);
+void bita_model_destroy(bita_model *m);
+
+/* Workspace bytes bita_verify_step needs for `batch` sequences of `rows` rows. */
+size_t bita_workspace_bytes(const bita_model *m, int32_t batch, int32_t rows);
+
+/* Validate a pass layout and mirror it to the device: depths, sibling ranks,
+ * mask-group structure and ancestor-or-self bitsets (what a row attends to
+ * inside the pass, Sec. 3.2) are derived here, once.  parent and is_mask are HOST
+ * arrays of `rows` entries; the first n_tree rows are the token tree.  Every mask
+ * group must be n_mask consecutive rows forming a chain. */
+int  bita_tree_template_create(const int32_t *parent, const uint8_t *is_mask, int32_t n_tree,
+                               int32_t rows, int32_t n_mask, bita_tree_template **out);
+void bita_tree_template_destroy(bita_tree_template *t);
+/* Host-side facts about a template: 0 rows, 1 n_tree, 2 n_groups, 3 tree depth,
+ * 4 kmax (largest sibling count), 5 bitset words per row. */
+int32_t bita_tree_template_info(const bita_tree_template *t, int32_t what);
+
+/* Tokens of the next pass (Algorithm 1: the candidate set C^t becomes the tree).
+ *   d_root_token [B]            the token emitted last (previous bonus token)
+ *   d_cand [B][cand_rows][kmax] top-k ids of the previous pass' mask rows
+ *                               (cand_rows = its number of groups times n)
+ *   d_group [B] or NULL (=0)    which group of the previous pass feeds the tree
+ *   d_shift [B] or NULL (=0)    how many of its leading masks are stale
+ *   d_token [B][R] out          draft row at depth dv, sibling rank j gets
+ *                               cand[group*n + dv-1+shift][j]; rows with no
+ *                               prediction are inactive (-1); mask rows carry
+ *                               their index inside the group. */
+int bita_build_tree(const bita_tree_template *t, const int32_t *d_root_token,
+                    const int32_t *d_cand, int32_t cand_rows, int32_t kmax,
+                    const int32_t *d_group, const int32_t *d_shift,
+                    int32_t batch, int32_t *d_token, void *stream);
+
+/* One forward pass over B sequences of R rows each (Algorithm 1, the call to F).
+ * Row r of sequence b is embedded (tok_emb[token] / mask_emb[index] / zero if
+ * inactive), placed at rotary position ctx_len[b] + depth(r), and attends to the
+ * prompt prefix (mask rows only), to cache slots 0..ctx_len[b]-1 and to its
+ * ancestors-or-self among the rows of the pass.  Writes the rows' K/V to
+ * kv->k_tree/v_tree.
+ *   d_argmax   [B][T]            greedy token of every tree row (ties: lowest id)
+ *   d_topk_ids [B][G*n][kmax]    top-k of every mask row, value descending, ties by
+ *                                lower id (may be NULL if the template has no masks)
+ *   d_topk_val same shape, fp32, or NULL
+ *   d_logits   [B][R][vocab] fp32 or NULL (then kept in the workspace)
+ * Errors: CAPACITY if ctx_hint + depth exceeds max_pos or smax, or ws too small. */
+int bita_verify_step(bita_model *m, const bita_kv *kv, const bita_tree_template *t,
+                     const int32_t *d_token, const int32_t *d_ctx_len, int32_t batch,
+                     void *d_workspace, size_t ws_bytes, int32_t kmax,
+                     int32_t *d_argmax, int32_t *d_topk_ids, float *d_topk_val,
+                     float *d_logits, void *stream);
+
+/* Greedy verification (Sec. 3.2; Algorithm 1): from the root, step to the child
+ * whose token equals the current row's greedy token (lowest row if several), until
+ * none does.
+ *   d_path    [B][depth+1]  accepted rows, root first, padded with -1
+ *   d_n_acc   [B]           path length, 1 .. depth+1
+ *   d_bonus   [B]           greedy token of the last accepted row (always emitted)
+ *   d_emitted [B][depth+1]  tokens of path[1:], then the bonus, padded with -1
+ *   d_next_group, d_next_shift [B]  mask group feeding the next tree: the one on the
+ *       last accepted row (shift 0), else the root's with shift = n_acc-1. */
+int bita_accept(const bita_tree_template *t, const int32_t *d_token, const int32_t *d_argmax,
+                int32_t batch, int32_t *d_path, int32_t *d_n_acc, int32_t *d_bonus,
+                int32_t *d_emitted, int32_t *d_next_group, int32_t *d_next_shift, void *stream);
+
+/* For every layer and kv-head: cache[ctx_len + i] <- tree[path[i]], i < n_acc;
+ * then ctx_len += n_acc.  Bit-exact copies.  path_stride is the row length of
+ * d_path.  Rows that would land beyond smax are dropped and ctx_len is left
+ * unchanged for that sequence (the host-side ctx_hint check normally prevents it). */
+int bita_compact_kv(const bita_model *m, const bita_kv *kv, const int32_t *d_path,
+                    int32_t path_stride, const int32_t *d_n_acc, int32_t *d_ctx_len,
+                    int32_t batch, void *stream);
+
+/* Tree-masked attention alone (the kernel bita_verify_step runs per layer), for
+ * kernel-level tests and measurement.  d_q [B][R][n_heads][hd] (already rotated),
+ * K/V arguments are one layer's slices laid out as in bita_kv; d_out
+ * [B][R][n_heads*hd] bf16.  d_ws needs bita_attention_workspace_bytes(). */
+size_t bita_attention_workspace_bytes(int32_t batch, int32_t rows, int32_t n_heads,
+                                      int32_t head_dim, int32_t ctx_hint, int32_t n_prompt);
+int bita_tree_attention(const bita_tree_template *t, const void *d_q,
+                        const void *d_k_cache, const void *d_v_cache,
+                        const void *d_k_tree, const void *d_v_tree,
+                        const void *d_prompt_k, const void *d_prompt_v,
+                        const int32_t *d_ctx_len, int32_t batch, int32_t n_heads,
+                        int32_t n_kv_heads, int32_t head_dim, int32_t n_prompt, int32_t smax,
+                        int32_t ctx_hint, void *d_ws, size_t ws_bytes, void *d_out, void *stream);
+
+/* Skinny GEMM alone: d_out[M][N] (fp32) = d_a[M][K] (bf16, row stride lda) times the
+ * packed [N][K] matrix transposed.  d_ws needs bita_gemm_workspace_bytes(). */
+size_t bita_gemm_workspace_bytes(int32_t m_rows, int64_t n_rows);
+int bita_gemm(const void *d_a, int32_t m_rows, int64_t k, int64_t lda, const void *d_w_packed,
+              int64_t n_rows, void *d_ws, size_t ws_bytes, float *d_out, void *stream);
+
+const char *bita_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BITA_H */

@@ -1,0 +1,392 @@
+// Tree-masked attention of the verify pass (Sec. 3.2, "tree-based attention"): every row of
+// the pass attends to all cached tokens and to its ancestors-or-self among the rows of the
+// pass; mask-token rows additionally attend to the per-layer prompt prefix.
+//
+// Flash-style, one workgroup per (sequence, query head, key split):
+//  * the key axis [prefix | cache | pass rows] is cut into 128-key tiles; K tiles are staged
+//    in LDS row-major, V tiles transposed, so both feed v_mfma_f32_16x16x32_bf16 with one
+//    16-byte LDS read per operand;
+//  * the 4 wavefronts split each tile's keys (32 each) and keep their own online-softmax
+//    state for all query rows, merged through LDS at the end (fixed order, deterministic);
+//  * S^T = K Q^T is computed so that its accumulator layout is already the B-operand layout
+//    of O^T = V^T P^T: the probabilities never leave registers;
+//  * the tree mask is derived from per-row ancestor bitsets and only evaluated in tiles that
+//    touch the prefix or the pass rows; pure cache tiles take an unmasked path.
+// Partial (m, l, O) per split are combined by attn_merge_kernel.
+#include "common.h"
+
+#define ATT_TK 128
+#define ATT_WAVES 4
+#define ATT_PAD 8   // bf16 elements of row padding in both LDS tiles
+
+template <int HD>
+struct AttSmem {
+    static constexpr int K_STRIDE = HD + ATT_PAD;          // bf16 per K row
+    static constexpr int V_STRIDE = ATT_TK + ATT_PAD;      // bf16 per V^T row
+    static constexpr int K_BYTES = ATT_TK * K_STRIDE * 2;
+    static constexpr int V_BYTES = HD * V_STRIDE * 2;
+    static constexpr int TILE_BYTES = K_BYTES + V_BYTES;
+};
+
+template <int HD, int MT>
+constexpr int att_smem_bytes() {
+    const int tile = AttSmem<HD>::TILE_BYTES;
+    const int merge = MT * 16 * (HD + 4) * 4 + 2 * ATT_WAVES * MT * 16 * 4;
+    return tile > merge ? tile : merge;
+}
+
+template <int HD, int MT>
+__global__ __launch_bounds__(ATT_WAVES * 64) void tree_attn_kernel(
+    TemplateDev t, const uint16_t *__restrict__ q, const uint16_t *__restrict__ k_cache,
+    const uint16_t *__restrict__ v_cache, const uint16_t *__restrict__ k_tree,
+    const uint16_t *__restrict__ v_tree, const uint16_t *__restrict__ prompt_k,
+    const uint16_t *__restrict__ prompt_v, const int32_t *__restrict__ ctx_len, int Hq, int Hkv,
+    int P, int smax, int n_splits, int n_qblk, float scale_log2, float *__restrict__ part_o,
+    float *__restrict__ part_ml) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    constexpr int GPK = HD / 8;                    // 16-byte granules per key row
+    constexpr int KSN = HD / 32;                   // k-steps of the QK^T contraction
+    constexpr int NTN = HD / 16;                   // 16-wide tiles of the head dimension
+    constexpr int K_IT = ATT_TK * GPK / 256;       // K granules per thread per tile
+    constexpr int V_IT = ATT_TK / 2 * GPK / 256;   // V key-pair granules per thread per tile
+    constexpr int KSTR = AttSmem<HD>::K_STRIDE * 2, VSTR = AttSmem<HD>::V_STRIDE * 2;   // bytes
+    unsigned char *ks_lds = smem, *vt_lds = smem + AttSmem<HD>::K_BYTES;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 4, c = lane & 15;
+    const int split = blockIdx.x, h = blockIdx.y / n_qblk, qblk = blockIdx.y % n_qblk, b = blockIdx.z;
+    const int kvh = h / (Hq / Hkv);
+    const int R = t.rows, Lc = ctx_len[b];
+    const int n_keys = P + Lc + R;
+    const int n_tiles = (n_keys + ATT_TK - 1) / ATT_TK;
+    const int per_split = (n_tiles + n_splits - 1) / n_splits;
+    const int tile_begin = split * per_split;
+    const int tile_end = min(n_tiles, tile_begin + per_split);
+    const int row0 = qblk * MT * 16;
+
+    const uint16_t *pk = prompt_k + (int64_t)kvh * P * HD, *pv = prompt_v + (int64_t)kvh * P * HD;
+    const uint16_t *ck = k_cache + ((int64_t)b * Hkv + kvh) * smax * HD;
+    const uint16_t *cv = v_cache + ((int64_t)b * Hkv + kvh) * smax * HD;
+    const uint16_t *tk = k_tree + ((int64_t)b * Hkv + kvh) * R * HD;
+    const uint16_t *tv = v_tree + ((int64_t)b * Hkv + kvh) * R * HD;
+
+    // Q fragments (B operand of S^T = K Q^T): lane holds Q[row0 + 16mt + c][32ks + 8g .. +8]
+    bf16x8 qf[MT][KSN];
+    bool row_ok[MT], row_mask[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; mt++) {
+        const int r = row0 + mt * 16 + c;
+        row_ok[mt] = r < R;
+        row_mask[mt] = row_ok[mt] && t.is_mask[r];
+#pragma unroll
+        for (int ks = 0; ks < KSN; ks++) {
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (row_ok[mt])
+                v = *reinterpret_cast<const uint4 *>(q + (((int64_t)b * R + r) * Hq + h) * HD + ks * 32 + g * 8);
+            qf[mt][ks] = __builtin_bit_cast(bf16x8, v);
+        }
+    }
+
+    f32x4 o_acc[NTN][MT];
+    float m_run[MT], l_run[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; mt++) {
+        m_run[mt] = -INFINITY;
+        l_run[mt] = 0.f;
+#pragma unroll
+        for (int nt = 0; nt < NTN; nt++) o_acc[nt][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    uint4 k_stage[K_IT], v_stage[V_IT][2];
+    auto src_row = [&](int kidx, const uint16_t *pp, const uint16_t *cp, const uint16_t *tp) -> const uint16_t * {
+        if (kidx < P) return pp + (int64_t)kidx * HD;
+        if (kidx < P + Lc) return cp + (int64_t)(kidx - P) * HD;
+        if (kidx < n_keys) return tp + (int64_t)(kidx - P - Lc) * HD;
+        return nullptr;
+    };
+    auto prefetch = [&](int tile) {
+        const int base = tile * ATT_TK;
+#pragma unroll
+        for (int it = 0; it < K_IT; it++) {
+            const int id = it * 256 + tid, key = id / GPK, part = id % GPK;
+            const uint16_t *p = src_row(base + key, pk, ck, tk);
+            k_stage[it] = p ? *reinterpret_cast<const uint4 *>(p + part * 8) : make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int it = 0; it < V_IT; it++) {
+            const int id = it * 256 + tid, kp = id / GPK, part = id % GPK;
+#pragma unroll
+            for (int e = 0; e < 2; e++) {
+                const uint16_t *p = src_row(base + 2 * kp + e, pv, cv, tv);
+                v_stage[it][e] = p ? *reinterpret_cast<const uint4 *>(p + part * 8) : make_uint4(0, 0, 0, 0);
+            }
+        }
+    };
+    auto stage_to_lds = [&]() {
+#pragma unroll
+        for (int it = 0; it < K_IT; it++) {
+            const int id = it * 256 + tid, key = id / GPK, part = id % GPK;
+            *reinterpret_cast<uint4 *>(ks_lds + key * KSTR + part * 16) = k_stage[it];
+        }
+#pragma unroll
+        for (int it = 0; it < V_IT; it++) {
+            const int id = it * 256 + tid, kp = id / GPK, part = id % GPK;
+            const uint32_t a[4] = {v_stage[it][0].x, v_stage[it][0].y, v_stage[it][0].z, v_stage[it][0].w};
+            const uint32_t d[4] = {v_stage[it][1].x, v_stage[it][1].y, v_stage[it][1].z, v_stage[it][1].w};
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+                // hd element 2j of both keys, then element 2j+1
+                const uint32_t even = (a[j] & 0xFFFFu) | (d[j] << 16);
+                const uint32_t odd = (a[j] >> 16) | (d[j] & 0xFFFF0000u);
+                *reinterpret_cast<uint32_t *>(vt_lds + (part * 8 + 2 * j) * VSTR + kp * 4) = even;
+                *reinterpret_cast<uint32_t *>(vt_lds + (part * 8 + 2 * j + 1) * VSTR + kp * 4) = odd;
+            }
+        }
+    };
+
+    if (tile_begin < tile_end) prefetch(tile_begin);
+    const int kb = wave * 32;                                // this wave's keys inside a tile
+    for (int tile = tile_begin; tile < tile_end; tile++) {
+        __syncthreads();                                     // previous tile fully consumed
+        stage_to_lds();
+        __syncthreads();
+        if (tile + 1 < tile_end) prefetch(tile + 1);
+        const int base = tile * ATT_TK;
+        if (base + kb >= n_keys) continue;                   // nothing but padding for this wave
+
+        // S^T[key][q]: rows of sub-tile tt are keys 8*(i/4) + 4*tt + i%4, so that a lane ends
+        // up with 8 consecutive keys (8g .. 8g+7) for its query row.
+        f32x4 s_acc[MT][2];
+#pragma unroll
+        for (int mt = 0; mt < MT; mt++) s_acc[mt][0] = s_acc[mt][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int tt = 0; tt < 2; tt++) {
+            const int key = kb + 8 * (c >> 2) + 4 * tt + (c & 3);
+#pragma unroll
+            for (int ks = 0; ks < KSN; ks++) {
+                const bf16x8 kf = __builtin_bit_cast(
+                    bf16x8, *reinterpret_cast<const uint4 *>(ks_lds + key * KSTR + (ks * 32 + g * 8) * 2));
+#pragma unroll
+                for (int mt = 0; mt < MT; mt++)
+                    s_acc[mt][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[mt][ks], s_acc[mt][tt], 0, 0, 0);
+            }
+        }
+
+        const bool need_mask = (base < P) || (base + ATT_TK > P + Lc);
+        bf16x8 pf[MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; mt++) {
+            float sv[8];
+#pragma unroll
+            for (int tt = 0; tt < 2; tt++)
+#pragma unroll
+                for (int r = 0; r < 4; r++) sv[tt * 4 + r] = s_acc[mt][tt][r] * scale_log2;
+            if (need_mask) {
+                // 8-bit visibility word for this lane's keys k0 .. k0+7, built with integer
+                // selects only: prefix -> mask rows, cache -> all rows, pass rows -> ancestor bits.
+                const int rq = row0 + mt * 16 + c;
+                const int k0 = base + kb + 8 * g;
+                uint32_t bits = 0;
+                if (row_ok[mt]) {
+                    const int j0 = k0 - P - Lc;                  // first key relative to the pass rows
+                    uint64_t win = 0;                            // ancestor bits j0 .. j0+7 in bits 0..7
+                    const uint64_t *a = t.anc + (int64_t)rq * t.words;
+                    if (j0 > -8 && j0 < R) {
+                        if (j0 < 0) {
+                            win = a[0] << (-j0);
+                        } else {
+                            const int w = j0 >> 6, sh = j0 & 63;
+                            win = a[w] >> sh;
+                            if (sh > 56 && w + 1 < t.words) win |= a[w + 1] << (64 - sh);
+                        }
+                    }
+                    const uint32_t tree_bits = (uint32_t)win & 0xFFu;
+#pragma unroll
+                    for (int e = 0; e < 8; e++) {
+                        const int kidx = k0 + e;
+                        const uint32_t in_prefix = kidx < P ? 1u : 0u;
+                        const uint32_t in_cache = (kidx >= P && kidx < P + Lc) ? 1u : 0u;
+                        const uint32_t in_tree = (kidx >= P + Lc && kidx < n_keys) ? 1u : 0u;
+                        const uint32_t v = (in_prefix & (row_mask[mt] ? 1u : 0u)) | in_cache |
+                                           (in_tree & (tree_bits >> e));
+                        bits |= (v & 1u) << e;
+                    }
+                }
+#pragma unroll
+                for (int e = 0; e < 8; e++) sv[e] = ((bits >> e) & 1u) ? sv[e] : -INFINITY;
+            }
+            float mx = sv[0];
+#pragma unroll
+            for (int e = 1; e < 8; e++) mx = fmaxf(mx, sv[e]);
+            mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            const float m_new = fmaxf(m_run[mt], mx);
+            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+            const float alpha = exp2f(m_run[mt] - m_use);
+            m_run[mt] = m_new;
+            float ps = 0.f;
+            uint32_t pk2[4];
+#pragma unroll
+            for (int e = 0; e < 8; e += 2) {
+                const float p0 = exp2f(sv[e] - m_use), p1 = exp2f(sv[e + 1] - m_use);
+                ps += p0 + p1;
+                pk2[e >> 1] = pack_bf16x2(p0, p1);
+            }
+            l_run[mt] = l_run[mt] * alpha + ps;
+            pf[mt] = __builtin_bit_cast(bf16x8, make_uint4(pk2[0], pk2[1], pk2[2], pk2[3]));
+#pragma unroll
+            for (int nt = 0; nt < NTN; nt++) o_acc[nt][mt] *= alpha;
+        }
+        // O^T[hd][q] += V^T[hd][keys 8g..8g+7] * P^T
+#pragma unroll
+        for (int nt = 0; nt < NTN; nt++) {
+            const bf16x8 vf = __builtin_bit_cast(
+                bf16x8, *reinterpret_cast<const uint4 *>(vt_lds + (nt * 16 + c) * VSTR + (kb + 8 * g) * 2));
+#pragma unroll
+            for (int mt = 0; mt < MT; mt++)
+                o_acc[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[mt], o_acc[nt][mt], 0, 0, 0);
+        }
+    }
+
+    // ---- merge the 4 wavefronts (each saw a disjoint key subset) --------------------------
+    __syncthreads();
+    constexpr int OSTR = HD + 4;                           // floats per merged row
+    float *o_sum = reinterpret_cast<float *>(smem);
+    float *sm = o_sum + MT * 16 * OSTR, *sl = sm + ATT_WAVES * MT * 16;
+#pragma unroll
+    for (int mt = 0; mt < MT; mt++) {
+        float l = l_run[mt];
+        l += __shfl_xor(l, 16, 64);
+        l += __shfl_xor(l, 32, 64);
+        l_run[mt] = l;
+        if (g == 0) {
+            sm[wave * MT * 16 + mt * 16 + c] = m_run[mt];
+            sl[wave * MT * 16 + mt * 16 + c] = l;
+        }
+    }
+    __syncthreads();
+    float m_tot[MT], l_tot[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; mt++) {
+        float m = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < ATT_WAVES; w++) m = fmaxf(m, sm[w * MT * 16 + mt * 16 + c]);
+        const float m_use = (m == -INFINITY) ? 0.f : m;
+        float l = 0.f;
+#pragma unroll
+        for (int w = 0; w < ATT_WAVES; w++)
+            l += sl[w * MT * 16 + mt * 16 + c] * exp2f(sm[w * MT * 16 + mt * 16 + c] - m_use);
+        const float f = exp2f(m_run[mt] - m_use);
+        m_tot[mt] = m;
+        l_tot[mt] = l;
+#pragma unroll
+        for (int nt = 0; nt < NTN; nt++) o_acc[nt][mt] *= f;
+    }
+    for (int w = 0; w < ATT_WAVES; w++) {
+        if (wave == w) {
+#pragma unroll
+            for (int mt = 0; mt < MT; mt++)
+#pragma unroll
+                for (int nt = 0; nt < NTN; nt++) {
+                    float4 *dst = reinterpret_cast<float4 *>(o_sum + (mt * 16 + c) * OSTR + nt * 16 + 4 * g);
+                    float4 v = make_float4(o_acc[nt][mt][0], o_acc[nt][mt][1], o_acc[nt][mt][2], o_acc[nt][mt][3]);
+                    if (w > 0) {
+                        const float4 old = *dst;
+                        v.x += old.x; v.y += old.y; v.z += old.z; v.w += old.w;
+                    }
+                    *dst = v;
+                }
+        }
+        __syncthreads();
+    }
+    // ---- write the split's partial result --------------------------------------------------
+    const int64_t pbase = (((int64_t)b * Hq + h) * n_splits + split) * R;
+    for (int idx = tid; idx < MT * 16 * (HD / 4); idx += 256) {
+        const int qr = idx / (HD / 4), c4 = idx % (HD / 4);
+        const int r = row0 + qr;
+        if (r < R)
+            *reinterpret_cast<float4 *>(part_o + (pbase + r) * HD + c4 * 4) =
+                *reinterpret_cast<const float4 *>(o_sum + qr * OSTR + c4 * 4);
+    }
+    if (wave == 0 && g == 0) {
+#pragma unroll
+        for (int mt = 0; mt < MT; mt++) {
+            const int r = row0 + mt * 16 + c;
+            if (r < R) {
+                part_ml[(pbase + r) * 2] = m_tot[mt];
+                part_ml[(pbase + r) * 2 + 1] = l_tot[mt];
+            }
+        }
+    }
+}
+
+// out[b][r][h*HD + i] = sum_s w_s O_s[i] / sum_s w_s l_s,  w_s = 2^(m_s - max m)
+__global__ void attn_merge_kernel(const float *__restrict__ part_o, const float *__restrict__ part_ml,
+                                  int R, int Hq, int HD, int n_splits, uint16_t *__restrict__ out) {
+    const int r = blockIdx.x, h = blockIdx.y, b = blockIdx.z, i = threadIdx.x;
+    const int64_t pbase = ((int64_t)b * Hq + h) * n_splits;
+    float m = -INFINITY;
+    for (int s = 0; s < n_splits; s++) m = fmaxf(m, part_ml[((pbase + s) * R + r) * 2]);
+    const float m_use = (m == -INFINITY) ? 0.f : m;
+    float l = 0.f, acc = 0.f;
+    for (int s = 0; s < n_splits; s++) {
+        const float w = exp2f(part_ml[((pbase + s) * R + r) * 2] - m_use);
+        l += w * part_ml[((pbase + s) * R + r) * 2 + 1];
+        acc += w * part_o[((pbase + s) * R + r) * HD + i];
+    }
+    out[(((int64_t)b * R + r) * Hq + h) * HD + i] = f32_to_bf16(l > 0.f ? acc / l : 0.f);
+}
+
+AttnPlan attn_plan(int batch, int rows, int n_heads, int hd, int ctx_hint, int n_prompt) {
+    AttnPlan p;
+    const int n_keys = n_prompt + ctx_hint + rows;
+    const int n_tiles = (n_keys + ATT_TK - 1) / ATT_TK;
+    const int n_qblk = (rows + 79) / 80;
+    const int wgs = batch * n_heads * n_qblk;
+    int splits = (512 + wgs - 1) / wgs;                   // aim at ~2 workgroups per CU
+    if (splits > n_tiles) splits = n_tiles;
+    if (splits < 1) splits = 1;
+    if (splits > 32) splits = 32;
+    p.splits = splits;
+    p.part_o_bytes = (size_t)batch * n_heads * splits * rows * hd * sizeof(float);
+    p.part_ml_bytes = (size_t)batch * n_heads * splits * rows * 2 * sizeof(float);
+    return p;
+}
+
+template <int HD, int MT>
+static void launch_attn_t(const TemplateDev &t, const void *q, const void *k_cache, const void *v_cache,
+                          const void *k_tree, const void *v_tree, const void *prompt_k,
+                          const void *prompt_v, const int32_t *ctx_len, int batch, int Hq, int Hkv, int P,
+                          int smax, const AttnPlan &p, float *part_o, float *part_ml, hipStream_t s) {
+    constexpr int smem = att_smem_bytes<HD, MT>();
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute((const void *)tree_attn_kernel<HD, MT>,
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+        attr_set = true;
+    }
+    const int n_qblk = (t.rows + MT * 16 - 1) / (MT * 16);
+    const float scale_log2 = 1.4426950408889634f / sqrtf((float)HD);
+    dim3 grid(p.splits, Hq * n_qblk, batch);
+    hipLaunchKernelGGL((tree_attn_kernel<HD, MT>), grid, dim3(ATT_WAVES * 64), smem, s, t,
+                       (const uint16_t *)q, (const uint16_t *)k_cache, (const uint16_t *)v_cache,
+                       (const uint16_t *)k_tree, (const uint16_t *)v_tree, (const uint16_t *)prompt_k,
+                       (const uint16_t *)prompt_v, ctx_len, Hq, Hkv, P, smax, p.splits, n_qblk, scale_log2,
+                       part_o, part_ml);
+}
+
+void launch_tree_attention(const TemplateDev &t, const void *q, const void *k_cache, const void *v_cache,
+                           const void *k_tree, const void *v_tree, const void *prompt_k,
+                           const void *prompt_v, const int32_t *ctx_len, int batch, int Hq, int Hkv, int hd,
+                           int P, int smax, const AttnPlan &p, float *part_o, float *part_ml, void *out,
+                           hipStream_t s) {
+    const bool small = t.rows <= 16;
+    if (hd == 128) {
+        if (small) launch_attn_t<128, 1>(t, q, k_cache, v_cache, k_tree, v_tree, prompt_k, prompt_v, ctx_len, batch, Hq, Hkv, P, smax, p, part_o, part_ml, s);
+        else launch_attn_t<128, 5>(t, q, k_cache, v_cache, k_tree, v_tree, prompt_k, prompt_v, ctx_len, batch, Hq, Hkv, P, smax, p, part_o, part_ml, s);
+    } else {
+        if (small) launch_attn_t<64, 1>(t, q, k_cache, v_cache, k_tree, v_tree, prompt_k, prompt_v, ctx_len, batch, Hq, Hkv, P, smax, p, part_o, part_ml, s);
+        else launch_attn_t<64, 5>(t, q, k_cache, v_cache, k_tree, v_tree, prompt_k, prompt_v, ctx_len, batch, Hq, Hkv, P, smax, p, part_o, part_ml, s);
+    }
+    hipLaunchKernelGGL(attn_merge_kernel, dim3(t.rows, Hq, batch), dim3(hd), 0, s, part_o, part_ml, t.rows,
+                       Hq, hd, p.splits, (uint16_t *)out);
+}

@@ -1,0 +1,82 @@
+// Internal declarations shared by the HIP sources of libbita (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "../../include/bita.h"
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+#define BITA_WAVE 64
+
+// bf16 <-> fp32 on raw bits (round to nearest even; inputs are finite)
+__device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+}
+
+// ---- host-side error plumbing -------------------------------------------------
+int  bita_set_error(int code, const char *fmt, ...);
+#define BITA_HIP_CHECK(expr)                                                                 \
+    do {                                                                                     \
+        hipError_t _e = (expr);                                                              \
+        if (_e != hipSuccess)                                                                \
+            return bita_set_error(BITA_ERR_HIP, "%s failed: %s", #expr, hipGetErrorString(_e)); \
+    } while (0)
+
+// ---- device mirror of a pass layout ---------------------------------------------
+struct TemplateDev {
+    int32_t rows, n_tree, n_mask, n_groups, depth_max, kmax, words;
+    const int32_t *parent;        // [R]
+    const int32_t *depth;         // [R]
+    const int32_t *rank;          // [R] sibling rank of a tree row
+    const int32_t *mask_index;    // [R] index inside its group, -1 for tree rows
+    const int32_t *group_of_node; // [T] group attached to a tree row or -1
+    const int32_t *mask_rows;     // [G*n] row of mask i of group g
+    const uint8_t *is_mask;       // [R]
+    const uint64_t *anc;          // [R][words] ancestor-or-self bitsets
+};
+struct bita_tree_template {
+    TemplateDev dev;
+    void *blob;                   // one device allocation backing all arrays
+};
+
+// ---- kernel launchers (each only enqueues) --------------------------------------
+struct GemmPlan { int splits, ksteps_per_split, nw; };
+GemmPlan gemm_plan(int m_rows, int64_t n_rows, int64_t k);
+// out_partial: [splits][m_rows][ldo] fp32
+void launch_gemm(const void *a, int m_rows, int64_t k, int64_t lda, const void *w_packed,
+                 int64_t n_rows, float *out_partial, int64_t ldo, const GemmPlan &p, hipStream_t s);
+void launch_reduce_partials(const float *partial, int splits, int m_rows, int64_t n, int64_t ld,
+                            float *out, hipStream_t s);
+void launch_pack(const void *src, int64_t n_rows, int64_t k, void *dst, int64_t tile0,
+                 int64_t tile_stride, hipStream_t s);
+
+void launch_embed(const int32_t *token, const TemplateDev &t, int batch, const void *tok_emb,
+                  const void *mask_emb, int d, int vocab, float *x, hipStream_t s);
+// x += sum of partials (optional), then h = rmsnorm(x) * gain as bf16 with row stride ldh
+void launch_rmsnorm(float *x, const float *partial, int splits, int m_rows, int d,
+                    const void *gain, float eps, void *h, int64_t ldh, hipStream_t s);
+void launch_qkv_rope(const float *partial, int splits, int batch, const TemplateDev &t,
+                     int n_heads, int n_kv_heads, int hd, const int32_t *ctx_len,
+                     const float *rope_cos, const float *rope_sin, int max_pos,
+                     void *q, void *k_tree, void *v_tree, hipStream_t s);
+void launch_silu_mul(const float *partial, int splits, int m_rows, int d_ffn, void *act,
+                     int64_t ld_act, hipStream_t s);
+void launch_select(const float *logits, int batch, const TemplateDev &t, int vocab, int kmax,
+                   int32_t *argmax, int32_t *topk_ids, float *topk_val, hipStream_t s);
+
+struct AttnPlan { int splits; size_t part_o_bytes, part_ml_bytes; };
+AttnPlan attn_plan(int batch, int rows, int n_heads, int hd, int ctx_hint, int n_prompt);
+void launch_tree_attention(const TemplateDev &t, const void *q, const void *k_cache,
+                           const void *v_cache, const void *k_tree, const void *v_tree,
+                           const void *prompt_k, const void *prompt_v, const int32_t *ctx_len,
+                           int batch, int n_heads, int n_kv_heads, int hd, int n_prompt, int smax,
+                           const AttnPlan &p, float *part_o, float *part_ml, void *out,
+                           hipStream_t s);

@@ -1,0 +1,202 @@
+// Row-wise kernels of the verify step: embedding gather, RMSNorm (fused with the split-K
+// reduction and the residual add), rotary embedding + tree K/V write, SwiGLU gating, and the
+// vocabulary argmax / top-k selection with wavefront-shuffle reductions.
+#include "common.h"
+
+// ---------------------------------------------------------------------------------------
+// Embedding: tree rows take tok_emb[token], mask rows mask_emb[index] (Sec. 3.1), inactive
+// rows (token < 0) the zero vector.  x is the fp32 residual stream [B*R][d].
+__global__ void embed_kernel(const int32_t *__restrict__ token, TemplateDev t,
+                             const uint16_t *__restrict__ tok_emb, const uint16_t *__restrict__ mask_emb,
+                             int d, int vocab, float *__restrict__ x) {
+    const int row = blockIdx.x, r = row % t.rows;
+    const int tok = token[row];
+    const uint16_t *src = nullptr;
+    if (t.is_mask[r]) {
+        src = mask_emb + (int64_t)t.mask_index[r] * d;
+    } else if (tok >= 0 && tok < vocab) {
+        src = tok_emb + (int64_t)tok * d;
+    }
+    for (int i = threadIdx.x; i < d; i += blockDim.x)
+        x[(int64_t)row * d + i] = src ? bf16_to_f32(src[i]) : 0.f;
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+// One workgroup per row: x += sum_s partial[s] (fixed order), h = x * rsqrt(mean(x^2)+eps) * g.
+__global__ __launch_bounds__(256) void rmsnorm_kernel(float *__restrict__ x, const float *__restrict__ partial,
+                                                      int splits, int M, int d,
+                                                      const uint16_t *__restrict__ gain, float eps,
+                                                      uint16_t *__restrict__ h, int64_t ldh) {
+    __shared__ float red[4];
+    const int row = blockIdx.x;
+    float *xr = x + (int64_t)row * d;
+    float ss = 0.f;
+    for (int i = threadIdx.x; i < d; i += 256) {
+        float v = xr[i];
+        for (int s = 0; s < splits; s++) v += partial[((int64_t)s * M + row) * d + i];
+        if (splits > 0) xr[i] = v;
+        ss += v * v;
+    }
+    ss = wave_sum(ss);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    const float tot = red[0] + red[1] + red[2] + red[3];
+    const float scale = 1.0f / sqrtf(tot / (float)d + eps);
+    for (int i = threadIdx.x; i < d; i += 256)
+        h[(int64_t)row * ldh + i] = f32_to_bf16(xr[i] * scale * bf16_to_f32(gain[i]));
+}
+
+// ---------------------------------------------------------------------------------------
+// QKV epilogue: sum split-K partials, rotate q and k by the row's position
+// ctx_len + depth(row) in the half-split pairing, write q [B][R][Hq][hd] and the rows'
+// k/v into the per-pass tree scratch [B][Hkv][R][hd].
+__global__ __launch_bounds__(64) void qkv_rope_kernel(
+    const float *__restrict__ partial, int splits, int M, TemplateDev t, int Hq, int Hkv, int hd,
+    const int32_t *__restrict__ ctx_len, const float *__restrict__ rope_cos,
+    const float *__restrict__ rope_sin, int max_pos, uint16_t *__restrict__ q,
+    uint16_t *__restrict__ k_tree, uint16_t *__restrict__ v_tree) {
+    const int row = blockIdx.x, head = blockIdx.y;       // head over Hq + 2*Hkv
+    const int b = row / t.rows, r = row % t.rows;
+    const int half = hd >> 1, i = threadIdx.x;
+    if (i >= half) return;
+    const int64_t ncols = (int64_t)(Hq + 2 * Hkv) * hd;
+    const int64_t col = (int64_t)head * hd + i;
+    float lo = 0.f, hi = 0.f;
+    for (int s = 0; s < splits; s++) {
+        const float *p = partial + ((int64_t)s * M + row) * ncols + col;
+        lo += p[0];
+        hi += p[half];
+    }
+    uint16_t *dst;
+    if (head < Hq) {
+        dst = q + ((int64_t)row * Hq + head) * hd;
+    } else if (head < Hq + Hkv) {
+        dst = k_tree + (((int64_t)b * Hkv + (head - Hq)) * t.rows + r) * hd;
+    } else {
+        dst = v_tree + (((int64_t)b * Hkv + (head - Hq - Hkv)) * t.rows + r) * hd;
+    }
+    if (head < Hq + Hkv) {
+        int pos = ctx_len[b] + t.depth[r];
+        pos = pos < max_pos ? pos : max_pos - 1;          // host checks capacity; stay in bounds
+        const float c = rope_cos[(int64_t)pos * half + i], sn = rope_sin[(int64_t)pos * half + i];
+        const float nlo = lo * c - hi * sn, nhi = hi * c + lo * sn;
+        lo = nlo;
+        hi = nhi;
+    }
+    dst[i] = f32_to_bf16(lo);
+    dst[i + half] = f32_to_bf16(hi);
+}
+
+// ---------------------------------------------------------------------------------------
+// SwiGLU gating on the gate/up GEMM output whose 16-column tiles alternate gate, up.
+__global__ void silu_mul_kernel(const float *__restrict__ partial, int splits, int M, int F,
+                                uint16_t *__restrict__ act, int64_t ld_act) {
+    const int f = blockIdx.x * blockDim.x + threadIdx.x;
+    const int row = blockIdx.y;
+    if (f >= ld_act) return;
+    float out = 0.f;
+    if (f < F) {
+        const int64_t cg = (int64_t)(f >> 4) * 32 + (f & 15), cu = cg + 16;
+        float gsum = 0.f, usum = 0.f;
+        for (int s = 0; s < splits; s++) {
+            const float *p = partial + ((int64_t)s * M + row) * (2 * (int64_t)F);
+            gsum += p[cg];
+            usum += p[cu];
+        }
+        out = gsum / (1.0f + expf(-gsum)) * usum;
+    }
+    act[(int64_t)row * ld_act + f] = f32_to_bf16(out);
+}
+
+// ---------------------------------------------------------------------------------------
+// Selection over the vocabulary.  Order: value descending, lower id first among equals.
+// One workgroup per selected row; pass p finds the best entry that comes strictly after
+// the previous winner in that order, so k passes give the sorted top-k and pass 0 alone
+// is the greedy argmax.  Reductions: per-lane scan, wave shuffles, then 4 waves via LDS.
+struct Cand { float v; int i; };
+__device__ __forceinline__ bool better(float v, int i, float bv, int bi) {
+    return v > bv || (v == bv && i < bi);
+}
+__global__ __launch_bounds__(256) void select_kernel(const float *__restrict__ logits, TemplateDev t,
+                                                     int vocab, int kmax, int32_t *__restrict__ argmax,
+                                                     int32_t *__restrict__ topk_ids,
+                                                     float *__restrict__ topk_val) {
+    __shared__ float sv[4];
+    __shared__ int si[4];
+    const int b = blockIdx.y;
+    const int sel = blockIdx.x;                       // 0..T-1 tree rows, then G*n mask rows
+    const bool is_tree = sel < t.n_tree;
+    const int r = is_tree ? sel : t.mask_rows[sel - t.n_tree];
+    const int k = is_tree ? 1 : kmax;
+    const float *row = logits + ((int64_t)b * t.rows + r) * vocab;
+    float prev_v = INFINITY;
+    int prev_i = -1;
+    for (int p = 0; p < k; p++) {
+        float bv = -INFINITY;
+        int bi = 0x7FFFFFFF;
+        for (int i = threadIdx.x; i < vocab; i += 256) {
+            const float v = row[i];
+            const bool after_prev = (p == 0) || v < prev_v || (v == prev_v && i > prev_i);
+            if (after_prev && better(v, i, bv, bi)) { bv = v; bi = i; }
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            const float ov = __shfl_xor(bv, o, 64);
+            const int oi = __shfl_xor(bi, o, 64);
+            if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+        }
+        if ((threadIdx.x & 63) == 0) { sv[threadIdx.x >> 6] = bv; si[threadIdx.x >> 6] = bi; }
+        __syncthreads();
+        bv = sv[0]; bi = si[0];
+#pragma unroll
+        for (int w = 1; w < 4; w++)
+            if (better(sv[w], si[w], bv, bi)) { bv = sv[w]; bi = si[w]; }
+        __syncthreads();
+        prev_v = bv; prev_i = bi;
+        if (threadIdx.x == 0) {
+            if (is_tree) {
+                argmax[b * t.n_tree + sel] = bi;
+            } else {
+                const int64_t o = ((int64_t)b * (t.n_groups * t.n_mask) + (sel - t.n_tree)) * kmax + p;
+                topk_ids[o] = bi;
+                if (topk_val) topk_val[o] = bv;
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+void launch_embed(const int32_t *token, const TemplateDev &t, int batch, const void *tok_emb,
+                  const void *mask_emb, int d, int vocab, float *x, hipStream_t s) {
+    hipLaunchKernelGGL(embed_kernel, dim3(batch * t.rows), dim3(256), 0, s, token, t,
+                       (const uint16_t *)tok_emb, (const uint16_t *)mask_emb, d, vocab, x);
+}
+void launch_rmsnorm(float *x, const float *partial, int splits, int M, int d, const void *gain,
+                    float eps, void *h, int64_t ldh, hipStream_t s) {
+    hipLaunchKernelGGL(rmsnorm_kernel, dim3(M), dim3(256), 0, s, x, partial, splits, M, d,
+                       (const uint16_t *)gain, eps, (uint16_t *)h, ldh);
+}
+void launch_qkv_rope(const float *partial, int splits, int batch, const TemplateDev &t, int Hq,
+                     int Hkv, int hd, const int32_t *ctx_len, const float *rope_cos,
+                     const float *rope_sin, int max_pos, void *q, void *k_tree, void *v_tree,
+                     hipStream_t s) {
+    hipLaunchKernelGGL(qkv_rope_kernel, dim3(batch * t.rows, Hq + 2 * Hkv), dim3(64), 0, s, partial,
+                       splits, batch * t.rows, t, Hq, Hkv, hd, ctx_len, rope_cos, rope_sin, max_pos,
+                       (uint16_t *)q, (uint16_t *)k_tree, (uint16_t *)v_tree);
+}
+void launch_silu_mul(const float *partial, int splits, int M, int F, void *act, int64_t ld_act,
+                     hipStream_t s) {
+    hipLaunchKernelGGL(silu_mul_kernel, dim3((unsigned)((ld_act + 255) / 256), M), dim3(256), 0, s,
+                       partial, splits, M, F, (uint16_t *)act, ld_act);
+}
+void launch_select(const float *logits, int batch, const TemplateDev &t, int vocab, int kmax,
+                   int32_t *argmax, int32_t *topk_ids, float *topk_val, hipStream_t s) {
+    const int n_sel = t.n_tree + (topk_ids ? t.n_groups * t.n_mask : 0);
+    hipLaunchKernelGGL(select_kernel, dim3(n_sel, batch), dim3(256), 0, s, logits, t, vocab, kmax,
+                       argmax, topk_ids, topk_val);
+}

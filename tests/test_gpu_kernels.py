@@ -1,0 +1,153 @@
+"""Kernel-level parity (GPU): skinny GEMM, tree-masked attention, integer kernels and the
+vocabulary selection, each against the oracle through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth
+from oracle.model import attend_row, topk_desc, argmax_low
+from oracle.tree import derive_template, ancestors_or_self, build_tree_tokens, accept_walk, next_group_and_shift
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def bita():
+    import paper_2401_12522_amd as b
+    b.lib()
+    return b
+
+
+@pytest.mark.parametrize("M,N,K", [(1, 16, 32), (5, 48, 256), (68, 1024, 256), (68, 256, 688),
+                                   (68, 4096, 4096), (80, 12288, 4096), (100, 1024, 1376), (16, 32000, 256),
+                                   (272, 512, 512)])
+def test_gemm_matches_float64_matmul(bita, M, N, K):
+    g = torch.Generator().manual_seed(M * 7 + N)
+    a = (torch.randn(M, K, generator=g)).to(torch.bfloat16)
+    w = (torch.randn(N, K, generator=g) * 0.05).to(torch.bfloat16)
+    ref = a.to(torch.float64).numpy() @ w.to(torch.float64).numpy().T
+    wp = bita.pack_weight(w.cuda())
+    out = bita.gemm(a.cuda(), wp, N).cpu().numpy()
+    torch.cuda.synchronize()
+    scale = np.abs(ref).max()
+    assert np.abs(out - ref).max() <= 2e-5 * scale + 1e-6, (np.abs(out - ref).max(), scale)
+
+
+def _attention_case(bita, B, Hq, Hkv, hd, P, ctx_lens, tree_parent, attach, n_mask, seed, smax=None):
+    rng = np.random.default_rng(seed)
+    tin = synth.attach_mask_groups(tree_parent, attach, n_mask)
+    d = derive_template(tin.parent, tin.is_mask, n_mask)
+    R = d.R
+    smax = smax or (max(ctx_lens) + 8)
+    r16 = lambda *s: synth.bf16_round(rng.normal(size=s))   # noqa: E731
+    q = r16(B, R, Hq, hd)
+    kc, vc = r16(B, Hkv, smax, hd), r16(B, Hkv, smax, hd)
+    kt, vt = r16(B, Hkv, R, hd), r16(B, Hkv, R, hd)
+    pk, pv = (r16(Hkv, P, hd), r16(Hkv, P, hd)) if P else (None, None)
+    tmpl = bita.TreeTemplate(tin.parent, tin.is_mask, tin.n_tree, n_mask)
+    tb = lambda a: None if a is None else torch.tensor(a).to(torch.bfloat16).cuda()   # noqa: E731
+    out = bita.tree_attention(tmpl, tb(q), tb(kc), tb(vc), tb(kt), tb(vt), tb(pk), tb(pv),
+                              torch.tensor(ctx_lens, dtype=torch.int32, device="cuda"), max(ctx_lens))
+    torch.cuda.synchronize()
+    out = out.to(torch.float64).cpu().numpy().reshape(B, R, Hq, hd)
+    worst = 0.0
+    for b in range(B):
+        Lc = ctx_lens[b]
+        for r in range(R):
+            vis = ancestors_or_self(d.parent, r)
+            ks = [kc[b, :, :Lc].transpose(1, 0, 2), kt[b][:, vis].transpose(1, 0, 2)]
+            vs = [vc[b, :, :Lc].transpose(1, 0, 2), vt[b][:, vis].transpose(1, 0, 2)]
+            if d.is_mask[r] and P:
+                ks.insert(0, pk.transpose(1, 0, 2))
+                vs.insert(0, pv.transpose(1, 0, 2))
+            ref = attend_row(q[b, r], np.concatenate(ks), np.concatenate(vs), Hq, Hkv)
+            worst = max(worst, np.abs(out[b, r] - ref).max())
+    return worst
+
+
+# bf16 output rounding (2^-9 relative on values of order 1) plus bf16 probabilities: 2e-2 abs
+ATT_TOL = 2e-2
+
+
+@pytest.mark.parametrize("case", [
+    dict(B=1, Hq=4, Hkv=4, hd=64, P=8, ctx=[63], T=8, depth=3, attach=[0], n=4),
+    dict(B=1, Hq=4, Hkv=2, hd=64, P=8, ctx=[300], T=8, depth=3, attach=[0, 3], n=4),
+    dict(B=2, Hq=4, Hkv=1, hd=128, P=16, ctx=[130, 517], T=64, depth=6, attach=[0], n=4),
+    dict(B=1, Hq=2, Hkv=2, hd=128, P=0, ctx=[0], T=5, depth=2, attach=[0], n=2),
+    dict(B=1, Hq=2, Hkv=2, hd=128, P=16, ctx=[1], T=1, depth=0, attach=[], n=4),
+    dict(B=3, Hq=8, Hkv=1, hd=128, P=16, ctx=[1024, 96, 2047], T=64, depth=5, attach=[0], n=4),
+    dict(B=1, Hq=2, Hkv=1, hd=64, P=4, ctx=[200], T=21, depth=4, attach=list(range(21)), n=4),
+])
+def test_tree_attention_matches_oracle(bita, case):
+    parent = synth.random_tree(case["T"], max(case["depth"], 1), 11) if case["T"] > 1 else np.array([-1], np.int32)
+    err = _attention_case(bita, case["B"], case["Hq"], case["Hkv"], case["hd"], case["P"], case["ctx"],
+                          parent, case["attach"], case["n"], seed=5)
+    assert err < ATT_TOL, err
+
+
+def test_tree_attention_chain_equals_causal(bita):
+    """Special case: a chain template is plain causal attention over [cache | chain]."""
+    err = _attention_case(bita, 1, 4, 4, 64, 0, [100], synth.chain_tree(40), [], 4, seed=6)
+    assert err < ATT_TOL, err
+
+
+def test_integer_kernels_match_oracle(bita):
+    rng = np.random.default_rng(0)
+    for trial in range(40):
+        T = int(rng.integers(1, 70))
+        n = int(rng.integers(1, 5))
+        parent = synth.random_tree(T, int(rng.integers(1, 7)), trial)
+        per_node = trial % 3 == 0 and T <= 40
+        tin = synth.attach_mask_groups(parent, list(range(T)) if per_node else [0], n)
+        d = derive_template(tin.parent, tin.is_mask, n)
+        tmpl = bita.TreeTemplate(tin.parent, tin.is_mask, tin.n_tree, n)
+        assert (tmpl.rows, tmpl.n_tree, tmpl.n_groups, tmpl.depth, tmpl.kmax) == (d.R, d.T, d.G, d.tree_depth, d.kmax)
+        if d.kmax > 64:          # wider than the library's top-k limit: must be refused, not run
+            from paper_2401_12522_amd.binding import BitaError, build_tree
+            z = torch.zeros((1, d.G * n, d.kmax), dtype=torch.int32, device="cuda")
+            with pytest.raises(BitaError):
+                build_tree(tmpl, z[0, 0, :1], z, None, None, 1, torch.zeros((1, d.R), dtype=torch.int32, device="cuda"))
+            continue
+        B = 3
+        vocab = 5
+        kmax = d.kmax
+        cand = rng.integers(0, vocab, size=(B, d.G * n, kmax)).astype(np.int32)
+        roots = rng.integers(0, vocab, size=B).astype(np.int32)
+        groups = rng.integers(0, d.G, size=B).astype(np.int32)
+        shifts = rng.integers(0, n + 1, size=B).astype(np.int32)
+        dev = lambda a: torch.tensor(a, dtype=torch.int32, device="cuda")   # noqa: E731
+        token = torch.zeros((B, d.R), dtype=torch.int32, device="cuda")
+        from paper_2401_12522_amd import binding as BB
+        BB.build_tree(tmpl, dev(roots), dev(cand), dev(groups), dev(shifts), B, token)
+        greedy = rng.integers(0, vocab, size=(B, d.T)).astype(np.int32)
+
+        class Buf:
+            pass
+        buf = Buf()
+        buf.token, buf.argmax = token, dev(greedy)
+        z = lambda *s: torch.zeros(s, dtype=torch.int32, device="cuda")   # noqa: E731
+        buf.path, buf.emitted = z(B, d.tree_depth + 1), z(B, d.tree_depth + 1)
+        buf.n_acc, buf.bonus, buf.next_group, buf.next_shift = z(B), z(B), z(B), z(B)
+        BB.accept(tmpl, buf, B)
+        torch.cuda.synchronize()
+        for b in range(B):
+            ref_tok = build_tree_tokens(d, roots[b], cand[b], int(groups[b]), int(shifts[b]))
+            assert token[b].cpu().tolist() == ref_tok
+            path, bonus = accept_walk(d, ref_tok, list(greedy[b]))
+            na = int(buf.n_acc[b])
+            assert na == len(path) and buf.path[b, :na].cpu().tolist() == path
+            assert all(x == -1 for x in buf.path[b, na:].cpu().tolist())
+            assert int(buf.bonus[b]) == bonus
+            assert buf.emitted[b, :na].cpu().tolist() == [ref_tok[c] for c in path[1:]] + [bonus]
+            g, s = next_group_and_shift(d, path)
+            assert (int(buf.next_group[b]), int(buf.next_shift[b])) == (g, s)
+
+
+def test_template_errors(bita):
+    from paper_2401_12522_amd.binding import BitaError
+    for parent, is_mask, T, n in [([-1, 1], [0, 0], 2, 1), ([0, 0], [0, 0], 2, 1), ([-1, 0, 0], [0, 1, 0], 2, 1),
+                                  ([-1, 0, 1], [0, 1, 1], 1, 3), ([-1, 0, 0], [0, 1, 1], 1, 1)]:
+        with pytest.raises(BitaError) as e:
+            bita.TreeTemplate(parent, is_mask, T, n)
+        assert e.value.code == -2
