@@ -1,0 +1,296 @@
+#!/usr/bin/env python3
+"""Benchmark of the BiTA tree-verify step on one MI355X.
+
+A "step" is one pass of the whole hot path -- build_tree, verify_step (decoder forward
+over the token tree + mask rows, tree-masked attention, LM head, argmax/top-k), accept,
+compact_kv -- over one batch of synthetic input, replayed from a HIP graph.  Default
+workload: the LLaMA-2-7B-shaped configuration (32 layers, d 4096, 32 heads, FFN 11008,
+vocab 32000, 16 prompt tokens, 1024-token context, 64-node tree + 4 mask rows, batch 1).
+
+Prints ONE JSON line (see the keys below).  `value` is scored rows per second with every
+input resident in HBM; `hbm_gbps` is the algorithmic bytes of a step (weights + K/V cache
++ prompt prefix) divided by the step time.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=128)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--workload", default="7b", choices=["tiny", "7b", "13b", "70b"])
+    ap.add_argument("--ctx", type=int, default=None)
+    ap.add_argument("--mode", default="planted", choices=["free", "planted"])
+    ap.add_argument("--no-graph", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--seed", type=int, default=0)
+    return ap.parse_args()
+
+
+def workload_template(synth, cfg, name):
+    """Draft-tree shape per workload: small case = seeded random 8-node tree; LLaMA shapes =
+    full branching by per-level top-k (4,3,2,1) truncated to 64 rows, one mask group on the root."""
+    if name == "tiny":
+        parent = synth.random_tree(8, 3, 0)
+    else:
+        parent = synth.full_branching_tree([4, 3, 2, 1], 64)
+    return synth.attach_mask_groups(parent, [0], cfg.n_mask)
+
+
+def prefill(B, model, kv, cfg, ctx_tokens, chunk=64):
+    """Fill the cache with context[:-1] by chain-template passes (a chain is causal attention)."""
+    import torch
+    import synth
+    n = len(ctx_tokens) - 1
+    done = 0
+    while done < n:
+        m = min(chunk, n - done)
+        tin = synth.attach_mask_groups(synth.chain_tree(m), [], cfg.n_mask)
+        tmpl = B.TreeTemplate(tin.parent, tin.is_mask, m, cfg.n_mask)
+        kv.resize_rows(model.n_layers, cfg, m)
+        buf = B.StepBuffers(model, tmpl, 1, 1)
+        buf.token[0] = torch.tensor(ctx_tokens[done:done + m], dtype=torch.int32, device="cuda")
+        B.verify_step(model, kv, done, tmpl, buf, 1)
+        path = torch.arange(m, dtype=torch.int32, device="cuda")[None]
+        n_acc = torch.tensor([m], dtype=torch.int32, device="cuda")
+        B.compact_kv(model, kv, done, buf, 1, path=path, n_acc=n_acc)
+        torch.cuda.synchronize()
+        done += m
+
+
+def cpu_baseline(cfg, wsrc_np, kv_np, tmpl_in, tokens, ctx_len):
+    """Time the oracle on a bounded sample: passes with 1 and 2 of the model's layers (+ LM
+    head) at full width, extrapolated linearly to the full depth."""
+    import oracle
+    from oracle.tree import derive_template, ancestors_or_self
+
+    class Src:
+        def get(self, name, layer=None):
+            return wsrc_np[(name, layer)]
+    om = oracle.OracleModel(cfg, Src(), cache_layers=False)
+    d = derive_template(tmpl_in.parent, tmpl_in.is_mask, tmpl_in.n_mask)
+    pos = [ctx_len + d.depth[r] for r in range(d.R)]
+    vis = [ancestors_or_self(d.parent, r) for r in range(d.R)]
+    ts = []
+    for nl in (1, 2):
+        t0 = time.perf_counter()
+        oracle.forward_rows(om, tokens, d.is_mask, d.mask_index, pos, vis, kv_np[0], kv_np[1], n_layers=nl)
+        ts.append(time.perf_counter() - t0)
+    layer = max(ts[1] - ts[0], 1e-9)
+    head = max(ts[0] - layer, 0.0)
+    full = head + cfg.n_layers * layer
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    return dict(value=d.R / full, unit="tokens/s", cores=int(threads), kind="oracle",
+                ms_per_step=full * 1e3,
+                sample=f"oracle forward of 1 and 2 of {cfg.n_layers} layers + LM head at full width "
+                       f"({ts[0]:.1f}s + {ts[1]:.1f}s), extrapolated linearly to {cfg.n_layers} layers")
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import synth
+    import paper_2401_12522_amd as bita
+    from paper_2401_12522_amd import binding as B
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    bita.lib()
+    cfg = synth.get_config(args.workload)
+    ctx_n = args.ctx or {"tiny": 64, "7b": 1024, "13b": 2048, "70b": 2048}[args.workload]
+    tin = workload_template(synth, cfg, args.workload)
+    steps, warmup = args.steps, args.warmup
+    R = tin.rows
+    depth_max = 4 if args.workload != "tiny" else 3
+    total_steps = warmup + steps
+    smax = ctx_n + (total_steps + 2) * (depth_max + 1) + 64
+    smax = (smax + 63) // 64 * 64
+
+    # ---- model: weights drawn on the GPU, packed layer by layer ----------------------------
+    w = synth.SynthWeights(cfg, seed=args.seed, device="cuda")
+    keep_layers = (0, 1)
+    wsrc_np = {}
+    if not args.no_cpu_baseline:
+        for l in keep_layers:
+            for n in ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down", "attn_norm", "ffn_norm",
+                      "prompt_k", "prompt_v"):
+                wsrc_np[(n, l)] = w.numpy(n, l)
+        for n in ("tok_emb", "mask_emb", "lm_head", "final_norm"):
+            wsrc_np[(n, None)] = w.numpy(n)
+    model = bita.Model(cfg, w, max_pos=smax + 64, free_source=True)
+    tmpl = bita.TreeTemplate(tin.parent, tin.is_mask, tin.n_tree, cfg.n_mask)
+    kv = bita.KVState(cfg, cfg.n_layers, 1, smax, R)
+    ctx_tokens = synth.random_context(cfg.vocab, ctx_n, args.seed)
+    prefill(B, model, kv, cfg, ctx_tokens)
+    kv.resize_rows(cfg.n_layers, cfg, R)
+    ctx0 = int(kv.ctx_len[0])
+    assert ctx0 == ctx_n - 1
+    k_snap, v_snap = kv.k_cache.clone(), kv.v_cache.clone()
+
+    kmax = tmpl.kmax
+    buf = bita.StepBuffers(model, tmpl, 1, kmax)
+    hint = ctx0 + (total_steps + 1) * (depth_max + 1)
+
+    def reset_state():
+        kv.k_cache.copy_(k_snap)
+        kv.v_cache.copy_(v_snap)
+        kv.ctx_len[0] = ctx0
+        buf.bonus[0] = int(ctx_tokens[-1])
+        buf.next_group[0] = 0
+        buf.next_shift[0] = cfg.n_mask          # first pass: no candidates, all drafts inactive
+        buf.topk_ids.zero_()
+
+    # ---- reference stream for planted drafts: free-running greedy decode on the device ------
+    n_stream = total_steps * (depth_max + 1) + 2
+    stream = []
+    if args.mode == "planted":
+        reset_state()
+        t1 = synth.attach_mask_groups(np.array([-1], np.int32), [], cfg.n_mask)
+        tm1 = B.TreeTemplate(t1.parent, t1.is_mask, 1, cfg.n_mask)
+        kv.resize_rows(cfg.n_layers, cfg, 1)
+        b1 = B.StepBuffers(model, tm1, 1, 1)
+        b1.bonus[0] = int(ctx_tokens[-1])
+        hint1 = ctx0 + n_stream + 1
+        if hint1 + 8 > smax:
+            raise SystemExit("internal: smax too small for the reference stream")
+        g1 = torch.cuda.CUDAGraph()
+        B.decode_step(model, kv, hint1, tm1, b1, 1, b1.bonus, None)
+        torch.cuda.synchronize()
+        out_toks = torch.zeros(n_stream, dtype=torch.int32, device="cuda")
+        st = torch.cuda.Stream()
+        with torch.cuda.stream(st):
+            with torch.cuda.graph(g1, stream=st):
+                B.decode_step(model, kv, hint1, tm1, b1, 1, b1.bonus, None)
+        kv.k_cache.copy_(k_snap); kv.v_cache.copy_(v_snap); kv.ctx_len[0] = ctx0
+        b1.bonus[0] = int(ctx_tokens[-1])
+        for i in range(n_stream):
+            g1.replay()
+            out_toks[i:i + 1].copy_(b1.bonus)
+        torch.cuda.synchronize()
+        stream = out_toks.cpu().tolist()
+        kv.resize_rows(cfg.n_layers, cfg, R)
+
+    # planted candidate tables for every step (acceptance lengths follow from the plan)
+    cand_all = None
+    plan_acc = []
+    if args.mode == "planted":
+        ks = [4, 3, 2, 1] if args.workload != "tiny" else [1, 1, 1, 1]
+        pos = 0
+        tabs = []
+        for t in range(total_steps):
+            rng = np.random.default_rng(1000 + t)
+            depth_ok = int(rng.integers(0, depth_max + 1))
+            col = np.array([int(rng.integers(0, ks[i])) for i in range(cfg.n_mask)])
+            # the 64-row truncation drops the last level-4 node: keep planted paths inside the tree
+            col[3] = 0
+            tabs.append(synth.planted_candidates(stream[pos:], cfg.n_mask, kmax, depth_ok, col, cfg.vocab, 50 + t))
+            plan_acc.append(1 + depth_ok)
+            pos += 1 + depth_ok
+        cand_all = torch.tensor(np.stack(tabs)[:, None], dtype=torch.int32, device="cuda")  # [steps][1][n][kmax]
+    cand_buf = torch.zeros((1, cfg.n_mask, kmax), dtype=torch.int32, device="cuda")
+
+    def one_step():
+        if args.mode == "planted":
+            B.decode_step(model, kv, hint, tmpl, buf, 1, buf.bonus, cand_buf)
+        else:
+            B.decode_step(model, kv, hint, tmpl, buf, 1, buf.bonus, buf.topk_ids, buf.next_group, buf.next_shift)
+
+    reset_state()
+    one_step()                                   # eager once (sets kernel attributes)
+    torch.cuda.synchronize()
+    graph = None
+    if not args.no_graph:
+        graph = torch.cuda.CUDAGraph()
+        st = torch.cuda.Stream()
+        with torch.cuda.stream(st):
+            with torch.cuda.graph(graph, stream=st):
+                one_step()
+        torch.cuda.synchronize()
+    reset_state()
+
+    emitted_log = torch.zeros((total_steps, depth_max + 1), dtype=torch.int32, device="cuda")
+    nacc_log = torch.zeros(total_steps, dtype=torch.int32, device="cuda")
+
+    def run(t):
+        if args.mode == "planted":
+            cand_buf.copy_(cand_all[t])
+        if graph is not None:
+            graph.replay()
+        else:
+            one_step()
+        emitted_log[t].copy_(buf.emitted[0])
+        nacc_log[t:t + 1].copy_(buf.n_acc)
+
+    for t in range(warmup):
+        run(t)
+    torch.cuda.synchronize()
+    ctx_start = int(kv.ctx_len[0])
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for t in range(warmup, total_steps):
+        run(t)
+    e1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    gpu_ms = e0.elapsed_time(e1)
+    ms_per_step = wall * 1e3 / steps
+
+    nacc = nacc_log.cpu().numpy()
+    em = emitted_log.cpu().numpy()
+    got = [int(x) for t in range(total_steps) for x in em[t, : nacc[t]]]
+    stream_ok = None
+    if args.mode == "planted":
+        stream_ok = got == stream[: len(got)]
+        if args.workload != "tiny":
+            stream_ok = stream_ok and [int(x) for x in nacc] == plan_acc
+    ctx_lens = ctx_start + np.concatenate([[0], np.cumsum(nacc[warmup:])[:-1]])
+    bytes_per_step = cfg.weight_bytes() + float(np.mean([cfg.kv_bytes([int(c)]) for c in ctx_lens]))
+    gbps = bytes_per_step / (ms_per_step * 1e-3) / 1e9
+
+    out = {
+        "metric": "tree_verify_scored_tokens_per_s", "value": R * steps / wall, "unit": "tokens/s",
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"llama2-{args.workload}-shaped random-init, ctx {ctx_n}, batch 1, "
+                               f"{tin.n_tree}-node tree + {cfg.n_mask} mask rows, P={cfg.n_prompt}, mode {args.mode}",
+                   "rows": R, "graph": graph is not None},
+        "hbm_gbps": gbps, "hbm_frac_of_peak": gbps / HBM_PEAK_GBPS, "bytes_per_step": bytes_per_step,
+        "gpu_ms_per_step": gpu_ms / steps, "mean_accepted": float(np.mean(nacc[warmup:])),
+        "generated_tokens_per_s": float(np.sum(nacc[warmup:])) / wall,
+        "stream_matches_ar_greedy": stream_ok,
+        "roofline": None, "cpu_baseline": None,
+    }
+
+    if not args.no_cpu_baseline:
+        kv_np = ([k_snap[l, 0, :, :ctx0].permute(1, 0, 2).float().cpu().numpy() for l in keep_layers],
+                 [v_snap[l, 0, :, :ctx0].permute(1, 0, 2).float().cpu().numpy() for l in keep_layers])
+        tokens = [int(ctx_tokens[-1])] + [int(x) for x in np.random.default_rng(3).integers(0, cfg.vocab, tin.n_tree - 1)] \
+            + list(range(cfg.n_mask))
+        out["cpu_baseline"] = cpu_baseline(cfg, wsrc_np, kv_np, tin, tokens, ctx0)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -106,15 +106,16 @@ typedef struct bita_tree_template bita_tree_template; /* opaque */
  * bita_pack_weight; N multiple of 16, K multiple of 8). */
 size_t bita_packed_bytes(int64_t n_rows, int64_t k);
 
-/* Re-lay rows of a row-major bf16 matrix d_src[N][K] (y = x W^T convention) into
- * the streaming order of the skinny-GEMM kernel: the destination is a sequence
- * of 16-row tiles, each holding its K range (zero-padded to a multiple of 32) as
- * 1 KiB blocks in MFMA operand order.  Source tile j is written to destination
- * tile dst_tile0 + j*dst_tile_stride, which lets several matrices share one
- * packed buffer (QKV concatenation, gate/up interleave).  A pure permutation of
- * bits.  d_dst must hold bita_packed_bytes(total rows, K). */
+/* Re-lay rows of a row-major bf16 matrix d_src[N][K] (y = x W^T convention) into the
+ * streaming order of the skinny-GEMM kernel.  The packed matrix of dst_total_rows rows
+ * is a sequence of 1 KiB blocks, each one MFMA operand (16 rows x 32 k), ordered
+ * [pair of k-steps][16-row tile][k-step of the pair], K zero-padded to a multiple of 64.
+ * Source tile j is written to destination tile dst_tile0 + j*dst_tile_stride, which lets
+ * several matrices share one packed buffer (QKV concatenation, gate/up interleave).  A
+ * pure permutation of bits.  d_dst must hold bita_packed_bytes(dst_total_rows, K). */
 int bita_pack_weight(const void *d_src, int64_t n_rows, int64_t k, void *d_dst,
-                     int64_t dst_tile0, int64_t dst_tile_stride, void *stream);
+                     int64_t dst_total_rows, int64_t dst_tile0, int64_t dst_tile_stride,
+                     void *stream);
 
 /* Create a model handle: copies the pointer table and builds the rotary
  * cos/sin table (allocates device memory once; freed by bita_model_destroy). */
@@ -191,12 +192,13 @@ int bita_compact_kv(const bita_model *m, const bita_kv *kv, const int32_t *d_pat
                     int32_t batch, void *stream);
 
 /* Tree-masked attention alone (the kernel bita_verify_step runs per layer), for
- * kernel-level tests and measurement.  d_q [B][R][n_heads][hd] (already rotated),
+ * kernel-level tests and measurement.  d_q [B][R][n_heads][hd] (already rotated; d_q_lo
+ * is an optional second bf16 plane of the same shape with the rounding residual),
  * K/V arguments are one layer's slices laid out as in bita_kv; d_out
  * [B][R][n_heads*hd] bf16.  d_ws needs bita_attention_workspace_bytes(). */
 size_t bita_attention_workspace_bytes(int32_t batch, int32_t rows, int32_t n_heads,
                                       int32_t head_dim, int32_t ctx_hint, int32_t n_prompt);
-int bita_tree_attention(const bita_tree_template *t, const void *d_q,
+int bita_tree_attention(const bita_tree_template *t, const void *d_q, const void *d_q_lo,
                         const void *d_k_cache, const void *d_v_cache,
                         const void *d_k_tree, const void *d_v_tree,
                         const void *d_prompt_k, const void *d_prompt_v,
@@ -204,11 +206,19 @@ int bita_tree_attention(const bita_tree_template *t, const void *d_q,
                         int32_t n_kv_heads, int32_t head_dim, int32_t n_prompt, int32_t smax,
                         int32_t ctx_hint, void *d_ws, size_t ws_bytes, void *d_out, void *stream);
 
-/* Skinny GEMM alone: d_out[M][N] (fp32) = d_a[M][K] (bf16, row stride lda) times the
- * packed [N][K] matrix transposed.  d_ws needs bita_gemm_workspace_bytes(). */
+/* Skinny GEMM alone: d_out[M][N] (fp32) = A[M][K] times the packed [N][K] matrix
+ * transposed.  A = d_a (bf16, row stride lda) plus, if d_a_lo is not NULL, a second bf16
+ * plane of the same shape holding the rounding residual (A = hi + lo), which is how
+ * bita_verify_step feeds its activations.  d_ws needs bita_gemm_workspace_bytes(). */
 size_t bita_gemm_workspace_bytes(int32_t m_rows, int64_t n_rows);
-int bita_gemm(const void *d_a, int32_t m_rows, int64_t k, int64_t lda, const void *d_w_packed,
-              int64_t n_rows, void *d_ws, size_t ws_bytes, float *d_out, void *stream);
+int bita_gemm(const void *d_a, const void *d_a_lo, int32_t m_rows, int64_t k, int64_t lda,
+              const void *d_w_packed, int64_t n_rows, void *d_ws, size_t ws_bytes, float *d_out,
+              void *stream);
+
+/* Tuning aid: override the GEMM launch heuristic for all later launches of this process
+ * (variant = workgroup shape index, splits = split-K factor; a negative value restores the
+ * heuristic for that knob).  Not thread-safe; results are unchanged, only speed. */
+void bita_tune_gemm(int32_t variant, int32_t splits);
 
 const char *bita_last_error(void);
 

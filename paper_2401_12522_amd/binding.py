@@ -16,7 +16,7 @@ EXPORTS = [
     "bita_workspace_bytes", "bita_tree_template_create", "bita_tree_template_destroy",
     "bita_tree_template_info", "bita_build_tree", "bita_verify_step", "bita_accept",
     "bita_compact_kv", "bita_attention_workspace_bytes", "bita_tree_attention",
-    "bita_gemm_workspace_bytes", "bita_gemm", "bita_last_error",
+    "bita_gemm_workspace_bytes", "bita_gemm", "bita_tune_gemm", "bita_last_error",
 ]
 
 
@@ -54,7 +54,7 @@ def lib():
     L = C.CDLL(_LIB_PATH)
     vp, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
     L.bita_packed_bytes.restype, L.bita_packed_bytes.argtypes = sz, [i64, i64]
-    L.bita_pack_weight.restype, L.bita_pack_weight.argtypes = C.c_int, [vp, i64, i64, vp, i64, i64, vp]
+    L.bita_pack_weight.restype, L.bita_pack_weight.argtypes = C.c_int, [vp, i64, i64, vp, i64, i64, i64, vp]
     L.bita_model_create.restype = C.c_int
     L.bita_model_create.argtypes = [C.POINTER(_Config), C.POINTER(_Weights), C.POINTER(vp)]
     L.bita_model_destroy.restype, L.bita_model_destroy.argtypes = None, [vp]
@@ -74,9 +74,10 @@ def lib():
     L.bita_attention_workspace_bytes.restype = sz
     L.bita_attention_workspace_bytes.argtypes = [i32] * 6
     L.bita_tree_attention.restype = C.c_int
-    L.bita_tree_attention.argtypes = [vp] * 9 + [i32] * 7 + [vp, sz, vp, vp]
+    L.bita_tree_attention.argtypes = [vp] * 10 + [i32] * 7 + [vp, sz, vp, vp]
     L.bita_gemm_workspace_bytes.restype, L.bita_gemm_workspace_bytes.argtypes = sz, [i32, i64]
-    L.bita_gemm.restype, L.bita_gemm.argtypes = C.c_int, [vp, i32, i64, i64, vp, i64, vp, sz, vp, vp]
+    L.bita_gemm.restype, L.bita_gemm.argtypes = C.c_int, [vp, vp, i32, i64, i64, vp, i64, vp, sz, vp, vp]
+    L.bita_tune_gemm.restype, L.bita_tune_gemm.argtypes = None, [i32, i32]
     L.bita_last_error.restype, L.bita_last_error.argtypes = C.c_char_p, []
     _lib = L
     return L
@@ -104,9 +105,10 @@ def pack_weight(src, dst=None, tile0=0, tile_stride=1, total_rows=None):
     when dst is None, sized for total_rows rows)."""
     n, k = src.shape
     assert src.dtype == torch.bfloat16 and src.is_cuda and src.is_contiguous()
+    total_rows = total_rows or n
     if dst is None:
-        dst = torch.empty(packed_bytes(total_rows or n, k), dtype=torch.uint8, device=src.device)
-    _check(lib().bita_pack_weight(_ptr(src), n, k, _ptr(dst), tile0, tile_stride, _stream()))
+        dst = torch.empty(packed_bytes(total_rows, k), dtype=torch.uint8, device=src.device)
+    _check(lib().bita_pack_weight(_ptr(src), n, k, _ptr(dst), total_rows, tile0, tile_stride, _stream()))
     return dst
 
 
@@ -146,11 +148,11 @@ class Model:
             dst = torch.empty(packed_bytes(total, k), dtype=torch.uint8, device=dev)
             if interleave:
                 for i, p in enumerate(parts):
-                    pack_weight(p.contiguous(), dst, i, len(parts))
+                    pack_weight(p.contiguous(), dst, i, len(parts), total_rows=total)
             else:
                 row = 0
                 for p in parts:
-                    pack_weight(p.contiguous(), dst, row // 16, 1)
+                    pack_weight(p.contiguous(), dst, row // 16, 1, total_rows=total)
                     row += p.shape[0]
             keep.append(dst)
             return dst
@@ -289,17 +291,17 @@ def decode_step(model, kv, ctx_hint, tmpl, buf, batch, root_token, cand, group=N
     compact_kv(model, kv, ctx_hint, buf, batch)
 
 
-def gemm(a, w_packed, n_rows, k=None):
-    """a: bf16 cuda [M][lda]; returns fp32 [M][n_rows]."""
+def gemm(a, w_packed, n_rows, k=None, a_lo=None):
+    """a (and optionally a_lo, the residual plane): bf16 cuda [M][lda]; returns fp32 [M][n_rows]."""
     m, lda = a.shape
     k = lda if k is None else k
     ws = torch.empty(lib().bita_gemm_workspace_bytes(m, n_rows), dtype=torch.uint8, device=a.device)
     out = torch.empty((m, n_rows), dtype=torch.float32, device=a.device)
-    _check(lib().bita_gemm(_ptr(a), m, k, lda, _ptr(w_packed), n_rows, _ptr(ws), ws.numel(), _ptr(out), _stream()))
+    _check(lib().bita_gemm(_ptr(a), _ptr(a_lo), m, k, lda, _ptr(w_packed), n_rows, _ptr(ws), ws.numel(), _ptr(out), _stream()))
     return out
 
 
-def tree_attention(tmpl, q, k_cache, v_cache, k_tree, v_tree, prompt_k, prompt_v, ctx_len, ctx_hint):
+def tree_attention(tmpl, q, k_cache, v_cache, k_tree, v_tree, prompt_k, prompt_v, ctx_len, ctx_hint, q_lo=None):
     """q [B][R][Hq][hd]; k/v_cache [B][Hkv][smax][hd]; k/v_tree [B][Hkv][R][hd];
     prompt_k/v [Hkv][P][hd] or None.  Returns bf16 [B][R][Hq*hd]."""
     B, R, Hq, hd = q.shape
@@ -307,7 +309,7 @@ def tree_attention(tmpl, q, k_cache, v_cache, k_tree, v_tree, prompt_k, prompt_v
     P = 0 if prompt_k is None else prompt_k.shape[1]
     ws = torch.empty(lib().bita_attention_workspace_bytes(B, R, Hq, hd, int(ctx_hint), P), dtype=torch.uint8, device=q.device)
     out = torch.empty((B, R, Hq * hd), dtype=torch.bfloat16, device=q.device)
-    _check(lib().bita_tree_attention(tmpl.handle, _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(k_tree), _ptr(v_tree),
+    _check(lib().bita_tree_attention(tmpl.handle, _ptr(q), _ptr(q_lo), _ptr(k_cache), _ptr(v_cache), _ptr(k_tree), _ptr(v_tree),
                                      _ptr(prompt_k), _ptr(prompt_v), _ptr(ctx_len), B, Hq, Hkv, hd, P, smax,
                                      int(ctx_hint), _ptr(ws), ws.numel(), _ptr(out), _stream()))
     return out

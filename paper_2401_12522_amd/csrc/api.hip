@@ -29,16 +29,20 @@ struct bita_model {
 
 extern "C" size_t bita_packed_bytes(int64_t n_rows, int64_t k) {
     if (n_rows <= 0 || k <= 0) return 0;
-    return (size_t)((n_rows + 15) / 16) * (size_t)((k + 31) / 32) * 1024;
+    return (size_t)((n_rows + 15) / 16) * (size_t)((k + 63) / 64) * 2048;
 }
 
 extern "C" int bita_pack_weight(const void *d_src, int64_t n_rows, int64_t k, void *d_dst,
-                                int64_t dst_tile0, int64_t dst_tile_stride, void *stream) {
+                                int64_t dst_total_rows, int64_t dst_tile0, int64_t dst_tile_stride,
+                                void *stream) {
     if (!d_src || !d_dst || n_rows <= 0 || k <= 0 || dst_tile0 < 0 || dst_tile_stride < 1)
         return bita_set_error(BITA_ERR_INVALID_ARG, "bita_pack_weight: bad argument");
-    if (n_rows % 16 || k % 8)
+    if (n_rows % 16 || k % 8 || dst_total_rows % 16)
         return bita_set_error(BITA_ERR_UNSUPPORTED, "bita_pack_weight: rows must be a multiple of 16 and k of 8");
-    launch_pack(d_src, n_rows, k, d_dst, dst_tile0, dst_tile_stride, (hipStream_t)stream);
+    if (dst_tile0 + (n_rows / 16 - 1) * dst_tile_stride >= dst_total_rows / 16)
+        return bita_set_error(BITA_ERR_INVALID_ARG, "bita_pack_weight: source tiles do not fit %lld destination rows",
+                              (long long)dst_total_rows);
+    launch_pack(d_src, n_rows, k, d_dst, dst_tile0, dst_tile_stride, dst_total_rows / 16, (hipStream_t)stream);
     BITA_HIP_CHECK(hipGetLastError());
     return BITA_OK;
 }
@@ -214,10 +218,11 @@ static WsLayout ws_layout(const bita_config &c, int batch, int rows) {
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
     L.x = take(M * c.d_model * 4);
-    L.h = take(M * c.d_model * 2);
-    L.q = take(M * nq * 2);
-    L.attn_out = take(M * nq * 2);
-    L.act = take(M * c.d_ffn * 2);
+    // bf16 activations are kept as two planes (hi, lo): [2][M][width]
+    L.h = take(2 * M * c.d_model * 2);
+    L.q = take(2 * M * nq * 2);
+    L.attn_out = take(2 * M * nq * 2);
+    L.act = take(2 * M * c.d_ffn * 2);
     size_t pb = 0;
     const int64_t shapes[5][2] = {{nqkv, c.d_model}, {c.d_model, nq}, {2 * (int64_t)c.d_ffn, c.d_model},
                                   {c.d_model, c.d_ffn}, {c.vocab, c.d_model}};
@@ -270,11 +275,13 @@ extern "C" int bita_verify_step(bita_model *m, const bita_kv *kv, const bita_tre
     hipStream_t s = (hipStream_t)stream;
     unsigned char *ws = (unsigned char *)d_workspace;
     float *x = (float *)(ws + L.x), *partial = (float *)(ws + L.partial);
-    void *h = ws + L.h, *q = ws + L.q, *attn_out = ws + L.attn_out, *act = ws + L.act;
+    unsigned char *h = ws + L.h, *q = ws + L.q, *attn_out = ws + L.attn_out, *act = ws + L.act;
     float *part_o = (float *)(ws + L.part_o), *part_ml = (float *)(ws + L.part_ml);
     float *logits = d_logits ? d_logits : (float *)(ws + L.logits);
     const int M = batch * td.rows, d = c.d_model, hd = c.head_dim;
     const int64_t nq = (int64_t)c.n_heads * hd, nqkv = (int64_t)(c.n_heads + 2 * c.n_kv_heads) * hd;
+    unsigned char *h_lo = h + (size_t)M * d * 2, *q_lo = q + (size_t)M * nq * 2;
+    unsigned char *attn_lo = attn_out + (size_t)M * nq * 2, *act_lo = act + (size_t)M * c.d_ffn * 2;
     const GemmPlan p_qkv = gemm_plan(M, nqkv, d), p_o = gemm_plan(M, d, nq),
                    p_gu = gemm_plan(M, 2 * (int64_t)c.d_ffn, d), p_dn = gemm_plan(M, d, c.d_ffn),
                    p_lm = gemm_plan(M, c.vocab, d);
@@ -286,27 +293,27 @@ extern "C" int bita_verify_step(bita_model *m, const bita_kv *kv, const bita_tre
     launch_embed(d_token, td, batch, m->tok_emb, m->mask_emb, d, c.vocab, x, s);
     int pending = 0;                                    // split-K partials waiting to be added to x
     for (int l = 0; l < c.n_layers; l++) {
-        launch_rmsnorm(x, partial, pending, M, d, m->attn_norm[l], c.rms_eps, h, d, s);
-        launch_gemm(h, M, d, d, m->wqkv[l], nqkv, partial, nqkv, p_qkv, s);
+        launch_rmsnorm(x, partial, pending, M, d, m->attn_norm[l], c.rms_eps, h, h_lo, d, s);
+        launch_gemm(h, h_lo, M, d, d, m->wqkv[l], nqkv, partial, nqkv, p_qkv, s);
         void *kt = (unsigned char *)kv->k_tree + l * kv_layer_tree, *vt = (unsigned char *)kv->v_tree + l * kv_layer_tree;
         launch_qkv_rope(partial, p_qkv.splits, batch, td, c.n_heads, c.n_kv_heads, hd, d_ctx_len, m->rope_cos,
-                        m->rope_sin, c.max_pos, q, kt, vt, s);
-        launch_tree_attention(td, q, (unsigned char *)kv->k_cache + l * kv_layer_cache,
+                        m->rope_sin, c.max_pos, q, q_lo, kt, vt, s);
+        launch_tree_attention(td, q, q_lo, (unsigned char *)kv->k_cache + l * kv_layer_cache,
                               (unsigned char *)kv->v_cache + l * kv_layer_cache, kt, vt, m->prompt_k[l],
                               m->prompt_v[l], d_ctx_len, batch, c.n_heads, c.n_kv_heads, hd, c.n_prompt, kv->smax,
-                              ap, part_o, part_ml, attn_out, s);
-        launch_gemm(attn_out, M, nq, nq, m->wo[l], d, partial, d, p_o, s);
-        launch_rmsnorm(x, partial, p_o.splits, M, d, m->ffn_norm[l], c.rms_eps, h, d, s);
-        launch_gemm(h, M, d, d, m->w_gate_up[l], 2 * (int64_t)c.d_ffn, partial, 2 * (int64_t)c.d_ffn, p_gu, s);
-        launch_silu_mul(partial, p_gu.splits, M, c.d_ffn, act, c.d_ffn, s);
-        launch_gemm(act, M, c.d_ffn, c.d_ffn, m->w_down[l], d, partial, d, p_dn, s);
+                              ap, part_o, part_ml, attn_out, attn_lo, s);
+        launch_gemm(attn_out, attn_lo, M, nq, nq, m->wo[l], d, partial, d, p_o, s);
+        launch_rmsnorm(x, partial, p_o.splits, M, d, m->ffn_norm[l], c.rms_eps, h, h_lo, d, s);
+        launch_gemm(h, h_lo, M, d, d, m->w_gate_up[l], 2 * (int64_t)c.d_ffn, partial, 2 * (int64_t)c.d_ffn, p_gu, s);
+        launch_silu_mul(partial, p_gu.splits, M, c.d_ffn, act, act_lo, c.d_ffn, s);
+        launch_gemm(act, act_lo, M, c.d_ffn, c.d_ffn, m->w_down[l], d, partial, d, p_dn, s);
         pending = p_dn.splits;
     }
-    launch_rmsnorm(x, partial, pending, M, d, m->final_norm, c.rms_eps, h, d, s);
+    launch_rmsnorm(x, partial, pending, M, d, m->final_norm, c.rms_eps, h, h_lo, d, s);
     if (p_lm.splits == 1) {
-        launch_gemm(h, M, d, d, m->lm_head, c.vocab, logits, c.vocab, p_lm, s);
+        launch_gemm(h, h_lo, M, d, d, m->lm_head, c.vocab, logits, c.vocab, p_lm, s);
     } else {
-        launch_gemm(h, M, d, d, m->lm_head, c.vocab, partial, c.vocab, p_lm, s);
+        launch_gemm(h, h_lo, M, d, d, m->lm_head, c.vocab, partial, c.vocab, p_lm, s);
         launch_reduce_partials(partial, p_lm.splits, M, c.vocab, c.vocab, logits, s);
     }
     launch_select(logits, batch, td, c.vocab, kmax, d_argmax, n_sel_mask > 0 ? d_topk_ids : nullptr, d_topk_val, s);
@@ -342,7 +349,8 @@ extern "C" size_t bita_attention_workspace_bytes(int32_t batch, int32_t rows, in
     return align_up(p.part_o_bytes, 256) + align_up(p.part_ml_bytes, 256);
 }
 
-extern "C" int bita_tree_attention(const bita_tree_template *t, const void *d_q, const void *d_k_cache,
+extern "C" int bita_tree_attention(const bita_tree_template *t, const void *d_q, const void *d_q_lo,
+                                   const void *d_k_cache,
                                    const void *d_v_cache, const void *d_k_tree, const void *d_v_tree,
                                    const void *d_prompt_k, const void *d_prompt_v, const int32_t *d_ctx_len,
                                    int32_t batch, int32_t n_heads, int32_t n_kv_heads, int32_t head_dim,
@@ -360,20 +368,23 @@ extern "C" int bita_tree_attention(const bita_tree_template *t, const void *d_q,
     const size_t need = align_up(p.part_o_bytes, 256) + align_up(p.part_ml_bytes, 256);
     if (ws_bytes < need) return bita_set_error(BITA_ERR_CAPACITY, "bita_tree_attention: workspace %zu < %zu", ws_bytes, need);
     float *part_o = (float *)d_ws, *part_ml = (float *)((unsigned char *)d_ws + align_up(p.part_o_bytes, 256));
-    launch_tree_attention(t->dev, d_q, d_k_cache, d_v_cache, d_k_tree, d_v_tree, d_prompt_k, d_prompt_v, d_ctx_len,
+    launch_tree_attention(t->dev, d_q, d_q_lo, d_k_cache, d_v_cache, d_k_tree, d_v_tree, d_prompt_k, d_prompt_v, d_ctx_len,
                           batch, n_heads, n_kv_heads, head_dim, n_prompt, smax, p, part_o, part_ml, d_out,
-                          (hipStream_t)stream);
+                          nullptr, (hipStream_t)stream);
     BITA_HIP_CHECK(hipGetLastError());
     return BITA_OK;
 }
+
+extern "C" void bita_tune_gemm(int32_t variant, int32_t splits) { gemm_force_plan(variant, splits); }
 
 extern "C" size_t bita_gemm_workspace_bytes(int32_t m_rows, int64_t n_rows) {
     if (m_rows <= 0 || n_rows <= 0) return 0;
     return (size_t)16 * m_rows * n_rows * 4;              // split-K never exceeds 16
 }
 
-extern "C" int bita_gemm(const void *d_a, int32_t m_rows, int64_t k, int64_t lda, const void *d_w_packed,
-                         int64_t n_rows, void *d_ws, size_t ws_bytes, float *d_out, void *stream) {
+extern "C" int bita_gemm(const void *d_a, const void *d_a_lo, int32_t m_rows, int64_t k, int64_t lda,
+                         const void *d_w_packed, int64_t n_rows, void *d_ws, size_t ws_bytes, float *d_out,
+                         void *stream) {
     if (!d_a || !d_w_packed || !d_ws || !d_out || m_rows <= 0 || k <= 0 || n_rows <= 0 || lda < k)
         return bita_set_error(BITA_ERR_INVALID_ARG, "bita_gemm: bad argument");
     if (n_rows % 16 || k % 8 || lda % 8)
@@ -383,9 +394,9 @@ extern "C" int bita_gemm(const void *d_a, int32_t m_rows, int64_t k, int64_t lda
         return bita_set_error(BITA_ERR_CAPACITY, "bita_gemm: workspace too small");
     hipStream_t s = (hipStream_t)stream;
     if (p.splits == 1) {
-        launch_gemm(d_a, m_rows, k, lda, d_w_packed, n_rows, d_out, n_rows, p, s);
+        launch_gemm(d_a, d_a_lo, m_rows, k, lda, d_w_packed, n_rows, d_out, n_rows, p, s);
     } else {
-        launch_gemm(d_a, m_rows, k, lda, d_w_packed, n_rows, (float *)d_ws, n_rows, p, s);
+        launch_gemm(d_a, d_a_lo, m_rows, k, lda, d_w_packed, n_rows, (float *)d_ws, n_rows, p, s);
         launch_reduce_partials((const float *)d_ws, p.splits, m_rows, n_rows, n_rows, d_out, s);
     }
     BITA_HIP_CHECK(hipGetLastError());

@@ -28,16 +28,23 @@ struct AttSmem {
     static constexpr int TILE_BYTES = K_BYTES + V_BYTES;
 };
 
+// LDS map: [K tile | V^T tile] (reused by the final merge) followed by the query fragments
+// (two bf16 planes, MFMA operand order).
 template <int HD, int MT>
-constexpr int att_smem_bytes() {
+constexpr int att_tile_region() {
     const int tile = AttSmem<HD>::TILE_BYTES;
     const int merge = MT * 16 * (HD + 4) * 4 + 2 * ATT_WAVES * MT * 16 * 4;
     return tile > merge ? tile : merge;
 }
+template <int HD, int MT>
+constexpr int att_smem_bytes() {
+    return att_tile_region<HD, MT>() + 2 * MT * (HD / 32) * 1024;
+}
 
 template <int HD, int MT>
 __global__ __launch_bounds__(ATT_WAVES * 64) void tree_attn_kernel(
-    TemplateDev t, const uint16_t *__restrict__ q, const uint16_t *__restrict__ k_cache,
+    TemplateDev t, const uint16_t *__restrict__ q, const uint16_t *__restrict__ q_lo,
+    const uint16_t *__restrict__ k_cache,
     const uint16_t *__restrict__ v_cache, const uint16_t *__restrict__ k_tree,
     const uint16_t *__restrict__ v_tree, const uint16_t *__restrict__ prompt_k,
     const uint16_t *__restrict__ prompt_v, const int32_t *__restrict__ ctx_len, int Hq, int Hkv,
@@ -51,6 +58,7 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void tree_attn_kernel(
     constexpr int V_IT = ATT_TK / 2 * GPK / 256;   // V key-pair granules per thread per tile
     constexpr int KSTR = AttSmem<HD>::K_STRIDE * 2, VSTR = AttSmem<HD>::V_STRIDE * 2;   // bytes
     unsigned char *ks_lds = smem, *vt_lds = smem + AttSmem<HD>::K_BYTES;
+    uint4 *q_lds = reinterpret_cast<uint4 *>(smem + att_tile_region<HD, MT>());   // [2][MT][KSN][64]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 4, c = lane & 15;
     const int split = blockIdx.x, h = blockIdx.y / n_qblk, qblk = blockIdx.y % n_qblk, b = blockIdx.z;
@@ -69,21 +77,24 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void tree_attn_kernel(
     const uint16_t *tk = k_tree + ((int64_t)b * Hkv + kvh) * R * HD;
     const uint16_t *tv = v_tree + ((int64_t)b * Hkv + kvh) * R * HD;
 
-    // Q fragments (B operand of S^T = K Q^T): lane holds Q[row0 + 16mt + c][32ks + 8g .. +8]
-    bf16x8 qf[MT][KSN];
+    // Query fragments (B operand of S^T = K Q^T) go to LDS once, as two bf16 planes (value and
+    // rounding residual): fragment (plane, mt, ks) holds, for lane (g, c),
+    // Q[row0 + 16mt + c][32ks + 8g .. +8].  Rows beyond R are zero.
     bool row_ok[MT], row_mask[MT];
 #pragma unroll
     for (int mt = 0; mt < MT; mt++) {
         const int r = row0 + mt * 16 + c;
         row_ok[mt] = r < R;
         row_mask[mt] = row_ok[mt] && t.is_mask[r];
-#pragma unroll
-        for (int ks = 0; ks < KSN; ks++) {
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (row_ok[mt])
-                v = *reinterpret_cast<const uint4 *>(q + (((int64_t)b * R + r) * Hq + h) * HD + ks * 32 + g * 8);
-            qf[mt][ks] = __builtin_bit_cast(bf16x8, v);
-        }
+    }
+    for (int f = wave; f < 2 * MT * KSN; f += ATT_WAVES) {
+        const int plane = f / (MT * KSN), mt = (f / KSN) % MT, ks = f % KSN;
+        const int r = row0 + mt * 16 + c;
+        const uint16_t *src = plane ? q_lo : q;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (r < R && src)
+            v = *reinterpret_cast<const uint4 *>(src + (((int64_t)b * R + r) * Hq + h) * HD + ks * 32 + g * 8);
+        q_lds[f * 64 + lane] = v;
     }
 
     f32x4 o_acc[NTN][MT];
@@ -158,18 +169,27 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void tree_attn_kernel(
         f32x4 s_acc[MT][2];
 #pragma unroll
         for (int mt = 0; mt < MT; mt++) s_acc[mt][0] = s_acc[mt][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+        bf16x8 kf[2][KSN];
 #pragma unroll
         for (int tt = 0; tt < 2; tt++) {
             const int key = kb + 8 * (c >> 2) + 4 * tt + (c & 3);
 #pragma unroll
-            for (int ks = 0; ks < KSN; ks++) {
-                const bf16x8 kf = __builtin_bit_cast(
+            for (int ks = 0; ks < KSN; ks++)
+                kf[tt][ks] = __builtin_bit_cast(
                     bf16x8, *reinterpret_cast<const uint4 *>(ks_lds + key * KSTR + (ks * 32 + g * 8) * 2));
-#pragma unroll
-                for (int mt = 0; mt < MT; mt++)
-                    s_acc[mt][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[mt][ks], s_acc[mt][tt], 0, 0, 0);
-            }
         }
+#pragma unroll
+        for (int ks = 0; ks < KSN; ks++)
+#pragma unroll
+            for (int mt = 0; mt < MT; mt++) {
+                const bf16x8 qh = __builtin_bit_cast(bf16x8, q_lds[((0 * MT + mt) * KSN + ks) * 64 + lane]);
+                const bf16x8 ql = __builtin_bit_cast(bf16x8, q_lds[((1 * MT + mt) * KSN + ks) * 64 + lane]);
+#pragma unroll
+                for (int tt = 0; tt < 2; tt++) {
+                    s_acc[mt][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[tt][ks], qh, s_acc[mt][tt], 0, 0, 0);
+                    s_acc[mt][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[tt][ks], ql, s_acc[mt][tt], 0, 0, 0);
+                }
+            }
 
         const bool need_mask = (base < P) || (base + ATT_TK > P + Lc);
         bf16x8 pf[MT];
@@ -321,7 +341,8 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void tree_attn_kernel(
 
 // out[b][r][h*HD + i] = sum_s w_s O_s[i] / sum_s w_s l_s,  w_s = 2^(m_s - max m)
 __global__ void attn_merge_kernel(const float *__restrict__ part_o, const float *__restrict__ part_ml,
-                                  int R, int Hq, int HD, int n_splits, uint16_t *__restrict__ out) {
+                                  int R, int Hq, int HD, int n_splits, uint16_t *__restrict__ out,
+                                  uint16_t *__restrict__ out_lo) {
     const int r = blockIdx.x, h = blockIdx.y, b = blockIdx.z, i = threadIdx.x;
     const int64_t pbase = ((int64_t)b * Hq + h) * n_splits;
     float m = -INFINITY;
@@ -333,7 +354,10 @@ __global__ void attn_merge_kernel(const float *__restrict__ part_o, const float 
         l += w * part_ml[((pbase + s) * R + r) * 2 + 1];
         acc += w * part_o[((pbase + s) * R + r) * HD + i];
     }
-    out[(((int64_t)b * R + r) * Hq + h) * HD + i] = f32_to_bf16(l > 0.f ? acc / l : 0.f);
+    uint16_t hi, lo;
+    split_bf16(l > 0.f ? acc / l : 0.f, hi, lo);
+    out[(((int64_t)b * R + r) * Hq + h) * HD + i] = hi;
+    if (out_lo) out_lo[(((int64_t)b * R + r) * Hq + h) * HD + i] = lo;
 }
 
 AttnPlan attn_plan(int batch, int rows, int n_heads, int hd, int ctx_hint, int n_prompt) {
@@ -353,7 +377,7 @@ AttnPlan attn_plan(int batch, int rows, int n_heads, int hd, int ctx_hint, int n
 }
 
 template <int HD, int MT>
-static void launch_attn_t(const TemplateDev &t, const void *q, const void *k_cache, const void *v_cache,
+static void launch_attn_t(const TemplateDev &t, const void *q, const void *q_lo, const void *k_cache, const void *v_cache,
                           const void *k_tree, const void *v_tree, const void *prompt_k,
                           const void *prompt_v, const int32_t *ctx_len, int batch, int Hq, int Hkv, int P,
                           int smax, const AttnPlan &p, float *part_o, float *part_ml, hipStream_t s) {
@@ -368,25 +392,25 @@ static void launch_attn_t(const TemplateDev &t, const void *q, const void *k_cac
     const float scale_log2 = 1.4426950408889634f / sqrtf((float)HD);
     dim3 grid(p.splits, Hq * n_qblk, batch);
     hipLaunchKernelGGL((tree_attn_kernel<HD, MT>), grid, dim3(ATT_WAVES * 64), smem, s, t,
-                       (const uint16_t *)q, (const uint16_t *)k_cache, (const uint16_t *)v_cache,
+                       (const uint16_t *)q, (const uint16_t *)q_lo, (const uint16_t *)k_cache, (const uint16_t *)v_cache,
                        (const uint16_t *)k_tree, (const uint16_t *)v_tree, (const uint16_t *)prompt_k,
                        (const uint16_t *)prompt_v, ctx_len, Hq, Hkv, P, smax, p.splits, n_qblk, scale_log2,
                        part_o, part_ml);
 }
 
-void launch_tree_attention(const TemplateDev &t, const void *q, const void *k_cache, const void *v_cache,
+void launch_tree_attention(const TemplateDev &t, const void *q, const void *q_lo, const void *k_cache, const void *v_cache,
                            const void *k_tree, const void *v_tree, const void *prompt_k,
                            const void *prompt_v, const int32_t *ctx_len, int batch, int Hq, int Hkv, int hd,
                            int P, int smax, const AttnPlan &p, float *part_o, float *part_ml, void *out,
-                           hipStream_t s) {
+                           void *out_lo, hipStream_t s) {
     const bool small = t.rows <= 16;
     if (hd == 128) {
-        if (small) launch_attn_t<128, 1>(t, q, k_cache, v_cache, k_tree, v_tree, prompt_k, prompt_v, ctx_len, batch, Hq, Hkv, P, smax, p, part_o, part_ml, s);
-        else launch_attn_t<128, 5>(t, q, k_cache, v_cache, k_tree, v_tree, prompt_k, prompt_v, ctx_len, batch, Hq, Hkv, P, smax, p, part_o, part_ml, s);
+        if (small) launch_attn_t<128, 1>(t, q, q_lo, k_cache, v_cache, k_tree, v_tree, prompt_k, prompt_v, ctx_len, batch, Hq, Hkv, P, smax, p, part_o, part_ml, s);
+        else launch_attn_t<128, 5>(t, q, q_lo, k_cache, v_cache, k_tree, v_tree, prompt_k, prompt_v, ctx_len, batch, Hq, Hkv, P, smax, p, part_o, part_ml, s);
     } else {
-        if (small) launch_attn_t<64, 1>(t, q, k_cache, v_cache, k_tree, v_tree, prompt_k, prompt_v, ctx_len, batch, Hq, Hkv, P, smax, p, part_o, part_ml, s);
-        else launch_attn_t<64, 5>(t, q, k_cache, v_cache, k_tree, v_tree, prompt_k, prompt_v, ctx_len, batch, Hq, Hkv, P, smax, p, part_o, part_ml, s);
+        if (small) launch_attn_t<64, 1>(t, q, q_lo, k_cache, v_cache, k_tree, v_tree, prompt_k, prompt_v, ctx_len, batch, Hq, Hkv, P, smax, p, part_o, part_ml, s);
+        else launch_attn_t<64, 5>(t, q, q_lo, k_cache, v_cache, k_tree, v_tree, prompt_k, prompt_v, ctx_len, batch, Hq, Hkv, P, smax, p, part_o, part_ml, s);
     }
     hipLaunchKernelGGL(attn_merge_kernel, dim3(t.rows, Hq, batch), dim3(hd), 0, s, part_o, part_ml, t.rows,
-                       Hq, hd, p.splits, (uint16_t *)out);
+                       Hq, hd, p.splits, (uint16_t *)out, (uint16_t *)out_lo);
 }

@@ -17,6 +17,11 @@ __device__ __forceinline__ uint16_t f32_to_bf16(float f) {
     u += 0x7FFFu + ((u >> 16) & 1u);
     return (uint16_t)(u >> 16);
 }
+// x ~= hi + lo with both parts bf16: the pair carries ~16 mantissa bits of x
+__device__ __forceinline__ void split_bf16(float x, uint16_t &hi, uint16_t &lo) {
+    hi = f32_to_bf16(x);
+    lo = f32_to_bf16(x - bf16_to_f32(hi));
+}
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
     return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
 }
@@ -48,35 +53,38 @@ struct bita_tree_template {
 };
 
 // ---- kernel launchers (each only enqueues) --------------------------------------
-struct GemmPlan { int splits, ksteps_per_split, nw; };
+struct GemmPlan { int splits, ksteps_per_split, variant; };
+void gemm_force_plan(int variant, int splits);   // tuning aid: < 0 restores the heuristic
 GemmPlan gemm_plan(int m_rows, int64_t n_rows, int64_t k);
 // out_partial: [splits][m_rows][ldo] fp32
-void launch_gemm(const void *a, int m_rows, int64_t k, int64_t lda, const void *w_packed,
-                 int64_t n_rows, float *out_partial, int64_t ldo, const GemmPlan &p, hipStream_t s);
+// a_lo may be null (single bf16 plane)
+void launch_gemm(const void *a_hi, const void *a_lo, int m_rows, int64_t k, int64_t lda,
+                 const void *w_packed, int64_t n_rows, float *out_partial, int64_t ldo,
+                 const GemmPlan &p, hipStream_t s);
 void launch_reduce_partials(const float *partial, int splits, int m_rows, int64_t n, int64_t ld,
                             float *out, hipStream_t s);
 void launch_pack(const void *src, int64_t n_rows, int64_t k, void *dst, int64_t tile0,
-                 int64_t tile_stride, hipStream_t s);
+                 int64_t tile_stride, int64_t total_tiles, hipStream_t s);
 
 void launch_embed(const int32_t *token, const TemplateDev &t, int batch, const void *tok_emb,
                   const void *mask_emb, int d, int vocab, float *x, hipStream_t s);
 // x += sum of partials (optional), then h = rmsnorm(x) * gain as bf16 with row stride ldh
 void launch_rmsnorm(float *x, const float *partial, int splits, int m_rows, int d,
-                    const void *gain, float eps, void *h, int64_t ldh, hipStream_t s);
+                    const void *gain, float eps, void *h_hi, void *h_lo, int64_t ldh, hipStream_t s);
 void launch_qkv_rope(const float *partial, int splits, int batch, const TemplateDev &t,
                      int n_heads, int n_kv_heads, int hd, const int32_t *ctx_len,
                      const float *rope_cos, const float *rope_sin, int max_pos,
-                     void *q, void *k_tree, void *v_tree, hipStream_t s);
+                     void *q, void *q_lo, void *k_tree, void *v_tree, hipStream_t s);
 void launch_silu_mul(const float *partial, int splits, int m_rows, int d_ffn, void *act,
-                     int64_t ld_act, hipStream_t s);
+                     void *act_lo, int64_t ld_act, hipStream_t s);
 void launch_select(const float *logits, int batch, const TemplateDev &t, int vocab, int kmax,
                    int32_t *argmax, int32_t *topk_ids, float *topk_val, hipStream_t s);
 
 struct AttnPlan { int splits; size_t part_o_bytes, part_ml_bytes; };
 AttnPlan attn_plan(int batch, int rows, int n_heads, int hd, int ctx_hint, int n_prompt);
-void launch_tree_attention(const TemplateDev &t, const void *q, const void *k_cache,
+void launch_tree_attention(const TemplateDev &t, const void *q, const void *q_lo, const void *k_cache,
                            const void *v_cache, const void *k_tree, const void *v_tree,
                            const void *prompt_k, const void *prompt_v, const int32_t *ctx_len,
                            int batch, int n_heads, int n_kv_heads, int hd, int n_prompt, int smax,
                            const AttnPlan &p, float *part_o, float *part_ml, void *out,
-                           hipStream_t s);
+                           void *out_lo, hipStream_t s);

@@ -4,32 +4,94 @@
 // extra rows are nearly free).
 //
 // Layout choices for gfx950:
-//  * W is pre-packed into 16-row tiles whose K range is a run of 1 KiB blocks, each block
-//    being exactly one v_mfma_f32_16x16x32_bf16 B-operand (lane l holds
-//    W[16t + l%16][32s + 8(l/16) .. +8]).  A wave therefore streams its tile with fully
-//    coalesced 16-byte-per-lane loads straight into MFMA registers; W never touches LDS.
-//  * The activation slab is small and shared by every wave, so it is staged through LDS in
-//    A-operand fragment order (conflict-free linear reads), double buffered along K.
-//  * Parallelism comes from N (16*NW rows per wave, 4 waves per workgroup) and, where N
-//    alone cannot fill 256 CUs, from split-K with fp32 partial sums reduced in a fixed
-//    order by the consumer (deterministic, no float atomics).
+//  * W is pre-packed into 1 KiB blocks, each exactly one v_mfma_f32_16x16x32_bf16 B-operand
+//    (16 rows x 32 k; lane l holds W[16t + l%16][32s + 8(l/16) .. +8]), so a wave loads its
+//    fragments with fully coalesced 16-byte-per-lane loads straight into MFMA registers; W
+//    never touches LDS.  Blocks are ordered k-major: [k-step pair][16-row tile][2 k-steps].
+//    Waves that run side by side work on neighbouring tiles of the same k range, so what
+//    the chip reads at any moment is one contiguous region (as in a plain copy), instead of
+//    thousands of streams a power-of-two stride apart that would pile onto few HBM channels.
+//  * The activation slab is small and shared by every wave.  It is brought into LDS with
+//    direct global->LDS loads, one 1 KiB A-operand fragment per instruction, so the LDS
+//    image is already in fragment order (conflict-free linear reads) and no VGPRs are spent
+//    on staging.
+//  * Activations may come as two bf16 planes (hi = bf16(x), lo = bf16(x - hi)); both are
+//    multiplied with the same weight fragment.  That removes the activation rounding from
+//    the error budget at the price of 2x MFMA work, which the kernel has to spare (at 68
+//    rows it needs ~1/4 of the matrix-core rate the HBM stream could feed).
+//  * A three-stage software pipeline keeps two stages of W (registers) and A (LDS ring) in
+//    flight behind the one being multiplied; waits are on the oldest stage only.
+//  * Parallelism comes from N (16*NW rows per wave) and, where N alone cannot fill 256 CUs,
+//    from split-K with fp32 partial sums reduced in a fixed order by the consumer
+//    (deterministic, no float atomics).
 #include "common.h"
+#include <type_traits>
 
-#define GEMM_KC 4          // k-steps (of 32) per LDS chunk
-#define GEMM_WAVES 4
+__device__ uint4 g_zero16 = {0u, 0u, 0u, 0u};   // source for out-of-range A granules
 
-template <int MT, int NW>
-__global__ __launch_bounds__(GEMM_WAVES * 64) void gemm_skinny_kernel(
-    const uint16_t *__restrict__ A, int M, int K, int64_t lda, const uint4 *__restrict__ Wp,
-    int NT, int KS, float *__restrict__ out, int64_t ldo, int ksteps_per_split) {
-    __shared__ uint4 a_lds[2][MT * GEMM_KC * 64];
+// index of the 1 KiB block holding rows 16t..16t+15, k 32ks..32ks+31 (k-major order)
+__host__ __device__ __forceinline__ int64_t packed_block(int64_t t, int64_t ks, int64_t n_tiles) {
+    return ((ks >> 1) * n_tiles + t) * 2 + (ks & 1);
+}
+
+// wait until at most N vector-memory operations of this wave are outstanding
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    static_assert(N >= 0 && N < 64, "vmcnt range");
+    __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0xF << 8));
+}
+
+// Workgroup barrier without the memory fences of __syncthreads(): those would drain every
+// outstanding vector-memory operation (vmcnt(0)) and with it the prefetched stages.  The
+// data hazards are covered explicitly: the wave waits for its own LDS-bound loads of the
+// stage about to be read (wait_vmcnt) before arriving, and its LDS reads of the previous
+// stage have been consumed by MFMAs, hence completed, before it arrives.
+__device__ __forceinline__ void wg_barrier() {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
+template <int I, int N, typename F>
+__device__ __forceinline__ void static_for(F &&f) {
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
+// MT m-tiles of 16 rows, NW n-tiles per wave, SPLIT = two activation planes, KC k-steps (of 32)
+// per pipeline stage, D stages in the ring (D-1 in flight behind the one being multiplied),
+// WAVES wavefronts per workgroup.
+template <int MT, int NW, bool SPLIT, int KC, int D, int WAVES>
+struct GemmCfg {
+    static constexpr int PL = SPLIT ? 2 : 1;
+    static constexpr int NFRAG = PL * MT * KC;                  // A fragments per stage
+    static constexpr int FPW = (NFRAG + WAVES - 1) / WAVES;     // fetched per wave per stage
+    static constexpr int SLOT_FRAGS = FPW * WAVES;              // incl. padding fragments
+#ifdef GEMM_EXP_NO_A
+    static constexpr int LOADS = NW * KC;
+#else
+    static constexpr int LOADS = NW * KC + FPW;                 // VMEM ops per wave per stage
+#endif
+    static constexpr int SMEM = D * SLOT_FRAGS * 1024;
+    static_assert((D - 2) * LOADS < 64, "vmcnt counter range");
+};
+
+template <int MT, int NW, bool SPLIT, int KC, int D, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
+    const uint16_t *__restrict__ A_hi, const uint16_t *__restrict__ A_lo, int M, int K, int64_t lda,
+    const uint4 *__restrict__ Wp, int NT, int KS, float *__restrict__ out, int64_t ldo,
+    int ksteps_per_split) {
+    using C = GemmCfg<MT, NW, SPLIT, KC, D, WAVES>;
+    extern __shared__ __attribute__((aligned(16))) uint4 a_lds[];   // [D][SLOT_FRAGS][64]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int t0 = (blockIdx.x * GEMM_WAVES + wave) * NW;
+    const int t0 = (blockIdx.x * WAVES + wave) * NW;
     const int ks_begin = blockIdx.y * ksteps_per_split;
     const int ks_end = min(KS, ks_begin + ksteps_per_split);
     const int m_base = blockIdx.z * (MT * 16);
-    const int n_chunks = (ks_end - ks_begin + GEMM_KC - 1) / GEMM_KC;
+    const int n_stages = (ks_end - ks_begin + KC - 1) / KC;
 
     f32x4 acc[MT][NW];
 #pragma unroll
@@ -37,69 +99,90 @@ __global__ __launch_bounds__(GEMM_WAVES * 64) void gemm_skinny_kernel(
 #pragma unroll
         for (int j = 0; j < NW; j++) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    uint4 w_next[NW][GEMM_KC];
-    uint4 a_stage[MT];
-    const uint4 zero4 = make_uint4(0, 0, 0, 0);
+    uint4 w[D][NW][KC];
+    const int a_row = lane & 15, a_kq = lane >> 4;
 
-    // staging map: thread tid of pass `it` owns row it*16 + tid%16, k-group tid/16
-    const int a_row = tid & 15, a_q = tid >> 4;
-
-    auto load_w = [&](int chunk) {
-        const int ks0 = ks_begin + chunk * GEMM_KC;
+    // Issue all loads of pipeline stage `stage` into ring slot SLOT: NW*KC weight fragments to
+    // registers and this wave's FPW activation fragments to LDS.  Every wave issues exactly
+    // C::LOADS vector-memory operations, which is what the vmcnt waits below count on.
+    auto issue = [&](auto slot_c, int stage) {
+        constexpr int SLOT = decltype(slot_c)::value;
+        const int ks0 = ks_begin + stage * KC;
 #pragma unroll
         for (int j = 0; j < NW; j++)
 #pragma unroll
-            for (int s = 0; s < GEMM_KC; s++) {
+            for (int s = 0; s < KC; s++) {
                 const int t = t0 + j, ks = ks0 + s;
-                w_next[j][s] = (t < NT && ks < ks_end)
-                                   ? Wp[((int64_t)t * KS + ks) * 64 + lane] : zero4;
+                const bool ok = (t < NT) && (ks < ks_end);
+                const uint4 *p = ok ? Wp + packed_block(t, ks, NT) * 64 + lane : &g_zero16;
+                w[SLOT][j][s] = *p;
             }
-    };
-    auto load_a = [&](int chunk) {
-        const int k = (ks_begin + chunk * GEMM_KC) * 32 + a_q * 8;
+#ifndef GEMM_EXP_NO_A
 #pragma unroll
-        for (int it = 0; it < MT; it++) {
-            const int m = m_base + it * 16 + a_row;
-            a_stage[it] = (m < M && k < K && k < ks_end * 32)
-                              ? *reinterpret_cast<const uint4 *>(A + (int64_t)m * lda + k) : zero4;
+        for (int i = 0; i < C::FPW; i++) {
+            const int f = i * WAVES + wave;                       // fragment id inside the stage
+            const int plane = f / (MT * KC), mt = (f / KC) % MT, s = f % KC;
+            const int m = m_base + mt * 16 + a_row;
+            const int k = (ks0 + s) * 32 + a_kq * 8;
+            const bool ok = (f < C::NFRAG) && (m < M) && (k < K) && (ks0 + s < ks_end);
+            const uint16_t *base = (SPLIT && plane == 1) ? A_lo : A_hi;
+            const void *src = ok ? (const void *)(base + (int64_t)m * lda + k) : (const void *)&g_zero16;
+            uint4 *dst = a_lds + ((SLOT * C::SLOT_FRAGS + f) * 64);   // wave-uniform; lane l lands at dst[l]
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                             (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
+        }
+#endif
+    };
+    auto compute = [&](auto slot_c, int stage) {
+        constexpr int SLOT = decltype(slot_c)::value;
+        const int ks0 = ks_begin + stage * KC;
+#pragma unroll
+        for (int s = 0; s < KC; s++) {
+            if (ks0 + s >= ks_end) break;
+#pragma unroll
+            for (int pl = 0; pl < C::PL; pl++)
+#pragma unroll
+                for (int i = 0; i < MT; i++) {
+                    const int f = (pl * MT + i) * KC + s;
+                    const bf16x8 a = __builtin_bit_cast(bf16x8, a_lds[(SLOT * C::SLOT_FRAGS + f) * 64 + lane]);
+#pragma unroll
+                    for (int j = 0; j < NW; j++)
+#ifdef GEMM_EXP_NO_MFMA
+                    { if (pl == 0 && i == 0) { acc[i][j][0] += __uint_as_float(w[SLOT][j][s].x ^ w[SLOT][j][s].y ^ w[SLOT][j][s].z ^ w[SLOT][j][s].w); } (void)a; }
+#else
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                            a, __builtin_bit_cast(bf16x8, w[SLOT][j][s]), acc[i][j], 0, 0, 0);
+#endif
+                }
         }
     };
-    auto store_a = [&](int buf) {
-#pragma unroll
-        for (int it = 0; it < MT; it++) a_lds[buf][it * 256 + tid] = a_stage[it];
+    // One pipeline step for stage c living in slot U: wait for its data (leaving the newer
+    // stages in flight), make it visible to the workgroup, refill the slot freed by stage
+    // c-1, multiply.
+    auto step = [&](auto u_c, int c) {
+        constexpr int U = decltype(u_c)::value;
+        constexpr int PRE = (U + D - 1) % D;
+        const int newer = min(D - 2, n_stages - 1 - c);
+        static_for<0, D - 1>([&](auto j_c) {
+            constexpr int J = decltype(j_c)::value;
+            if (newer == J) wait_vmcnt<J * C::LOADS>();
+        });
+#ifndef GEMM_EXP_NO_BARRIER
+        wg_barrier();
+#endif
+        if (c + D - 1 < n_stages) issue(std::integral_constant<int, PRE>{}, c + D - 1);
+        compute(u_c, c);
     };
 
-    if (n_chunks > 0) {
-        load_w(0);
-        load_a(0);
-        store_a(0);
-    }
-    __syncthreads();
-    for (int c = 0; c < n_chunks; c++) {
-        uint4 w_cur[NW][GEMM_KC];
-#pragma unroll
-        for (int j = 0; j < NW; j++)
-#pragma unroll
-            for (int s = 0; s < GEMM_KC; s++) w_cur[j][s] = w_next[j][s];
-        const bool more = (c + 1 < n_chunks);
-        if (more) {
-            load_w(c + 1);
-            load_a(c + 1);
-        }
-        const int buf = c & 1;
-#pragma unroll
-        for (int s = 0; s < GEMM_KC; s++) {
-#pragma unroll
-            for (int i = 0; i < MT; i++) {
-                const bf16x8 a = __builtin_bit_cast(bf16x8, a_lds[buf][(i * GEMM_KC + s) * 64 + lane]);
-#pragma unroll
-                for (int j = 0; j < NW; j++)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                        a, __builtin_bit_cast(bf16x8, w_cur[j][s]), acc[i][j], 0, 0, 0);
-            }
-        }
-        if (more) store_a(buf ^ 1);
-        __syncthreads();
+    static_for<0, D - 1>([&](auto u_c) {
+        constexpr int U = decltype(u_c)::value;
+        if (U < n_stages) issue(u_c, U);
+    });
+    for (int c = 0; c < n_stages; c += D) {
+        static_for<0, D>([&](auto u_c) {
+            constexpr int U = decltype(u_c)::value;
+            if (c + U < n_stages) step(u_c, c + U);
+        });
     }
 
     // D layout: lane (g = lane/16, c = lane%16) holds rows 4g..4g+3, column c of each tile.
@@ -132,52 +215,91 @@ __global__ void reduce_partials_kernel(const float *__restrict__ partial, int sp
 
 // Pure permutation: row-major [N][K] bf16 -> packed tiles (see file header).
 __global__ void pack_weight_kernel(const uint16_t *__restrict__ src, int64_t N, int64_t K, int64_t KS,
-                                   uint4 *__restrict__ dst, int64_t tile0, int64_t tile_stride) {
-    const int64_t blk = blockIdx.x;            // (source tile, k-step)
+                                   uint4 *__restrict__ dst, int64_t tile0, int64_t tile_stride,
+                                   int64_t total_tiles) {
+    const int64_t blk = blockIdx.x;            // (source tile, k-step incl. the padding step)
     const int64_t t = blk / KS, s = blk % KS;
     const int lane = threadIdx.x;
     const int64_t n = t * 16 + (lane & 15), k = s * 32 + (lane >> 4) * 8;
     uint4 v = make_uint4(0, 0, 0, 0);
     if (k < K) v = *reinterpret_cast<const uint4 *>(src + n * K + k);
-    dst[((tile0 + t * tile_stride) * KS + s) * 64 + lane] = v;
+    dst[packed_block(tile0 + t * tile_stride, s, total_tiles) * 64 + lane] = v;
 }
+
+// Launch shapes.  variant: 0 = 4 waves x 1 tile, 1 = 4 waves x 2 tiles, 2 = 4 waves x 4 tiles,
+// 3 = 8 waves x 2 tiles (rows per workgroup: 64, 128, 256, 256).
+static const int kVariantWaves[] = {4, 4, 4, 8, 4, 4, 8, 8, 4, 8};
+static const int kVariantNw[] = {1, 2, 4, 2, 2, 2, 1, 2, 4, 1};
+#define GEMM_N_VARIANTS 10
+#define GEMM_RING_KC 2
+static int g_force_variant = -1, g_force_splits = -1;
+void gemm_force_plan(int variant, int splits) { g_force_variant = variant; g_force_splits = splits; }
 
 GemmPlan gemm_plan(int m_rows, int64_t n_rows, int64_t k) {
     GemmPlan p;
     const int64_t NT = n_rows / 16, KS = (k + 31) / 32;
-    p.nw = (NT >= 2048) ? 2 : 1;
-    const int64_t wgs_n = (NT + GEMM_WAVES * p.nw - 1) / (GEMM_WAVES * p.nw);
-    int64_t splits = (1024 + wgs_n - 1) / wgs_n;          // aim at >= ~4 workgroups per CU
-    const int64_t max_splits = (KS + 2 * GEMM_KC - 1) / (2 * GEMM_KC);  // >= 2 chunks per split
+    p.variant = (NT >= 512) ? 1 : 0;
+    if (g_force_variant >= 0 && g_force_variant < GEMM_N_VARIANTS) p.variant = g_force_variant;
+    const int tiles_wg = kVariantWaves[p.variant] * kVariantNw[p.variant];
+    const int64_t wgs_n = (NT + tiles_wg - 1) / tiles_wg;
+    // two workgroups are resident per CU: aim at one full round of 512 workgroups
+    int64_t splits = 512 / wgs_n;
+    const int64_t max_splits = KS / (4 * GEMM_RING_KC);       // at least 4 stages per split
     if (splits > max_splits) splits = max_splits;
-    if (splits < 1) splits = 1;
     if (splits > 16) splits = 16;
+    if (g_force_splits > 0) splits = g_force_splits;
+    if (splits < 1) splits = 1;
     int64_t per = (KS + splits - 1) / splits;
-    per = (per + GEMM_KC - 1) / GEMM_KC * GEMM_KC;        // whole chunks
+    per = (per + GEMM_RING_KC - 1) / GEMM_RING_KC * GEMM_RING_KC;   // whole stages
     p.ksteps_per_split = (int)per;
     p.splits = (int)((KS + per - 1) / per);
     (void)m_rows;
     return p;
 }
 
-template <int MT, int NW>
-static void launch_gemm_t(const void *a, int M, int64_t K, int64_t lda, const void *w, int64_t N,
-                          float *out, int64_t ldo, const GemmPlan &p, hipStream_t s) {
+template <int MT, int NW, bool SPLIT, int KC, int D, int WAVES>
+static void launch_gemm_t(const void *a_hi, const void *a_lo, int M, int64_t K, int64_t lda, const void *w,
+                          int64_t N, float *out, int64_t ldo, const GemmPlan &p, hipStream_t s) {
+    using C = GemmCfg<MT, NW, SPLIT, KC, D, WAVES>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute((const void *)gemm_skinny_kernel<MT, NW, SPLIT, KC, D, WAVES>,
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM);
+        attr_set = true;
+    }
     const int NT = (int)(N / 16), KS = (int)((K + 31) / 32);
-    dim3 grid((NT + GEMM_WAVES * NW - 1) / (GEMM_WAVES * NW), p.splits, (M + MT * 16 - 1) / (MT * 16));
-    hipLaunchKernelGGL((gemm_skinny_kernel<MT, NW>), grid, dim3(GEMM_WAVES * 64), 0, s,
-                       (const uint16_t *)a, M, (int)K, lda, (const uint4 *)w, NT, KS, out, ldo,
-                       p.ksteps_per_split);
+    dim3 grid((NT + WAVES * NW - 1) / (WAVES * NW), p.splits, (M + MT * 16 - 1) / (MT * 16));
+    hipLaunchKernelGGL((gemm_skinny_kernel<MT, NW, SPLIT, KC, D, WAVES>), grid, dim3(WAVES * 64), C::SMEM, s,
+                       (const uint16_t *)a_hi, (const uint16_t *)a_lo, M, (int)K, lda, (const uint4 *)w, NT,
+                       KS, out, ldo, p.ksteps_per_split);
 }
 
-void launch_gemm(const void *a, int M, int64_t K, int64_t lda, const void *w, int64_t N, float *out,
-                 int64_t ldo, const GemmPlan &p, hipStream_t s) {
+template <int MT, bool SPLIT>
+static void launch_gemm_v(const void *a_hi, const void *a_lo, int M, int64_t K, int64_t lda, const void *w,
+                          int64_t N, float *out, int64_t ldo, const GemmPlan &p, hipStream_t s) {
+    constexpr int KC = GEMM_RING_KC;
+    switch (p.variant) {
+        case 0: launch_gemm_t<MT, 1, SPLIT, KC, 4, 4>(a_hi, a_lo, M, K, lda, w, N, out, ldo, p, s); break;
+        case 1: launch_gemm_t<MT, 2, SPLIT, KC, 3, 4>(a_hi, a_lo, M, K, lda, w, N, out, ldo, p, s); break;
+        case 2: launch_gemm_t<MT, 4, SPLIT, KC, 3, 4>(a_hi, a_lo, M, K, lda, w, N, out, ldo, p, s); break;
+        case 3: launch_gemm_t<MT, 2, SPLIT, KC, 3, 8>(a_hi, a_lo, M, K, lda, w, N, out, ldo, p, s); break;
+        case 4: launch_gemm_t<MT, 2, SPLIT, KC, 4, 4>(a_hi, a_lo, M, K, lda, w, N, out, ldo, p, s); break;
+        case 5: launch_gemm_t<MT, 2, SPLIT, KC, 5, 4>(a_hi, a_lo, M, K, lda, w, N, out, ldo, p, s); break;
+        case 6: launch_gemm_t<MT, 1, SPLIT, KC, 4, 8>(a_hi, a_lo, M, K, lda, w, N, out, ldo, p, s); break;
+        case 7: launch_gemm_t<MT, 2, SPLIT, KC, 4, 8>(a_hi, a_lo, M, K, lda, w, N, out, ldo, p, s); break;
+        case 8: launch_gemm_t<MT, 4, SPLIT, KC, 4, 4>(a_hi, a_lo, M, K, lda, w, N, out, ldo, p, s); break;
+        default: launch_gemm_t<MT, 1, SPLIT, KC, 6, 8>(a_hi, a_lo, M, K, lda, w, N, out, ldo, p, s); break;
+    }
+}
+
+void launch_gemm(const void *a_hi, const void *a_lo, int M, int64_t K, int64_t lda, const void *w, int64_t N,
+                 float *out, int64_t ldo, const GemmPlan &p, hipStream_t s) {
     if (M <= 16) {
-        if (p.nw == 2) launch_gemm_t<1, 2>(a, M, K, lda, w, N, out, ldo, p, s);
-        else launch_gemm_t<1, 1>(a, M, K, lda, w, N, out, ldo, p, s);
+        if (a_lo) launch_gemm_v<1, true>(a_hi, a_lo, M, K, lda, w, N, out, ldo, p, s);
+        else launch_gemm_v<1, false>(a_hi, nullptr, M, K, lda, w, N, out, ldo, p, s);
     } else {
-        if (p.nw == 2) launch_gemm_t<5, 2>(a, M, K, lda, w, N, out, ldo, p, s);
-        else launch_gemm_t<5, 1>(a, M, K, lda, w, N, out, ldo, p, s);
+        if (a_lo) launch_gemm_v<5, true>(a_hi, a_lo, M, K, lda, w, N, out, ldo, p, s);
+        else launch_gemm_v<5, false>(a_hi, nullptr, M, K, lda, w, N, out, ldo, p, s);
     }
 }
 
@@ -188,8 +310,8 @@ void launch_reduce_partials(const float *partial, int splits, int M, int64_t N, 
 }
 
 void launch_pack(const void *src, int64_t N, int64_t K, void *dst, int64_t tile0, int64_t tile_stride,
-                 hipStream_t s) {
-    const int64_t KS = (K + 31) / 32;
+                 int64_t total_tiles, hipStream_t s) {
+    const int64_t KS = ((K + 63) / 64) * 2;                 // k-steps incl. zero padding to a pair
     hipLaunchKernelGGL(pack_weight_kernel, dim3((unsigned)((N / 16) * KS)), dim3(64), 0, s,
-                       (const uint16_t *)src, N, K, KS, (uint4 *)dst, tile0, tile_stride);
+                       (const uint16_t *)src, N, K, KS, (uint4 *)dst, tile0, tile_stride, total_tiles);
 }

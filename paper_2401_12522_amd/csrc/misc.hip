@@ -27,39 +27,81 @@ __device__ __forceinline__ float wave_sum(float v) {
     return v;
 }
 
-// One workgroup per row: x += sum_s partial[s] (fixed order), h = x * rsqrt(mean(x^2)+eps) * g.
+// One workgroup per row: x += sum_s partial[s] (fixed order), h = x * rsqrt(mean(x^2)+eps) * g,
+// written as two bf16 planes (hi = bf16(h), lo = bf16(h - hi)) so that the following GEMM sees
+// the activation to ~16 mantissa bits.  Each thread owns float4 columns tid, tid+256, ...; all
+// loads of a column are independent and issued together.
+#define RMS_MAX_V4 8      // d_model <= 8192 is kept in registers, larger rows are re-read
 __global__ __launch_bounds__(256) void rmsnorm_kernel(float *__restrict__ x, const float *__restrict__ partial,
                                                       int splits, int M, int d,
                                                       const uint16_t *__restrict__ gain, float eps,
-                                                      uint16_t *__restrict__ h, int64_t ldh) {
+                                                      uint16_t *__restrict__ h_hi, uint16_t *__restrict__ h_lo,
+                                                      int64_t ldh) {
     __shared__ float red[4];
-    const int row = blockIdx.x;
-    float *xr = x + (int64_t)row * d;
+    const int row = blockIdx.x, tid = threadIdx.x;
+    const int nv = d >> 2;                                   // float4 columns (d % 4 == 0)
+    float4 *xr = reinterpret_cast<float4 *>(x + (int64_t)row * d);
+    float4 keep[RMS_MAX_V4];
     float ss = 0.f;
-    for (int i = threadIdx.x; i < d; i += 256) {
-        float v = xr[i];
-        for (int s = 0; s < splits; s++) v += partial[((int64_t)s * M + row) * d + i];
-        if (splits > 0) xr[i] = v;
-        ss += v * v;
+#pragma unroll
+    for (int it = 0; it < RMS_MAX_V4; it++) {
+        const int c = it * 256 + tid;
+        if (c < nv) {
+            float4 v = xr[c];
+            for (int s = 0; s < splits; s++) {
+                const float4 p = reinterpret_cast<const float4 *>(partial + ((int64_t)s * M + row) * d)[c];
+                v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
+            }
+            if (splits > 0) xr[c] = v;
+            keep[it] = v;
+            ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+        }
+    }
+    for (int c = RMS_MAX_V4 * 256 + tid; c < nv; c += 256) {   // rows wider than the register budget
+        float4 v = xr[c];
+        for (int s = 0; s < splits; s++) {
+            const float4 p = reinterpret_cast<const float4 *>(partial + ((int64_t)s * M + row) * d)[c];
+            v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
+        }
+        if (splits > 0) xr[c] = v;
+        ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
     }
     ss = wave_sum(ss);
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+    if ((tid & 63) == 0) red[tid >> 6] = ss;
     __syncthreads();
     const float tot = red[0] + red[1] + red[2] + red[3];
     const float scale = 1.0f / sqrtf(tot / (float)d + eps);
-    for (int i = threadIdx.x; i < d; i += 256)
-        h[(int64_t)row * ldh + i] = f32_to_bf16(xr[i] * scale * bf16_to_f32(gain[i]));
+    auto emit = [&](int c, float4 v) {
+        const uint2 gq = reinterpret_cast<const uint2 *>(gain)[c];
+        const float g0 = bf16_to_f32((uint16_t)(gq.x & 0xFFFFu)), g1 = bf16_to_f32((uint16_t)(gq.x >> 16));
+        const float g2 = bf16_to_f32((uint16_t)(gq.y & 0xFFFFu)), g3 = bf16_to_f32((uint16_t)(gq.y >> 16));
+        const float o[4] = {v.x * scale * g0, v.y * scale * g1, v.z * scale * g2, v.w * scale * g3};
+        uint16_t hi[4], lo[4];
+#pragma unroll
+        for (int e = 0; e < 4; e++) split_bf16(o[e], hi[e], lo[e]);
+        uint2 ph, pl;
+        ph.x = hi[0] | ((uint32_t)hi[1] << 16); ph.y = hi[2] | ((uint32_t)hi[3] << 16);
+        pl.x = lo[0] | ((uint32_t)lo[1] << 16); pl.y = lo[2] | ((uint32_t)lo[3] << 16);
+        reinterpret_cast<uint2 *>(h_hi + (int64_t)row * ldh)[c] = ph;
+        reinterpret_cast<uint2 *>(h_lo + (int64_t)row * ldh)[c] = pl;
+    };
+#pragma unroll
+    for (int it = 0; it < RMS_MAX_V4; it++) {
+        const int c = it * 256 + tid;
+        if (c < nv) emit(c, keep[it]);
+    }
+    for (int c = RMS_MAX_V4 * 256 + tid; c < nv; c += 256) emit(c, xr[c]);
 }
 
 // ---------------------------------------------------------------------------------------
 // QKV epilogue: sum split-K partials, rotate q and k by the row's position
 // ctx_len + depth(row) in the half-split pairing, write q [B][R][Hq][hd] and the rows'
-// k/v into the per-pass tree scratch [B][Hkv][R][hd].
+// k/v into the per-pass tree scratch [B][Hkv][R][hd].  q is written as hi and lo bf16 planes.
 __global__ __launch_bounds__(64) void qkv_rope_kernel(
     const float *__restrict__ partial, int splits, int M, TemplateDev t, int Hq, int Hkv, int hd,
     const int32_t *__restrict__ ctx_len, const float *__restrict__ rope_cos,
     const float *__restrict__ rope_sin, int max_pos, uint16_t *__restrict__ q,
-    uint16_t *__restrict__ k_tree, uint16_t *__restrict__ v_tree) {
+    uint16_t *__restrict__ q_lo, uint16_t *__restrict__ k_tree, uint16_t *__restrict__ v_tree) {
     const int row = blockIdx.x, head = blockIdx.y;       // head over Hq + 2*Hkv
     const int b = row / t.rows, r = row % t.rows;
     const int half = hd >> 1, i = threadIdx.x;
@@ -72,9 +114,10 @@ __global__ __launch_bounds__(64) void qkv_rope_kernel(
         lo += p[0];
         hi += p[half];
     }
-    uint16_t *dst;
+    uint16_t *dst, *dst_lo = nullptr;
     if (head < Hq) {
         dst = q + ((int64_t)row * Hq + head) * hd;
+        dst_lo = q_lo + ((int64_t)row * Hq + head) * hd;
     } else if (head < Hq + Hkv) {
         dst = k_tree + (((int64_t)b * Hkv + (head - Hq)) * t.rows + r) * hd;
     } else {
@@ -88,14 +131,21 @@ __global__ __launch_bounds__(64) void qkv_rope_kernel(
         lo = nlo;
         hi = nhi;
     }
-    dst[i] = f32_to_bf16(lo);
-    dst[i + half] = f32_to_bf16(hi);
+    uint16_t a_hi, a_lo, b_hi, b_lo;
+    split_bf16(lo, a_hi, a_lo);
+    split_bf16(hi, b_hi, b_lo);
+    dst[i] = a_hi;
+    dst[i + half] = b_hi;
+    if (dst_lo) {                                   // queries keep their rounding residual as well
+        dst_lo[i] = a_lo;
+        dst_lo[i + half] = b_lo;
+    }
 }
 
 // ---------------------------------------------------------------------------------------
 // SwiGLU gating on the gate/up GEMM output whose 16-column tiles alternate gate, up.
 __global__ void silu_mul_kernel(const float *__restrict__ partial, int splits, int M, int F,
-                                uint16_t *__restrict__ act, int64_t ld_act) {
+                                uint16_t *__restrict__ act, uint16_t *__restrict__ act_lo, int64_t ld_act) {
     const int f = blockIdx.x * blockDim.x + threadIdx.x;
     const int row = blockIdx.y;
     if (f >= ld_act) return;
@@ -110,7 +160,10 @@ __global__ void silu_mul_kernel(const float *__restrict__ partial, int splits, i
         }
         out = gsum / (1.0f + expf(-gsum)) * usum;
     }
-    act[(int64_t)row * ld_act + f] = f32_to_bf16(out);
+    uint16_t hi, lo;
+    split_bf16(out, hi, lo);
+    act[(int64_t)row * ld_act + f] = hi;
+    act_lo[(int64_t)row * ld_act + f] = lo;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -177,22 +230,22 @@ void launch_embed(const int32_t *token, const TemplateDev &t, int batch, const v
                        (const uint16_t *)tok_emb, (const uint16_t *)mask_emb, d, vocab, x);
 }
 void launch_rmsnorm(float *x, const float *partial, int splits, int M, int d, const void *gain,
-                    float eps, void *h, int64_t ldh, hipStream_t s) {
+                    float eps, void *h_hi, void *h_lo, int64_t ldh, hipStream_t s) {
     hipLaunchKernelGGL(rmsnorm_kernel, dim3(M), dim3(256), 0, s, x, partial, splits, M, d,
-                       (const uint16_t *)gain, eps, (uint16_t *)h, ldh);
+                       (const uint16_t *)gain, eps, (uint16_t *)h_hi, (uint16_t *)h_lo, ldh);
 }
 void launch_qkv_rope(const float *partial, int splits, int batch, const TemplateDev &t, int Hq,
                      int Hkv, int hd, const int32_t *ctx_len, const float *rope_cos,
-                     const float *rope_sin, int max_pos, void *q, void *k_tree, void *v_tree,
+                     const float *rope_sin, int max_pos, void *q, void *q_lo, void *k_tree, void *v_tree,
                      hipStream_t s) {
     hipLaunchKernelGGL(qkv_rope_kernel, dim3(batch * t.rows, Hq + 2 * Hkv), dim3(64), 0, s, partial,
                        splits, batch * t.rows, t, Hq, Hkv, hd, ctx_len, rope_cos, rope_sin, max_pos,
-                       (uint16_t *)q, (uint16_t *)k_tree, (uint16_t *)v_tree);
+                       (uint16_t *)q, (uint16_t *)q_lo, (uint16_t *)k_tree, (uint16_t *)v_tree);
 }
-void launch_silu_mul(const float *partial, int splits, int M, int F, void *act, int64_t ld_act,
-                     hipStream_t s) {
+void launch_silu_mul(const float *partial, int splits, int M, int F, void *act, void *act_lo,
+                     int64_t ld_act, hipStream_t s) {
     hipLaunchKernelGGL(silu_mul_kernel, dim3((unsigned)((ld_act + 255) / 256), M), dim3(256), 0, s,
-                       partial, splits, M, F, (uint16_t *)act, ld_act);
+                       partial, splits, M, F, (uint16_t *)act, (uint16_t *)act_lo, ld_act);
 }
 void launch_select(const float *logits, int batch, const TemplateDev &t, int vocab, int kmax,
                    int32_t *argmax, int32_t *topk_ids, float *topk_val, hipStream_t s) {

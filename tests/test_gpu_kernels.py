@@ -34,21 +34,45 @@ def test_gemm_matches_float64_matmul(bita, M, N, K):
     assert np.abs(out - ref).max() <= 2e-5 * scale + 1e-6, (np.abs(out - ref).max(), scale)
 
 
-def _attention_case(bita, B, Hq, Hkv, hd, P, ctx_lens, tree_parent, attach, n_mask, seed, smax=None):
+@pytest.mark.parametrize("M,N,K", [(68, 4096, 4096), (68, 22016, 4096), (12, 256, 688), (1, 1024, 256)])
+def test_gemm_two_plane_activation(bita, M, N, K):
+    """A = hi + lo (two bf16 planes): the product must match float64 on the summed operand
+    to fp32-accumulation accuracy, i.e. the activation rounding is gone."""
+    g = torch.Generator().manual_seed(N + K)
+    a32 = torch.randn(M, K, generator=g)
+    hi = a32.to(torch.bfloat16)
+    lo = (a32 - hi.float()).to(torch.bfloat16)
+    w = (torch.randn(N, K, generator=g) * 0.05).to(torch.bfloat16)
+    a_sum = hi.to(torch.float64) + lo.to(torch.float64)
+    ref = a_sum.numpy() @ w.to(torch.float64).numpy().T
+    out = bita.gemm(hi.cuda(), bita.pack_weight(w.cuda()), N, a_lo=lo.cuda()).cpu().numpy()
+    scale = np.abs(ref).max()
+    assert np.abs(out - ref).max() <= 2e-5 * scale + 1e-6
+    # and it is closer to the unrounded product than a single plane can be
+    full = a32.to(torch.float64).numpy() @ w.to(torch.float64).numpy().T
+    assert np.abs(out - full).max() <= 3e-4 * scale
+
+
+def _attention_case(bita, B, Hq, Hkv, hd, P, ctx_lens, tree_parent, attach, n_mask, seed, smax=None,
+                    two_plane_q=True):
     rng = np.random.default_rng(seed)
     tin = synth.attach_mask_groups(tree_parent, attach, n_mask)
     d = derive_template(tin.parent, tin.is_mask, n_mask)
     R = d.R
     smax = smax or (max(ctx_lens) + 8)
     r16 = lambda *s: synth.bf16_round(rng.normal(size=s))   # noqa: E731
-    q = r16(B, R, Hq, hd)
+    q_full = rng.normal(size=(B, R, Hq, hd))
+    q_hi = synth.bf16_round(q_full)
+    q_lo = synth.bf16_round(q_full - q_hi) if two_plane_q else None
+    q = q_hi + (q_lo if two_plane_q else 0.0)          # what the kernel is given, exactly
     kc, vc = r16(B, Hkv, smax, hd), r16(B, Hkv, smax, hd)
     kt, vt = r16(B, Hkv, R, hd), r16(B, Hkv, R, hd)
     pk, pv = (r16(Hkv, P, hd), r16(Hkv, P, hd)) if P else (None, None)
     tmpl = bita.TreeTemplate(tin.parent, tin.is_mask, tin.n_tree, n_mask)
     tb = lambda a: None if a is None else torch.tensor(a).to(torch.bfloat16).cuda()   # noqa: E731
-    out = bita.tree_attention(tmpl, tb(q), tb(kc), tb(vc), tb(kt), tb(vt), tb(pk), tb(pv),
-                              torch.tensor(ctx_lens, dtype=torch.int32, device="cuda"), max(ctx_lens))
+    out = bita.tree_attention(tmpl, tb(q_hi), tb(kc), tb(vc), tb(kt), tb(vt), tb(pk), tb(pv),
+                              torch.tensor(ctx_lens, dtype=torch.int32, device="cuda"), max(ctx_lens),
+                              q_lo=tb(q_lo))
     torch.cuda.synchronize()
     out = out.to(torch.float64).cpu().numpy().reshape(B, R, Hq, hd)
     worst = 0.0
@@ -89,6 +113,8 @@ def test_tree_attention_matches_oracle(bita, case):
 def test_tree_attention_chain_equals_causal(bita):
     """Special case: a chain template is plain causal attention over [cache | chain]."""
     err = _attention_case(bita, 1, 4, 4, 64, 0, [100], synth.chain_tree(40), [], 4, seed=6)
+    assert err < ATT_TOL, err
+    err = _attention_case(bita, 1, 4, 4, 64, 0, [100], synth.chain_tree(40), [], 4, seed=6, two_plane_q=False)
     assert err < ATT_TOL, err
 
 

@@ -1,0 +1,60 @@
+"""Parity at the real widths (GPU): LLaMA-2-7B- and 70B-shaped layers at reduced depth, one
+full step each against the oracle on the same bf16-representable weights and cache."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth
+from oracle.tree import derive_template, accept_walk
+from oracle.decode import BitaState, bita_step
+from gpu_util import dev_i32, load_cache, round_state
+
+pytestmark = pytest.mark.gpu
+
+LOGIT_TOL = 3e-2
+MARGIN = 6e-2
+
+
+@pytest.mark.parametrize("name,n_layers,ctx_n", [("7b", 2, 150), ("70b", 1, 140)])
+def test_full_width_reduced_depth_step(name, n_layers, ctx_n):
+    import paper_2401_12522_amd as bita
+    cfg = synth.get_config(name, n_layers=n_layers)
+    w = synth.SynthWeights(cfg, seed=1, device="cuda")
+    wc = synth.SynthWeights(cfg, seed=1, device="cpu")
+    # the oracle reads the very tensors the GPU drew
+    for n in synth.weights.GLOBAL_TENSORS:
+        wc._store[(n, None)] = w.torch(n).cpu()
+    for l in range(n_layers):
+        for n in synth.weights.LAYER_TENSORS:
+            wc._store[(n, l)] = w.torch(n, l).cpu()
+    om = oracle.OracleModel(cfg, wc, cache_layers=False)
+    tin = synth.attach_mask_groups(synth.full_branching_tree([4, 3, 2, 1], 64), [0], cfg.n_mask)
+    d = derive_template(tin.parent, tin.is_mask, cfg.n_mask)
+    smax = 256
+    model = bita.Model(cfg, w, max_pos=smax + 64)
+    tmpl = bita.TreeTemplate(tin.parent, tin.is_mask, tin.n_tree, cfg.n_mask)
+    kv = bita.KVState(cfg, n_layers, 1, smax, tmpl.rows)
+    ctx = synth.random_context(cfg.vocab, ctx_n, 2)
+    st = round_state(BitaState(om, ctx))
+    Lc = load_cache(kv, st.cache_k, st.cache_v)
+    cand = np.random.default_rng(5).integers(0, cfg.vocab, size=(cfg.n_mask, d.kmax)).astype(np.int32)
+    buf = bita.StepBuffers(model, tmpl, 1, d.kmax, want_logits=True)
+    ref = bita_step(om, d, st, cand)
+    bita.decode_step(model, kv, Lc, tmpl, buf, 1, dev_i32([int(ctx[-1])]), dev_i32(cand[None]))
+    torch.cuda.synchronize()
+    assert buf.token[0].cpu().tolist() == ref["tokens"]
+    lg = buf.logits[0].cpu().numpy()
+    err = np.abs(lg - ref["logits"]).max()
+    print(f"{name}: logits max-abs err {err:.4f}, max |logit| {np.abs(ref['logits']).max():.2f}")
+    assert err <= LOGIT_TOL, err
+    gpu_greedy = buf.argmax[0].cpu().tolist()
+    for r in range(d.T):
+        s = np.sort(ref["logits"][r])
+        if s[-1] - s[-2] > MARGIN:
+            assert gpu_greedy[r] == ref["greedy"][r]
+    path, bonus = accept_walk(d, ref["tokens"], gpu_greedy)
+    assert buf.path[0, : len(path)].cpu().tolist() == path and int(buf.bonus[0]) == bonus
+    for l in range(n_layers):
+        got_k = kv.k_tree[l, 0].permute(1, 0, 2).to(torch.float64).cpu().numpy()
+        assert np.abs(got_k - ref["new_k"][l]).max() < 3e-2
