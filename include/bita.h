@@ -215,6 +215,16 @@ int bita_gemm(const void *d_a, const void *d_a_lo, int32_t m_rows, int64_t k, in
               const void *d_w_packed, int64_t n_rows, void *d_ws, size_t ws_bytes, float *d_out,
               void *stream);
 
+/* Measurement aid: while enabled, bita_verify_step brackets each of its GEMM launches with
+ * a pair of HIP events on the caller's stream (not usable under graph capture).
+ * bita_profile_enable creates the events (up to max_records launches are recorded from the
+ * next step on); bita_profile_read waits for them and returns, per recorded launch, the
+ * elapsed milliseconds and the bytes of the weight matrix it streamed (HOST arrays of
+ * `capacity` entries). */
+int  bita_profile_enable(int32_t max_records);
+void bita_profile_disable(void);
+int  bita_profile_read(int32_t capacity, int32_t *n_records, float *ms, int64_t *weight_bytes);
+
 /* Tuning aid: override the GEMM launch heuristic for all later launches of this process
  * (variant = workgroup shape index, splits = split-K factor; a negative value restores the
  * heuristic for that knob).  Not thread-safe; results are unchanged, only speed. */

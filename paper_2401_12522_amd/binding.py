@@ -16,7 +16,8 @@ EXPORTS = [
     "bita_workspace_bytes", "bita_tree_template_create", "bita_tree_template_destroy",
     "bita_tree_template_info", "bita_build_tree", "bita_verify_step", "bita_accept",
     "bita_compact_kv", "bita_attention_workspace_bytes", "bita_tree_attention",
-    "bita_gemm_workspace_bytes", "bita_gemm", "bita_tune_gemm", "bita_last_error",
+    "bita_gemm_workspace_bytes", "bita_gemm", "bita_tune_gemm", "bita_profile_enable",
+    "bita_profile_disable", "bita_profile_read", "bita_last_error",
 ]
 
 
@@ -78,6 +79,9 @@ def lib():
     L.bita_gemm_workspace_bytes.restype, L.bita_gemm_workspace_bytes.argtypes = sz, [i32, i64]
     L.bita_gemm.restype, L.bita_gemm.argtypes = C.c_int, [vp, vp, i32, i64, i64, vp, i64, vp, sz, vp, vp]
     L.bita_tune_gemm.restype, L.bita_tune_gemm.argtypes = None, [i32, i32]
+    L.bita_profile_enable.restype, L.bita_profile_enable.argtypes = C.c_int, [i32]
+    L.bita_profile_disable.restype, L.bita_profile_disable.argtypes = None, []
+    L.bita_profile_read.restype, L.bita_profile_read.argtypes = C.c_int, [i32, vp, vp, vp]
     L.bita_last_error.restype, L.bita_last_error.argtypes = C.c_char_p, []
     _lib = L
     return L
@@ -289,6 +293,20 @@ def decode_step(model, kv, ctx_hint, tmpl, buf, batch, root_token, cand, group=N
     verify_step(model, kv, ctx_hint, tmpl, buf, batch)
     accept(tmpl, buf, batch)
     compact_kv(model, kv, ctx_hint, buf, batch)
+
+
+def profile_enable(max_records):
+    _check(lib().bita_profile_enable(int(max_records)))
+
+
+def profile_read(capacity):
+    """Returns (ms[n], weight_bytes[n]) of the GEMM launches recorded since profile_enable."""
+    n = C.c_int32(0)
+    ms = np.zeros(capacity, np.float32)
+    wb = np.zeros(capacity, np.int64)
+    _check(lib().bita_profile_read(capacity, C.byref(n), ms.ctypes.data_as(C.c_void_p), wb.ctypes.data_as(C.c_void_p)))
+    lib().bita_profile_disable()
+    return ms[: n.value], wb[: n.value]
 
 
 def gemm(a, w_packed, n_rows, k=None, a_lo=None):

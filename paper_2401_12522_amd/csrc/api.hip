@@ -205,6 +205,47 @@ extern "C" int32_t bita_tree_template_info(const bita_tree_template *t, int32_t 
 }
 
 // ------------------------------------------------------------------------------------------
+// Optional instrumentation: HIP events around every GEMM launch of bita_verify_step, recorded
+// on the caller's stream.  Events are created by bita_profile_enable (never inside a step).
+struct GemmRecord { hipEvent_t start, stop; int64_t weight_bytes; };
+static std::vector<GemmRecord> g_prof;
+static size_t g_prof_used = 0;
+static bool g_prof_on = false;
+
+extern "C" int bita_profile_enable(int32_t max_records) {
+    if (max_records <= 0) return bita_set_error(BITA_ERR_INVALID_ARG, "bita_profile_enable: max_records <= 0");
+    while ((int)g_prof.size() < max_records) {
+        GemmRecord r;
+        r.weight_bytes = 0;
+        BITA_HIP_CHECK(hipEventCreate(&r.start));
+        BITA_HIP_CHECK(hipEventCreate(&r.stop));
+        g_prof.push_back(r);
+    }
+    g_prof_used = 0;
+    g_prof_on = true;
+    return BITA_OK;
+}
+extern "C" void bita_profile_disable(void) { g_prof_on = false; }
+extern "C" int bita_profile_read(int32_t capacity, int32_t *n_records, float *ms, int64_t *weight_bytes) {
+    if (!n_records || !ms || !weight_bytes) return bita_set_error(BITA_ERR_INVALID_ARG, "bita_profile_read: null");
+    int n = 0;
+    for (size_t i = 0; i < g_prof_used && n < capacity; i++, n++) {
+        BITA_HIP_CHECK(hipEventSynchronize(g_prof[i].stop));
+        BITA_HIP_CHECK(hipEventElapsedTime(&ms[n], g_prof[i].start, g_prof[i].stop));
+        weight_bytes[n] = g_prof[i].weight_bytes;
+    }
+    *n_records = n;
+    return BITA_OK;
+}
+static void timed_gemm(const void *a_hi, const void *a_lo, int M, int64_t K, int64_t lda, const void *w, int64_t N,
+                       float *out, int64_t ldo, const GemmPlan &p, hipStream_t s) {
+    GemmRecord *r = (g_prof_on && g_prof_used < g_prof.size()) ? &g_prof[g_prof_used++] : nullptr;
+    if (r) { r->weight_bytes = N * K * 2; (void)hipEventRecord(r->start, s); }
+    launch_gemm(a_hi, a_lo, M, K, lda, w, N, out, ldo, p, s);
+    if (r) (void)hipEventRecord(r->stop, s);
+}
+
+// ------------------------------------------------------------------------------------------
 struct WsLayout {
     size_t x, h, q, attn_out, act, partial, part_o, part_ml, logits, total;
     size_t partial_bytes;
@@ -294,7 +335,7 @@ extern "C" int bita_verify_step(bita_model *m, const bita_kv *kv, const bita_tre
     int pending = 0;                                    // split-K partials waiting to be added to x
     for (int l = 0; l < c.n_layers; l++) {
         launch_rmsnorm(x, partial, pending, M, d, m->attn_norm[l], c.rms_eps, h, h_lo, d, s);
-        launch_gemm(h, h_lo, M, d, d, m->wqkv[l], nqkv, partial, nqkv, p_qkv, s);
+        timed_gemm(h, h_lo, M, d, d, m->wqkv[l], nqkv, partial, nqkv, p_qkv, s);
         void *kt = (unsigned char *)kv->k_tree + l * kv_layer_tree, *vt = (unsigned char *)kv->v_tree + l * kv_layer_tree;
         launch_qkv_rope(partial, p_qkv.splits, batch, td, c.n_heads, c.n_kv_heads, hd, d_ctx_len, m->rope_cos,
                         m->rope_sin, c.max_pos, q, q_lo, kt, vt, s);
@@ -302,18 +343,18 @@ extern "C" int bita_verify_step(bita_model *m, const bita_kv *kv, const bita_tre
                               (unsigned char *)kv->v_cache + l * kv_layer_cache, kt, vt, m->prompt_k[l],
                               m->prompt_v[l], d_ctx_len, batch, c.n_heads, c.n_kv_heads, hd, c.n_prompt, kv->smax,
                               ap, part_o, part_ml, attn_out, attn_lo, s);
-        launch_gemm(attn_out, attn_lo, M, nq, nq, m->wo[l], d, partial, d, p_o, s);
+        timed_gemm(attn_out, attn_lo, M, nq, nq, m->wo[l], d, partial, d, p_o, s);
         launch_rmsnorm(x, partial, p_o.splits, M, d, m->ffn_norm[l], c.rms_eps, h, h_lo, d, s);
-        launch_gemm(h, h_lo, M, d, d, m->w_gate_up[l], 2 * (int64_t)c.d_ffn, partial, 2 * (int64_t)c.d_ffn, p_gu, s);
+        timed_gemm(h, h_lo, M, d, d, m->w_gate_up[l], 2 * (int64_t)c.d_ffn, partial, 2 * (int64_t)c.d_ffn, p_gu, s);
         launch_silu_mul(partial, p_gu.splits, M, c.d_ffn, act, act_lo, c.d_ffn, s);
-        launch_gemm(act, act_lo, M, c.d_ffn, c.d_ffn, m->w_down[l], d, partial, d, p_dn, s);
+        timed_gemm(act, act_lo, M, c.d_ffn, c.d_ffn, m->w_down[l], d, partial, d, p_dn, s);
         pending = p_dn.splits;
     }
     launch_rmsnorm(x, partial, pending, M, d, m->final_norm, c.rms_eps, h, h_lo, d, s);
     if (p_lm.splits == 1) {
-        launch_gemm(h, h_lo, M, d, d, m->lm_head, c.vocab, logits, c.vocab, p_lm, s);
+        timed_gemm(h, h_lo, M, d, d, m->lm_head, c.vocab, logits, c.vocab, p_lm, s);
     } else {
-        launch_gemm(h, h_lo, M, d, d, m->lm_head, c.vocab, partial, c.vocab, p_lm, s);
+        timed_gemm(h, h_lo, M, d, d, m->lm_head, c.vocab, partial, c.vocab, p_lm, s);
         launch_reduce_partials(partial, p_lm.splits, M, c.vocab, c.vocab, logits, s);
     }
     launch_select(logits, batch, td, c.vocab, kmax, d_argmax, n_sel_mask > 0 ? d_topk_ids : nullptr, d_topk_val, s);
