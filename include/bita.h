@@ -210,7 +210,7 @@ int bita_tree_attention(const bita_tree_template *t, const void *d_q, const void
  * transposed.  A = d_a (bf16, row stride lda) plus, if d_a_lo is not NULL, a second bf16
  * plane of the same shape holding the rounding residual (A = hi + lo), which is how
  * bita_verify_step feeds its activations.  d_ws needs bita_gemm_workspace_bytes(). */
-size_t bita_gemm_workspace_bytes(int32_t m_rows, int64_t n_rows);
+size_t bita_gemm_workspace_bytes(int32_t m_rows, int64_t n_rows, int64_t k);
 int bita_gemm(const void *d_a, const void *d_a_lo, int32_t m_rows, int64_t k, int64_t lda,
               const void *d_w_packed, int64_t n_rows, void *d_ws, size_t ws_bytes, float *d_out,
               void *stream);

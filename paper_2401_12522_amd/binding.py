@@ -76,7 +76,7 @@ def lib():
     L.bita_attention_workspace_bytes.argtypes = [i32] * 6
     L.bita_tree_attention.restype = C.c_int
     L.bita_tree_attention.argtypes = [vp] * 10 + [i32] * 7 + [vp, sz, vp, vp]
-    L.bita_gemm_workspace_bytes.restype, L.bita_gemm_workspace_bytes.argtypes = sz, [i32, i64]
+    L.bita_gemm_workspace_bytes.restype, L.bita_gemm_workspace_bytes.argtypes = sz, [i32, i64, i64]
     L.bita_gemm.restype, L.bita_gemm.argtypes = C.c_int, [vp, vp, i32, i64, i64, vp, i64, vp, sz, vp, vp]
     L.bita_tune_gemm.restype, L.bita_tune_gemm.argtypes = None, [i32, i32]
     L.bita_profile_enable.restype, L.bita_profile_enable.argtypes = C.c_int, [i32]
@@ -313,7 +313,7 @@ def gemm(a, w_packed, n_rows, k=None, a_lo=None):
     """a (and optionally a_lo, the residual plane): bf16 cuda [M][lda]; returns fp32 [M][n_rows]."""
     m, lda = a.shape
     k = lda if k is None else k
-    ws = torch.empty(lib().bita_gemm_workspace_bytes(m, n_rows), dtype=torch.uint8, device=a.device)
+    ws = torch.empty(lib().bita_gemm_workspace_bytes(m, n_rows, k), dtype=torch.uint8, device=a.device)
     out = torch.empty((m, n_rows), dtype=torch.float32, device=a.device)
     _check(lib().bita_gemm(_ptr(a), _ptr(a_lo), m, k, lda, _ptr(w_packed), n_rows, _ptr(ws), ws.numel(), _ptr(out), _stream()))
     return out

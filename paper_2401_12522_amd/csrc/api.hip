@@ -237,11 +237,11 @@ extern "C" int bita_profile_read(int32_t capacity, int32_t *n_records, float *ms
     *n_records = n;
     return BITA_OK;
 }
-static void timed_gemm(const void *a_hi, const void *a_lo, int M, int64_t K, int64_t lda, const void *w, int64_t N,
-                       float *out, int64_t ldo, const GemmPlan &p, hipStream_t s) {
+static void timed_gemm(const void *a_frag, int M, int64_t K, const void *w, int64_t N, float *out, int64_t ldo,
+                       const GemmPlan &p, hipStream_t s) {
     GemmRecord *r = (g_prof_on && g_prof_used < g_prof.size()) ? &g_prof[g_prof_used++] : nullptr;
     if (r) { r->weight_bytes = N * K * 2; (void)hipEventRecord(r->start, s); }
-    launch_gemm(a_hi, a_lo, M, K, lda, w, N, out, ldo, p, s);
+    launch_gemm(a_frag, true, M, K, w, N, out, ldo, p, s);
     if (r) (void)hipEventRecord(r->stop, s);
 }
 
@@ -259,11 +259,11 @@ static WsLayout ws_layout(const bita_config &c, int batch, int rows) {
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
     L.x = take(M * c.d_model * 4);
-    // bf16 activations are kept as two planes (hi, lo): [2][M][width]
-    L.h = take(2 * M * c.d_model * 2);
+    // GEMM inputs: two bf16 planes (hi, lo) in fragment order; queries: two row-major planes
+    L.h = take(frag_bytes((int)M, c.d_model));
     L.q = take(2 * M * nq * 2);
-    L.attn_out = take(2 * M * nq * 2);
-    L.act = take(2 * M * c.d_ffn * 2);
+    L.attn_out = take(frag_bytes((int)M, nq));
+    L.act = take(frag_bytes((int)M, c.d_ffn));
     size_t pb = 0;
     const int64_t shapes[5][2] = {{nqkv, c.d_model}, {c.d_model, nq}, {2 * (int64_t)c.d_ffn, c.d_model},
                                   {c.d_model, c.d_ffn}, {c.vocab, c.d_model}};
@@ -321,8 +321,7 @@ extern "C" int bita_verify_step(bita_model *m, const bita_kv *kv, const bita_tre
     float *logits = d_logits ? d_logits : (float *)(ws + L.logits);
     const int M = batch * td.rows, d = c.d_model, hd = c.head_dim;
     const int64_t nq = (int64_t)c.n_heads * hd, nqkv = (int64_t)(c.n_heads + 2 * c.n_kv_heads) * hd;
-    unsigned char *h_lo = h + (size_t)M * d * 2, *q_lo = q + (size_t)M * nq * 2;
-    unsigned char *attn_lo = attn_out + (size_t)M * nq * 2, *act_lo = act + (size_t)M * c.d_ffn * 2;
+    unsigned char *q_lo = q + (size_t)M * nq * 2;
     const GemmPlan p_qkv = gemm_plan(M, nqkv, d), p_o = gemm_plan(M, d, nq),
                    p_gu = gemm_plan(M, 2 * (int64_t)c.d_ffn, d), p_dn = gemm_plan(M, d, c.d_ffn),
                    p_lm = gemm_plan(M, c.vocab, d);
@@ -334,27 +333,27 @@ extern "C" int bita_verify_step(bita_model *m, const bita_kv *kv, const bita_tre
     launch_embed(d_token, td, batch, m->tok_emb, m->mask_emb, d, c.vocab, x, s);
     int pending = 0;                                    // split-K partials waiting to be added to x
     for (int l = 0; l < c.n_layers; l++) {
-        launch_rmsnorm(x, partial, pending, M, d, m->attn_norm[l], c.rms_eps, h, h_lo, d, s);
-        timed_gemm(h, h_lo, M, d, d, m->wqkv[l], nqkv, partial, nqkv, p_qkv, s);
+        launch_rmsnorm(x, partial, pending, M, d, m->attn_norm[l], c.rms_eps, h, s);
+        timed_gemm(h, M, d, m->wqkv[l], nqkv, partial, nqkv, p_qkv, s);
         void *kt = (unsigned char *)kv->k_tree + l * kv_layer_tree, *vt = (unsigned char *)kv->v_tree + l * kv_layer_tree;
         launch_qkv_rope(partial, p_qkv.splits, batch, td, c.n_heads, c.n_kv_heads, hd, d_ctx_len, m->rope_cos,
                         m->rope_sin, c.max_pos, q, q_lo, kt, vt, s);
         launch_tree_attention(td, q, q_lo, (unsigned char *)kv->k_cache + l * kv_layer_cache,
                               (unsigned char *)kv->v_cache + l * kv_layer_cache, kt, vt, m->prompt_k[l],
                               m->prompt_v[l], d_ctx_len, batch, c.n_heads, c.n_kv_heads, hd, c.n_prompt, kv->smax,
-                              ap, part_o, part_ml, attn_out, attn_lo, s);
-        timed_gemm(attn_out, attn_lo, M, nq, nq, m->wo[l], d, partial, d, p_o, s);
-        launch_rmsnorm(x, partial, p_o.splits, M, d, m->ffn_norm[l], c.rms_eps, h, h_lo, d, s);
-        timed_gemm(h, h_lo, M, d, d, m->w_gate_up[l], 2 * (int64_t)c.d_ffn, partial, 2 * (int64_t)c.d_ffn, p_gu, s);
-        launch_silu_mul(partial, p_gu.splits, M, c.d_ffn, act, act_lo, c.d_ffn, s);
-        timed_gemm(act, act_lo, M, c.d_ffn, c.d_ffn, m->w_down[l], d, partial, d, p_dn, s);
+                              ap, part_o, part_ml, attn_out, true, s);
+        timed_gemm(attn_out, M, nq, m->wo[l], d, partial, d, p_o, s);
+        launch_rmsnorm(x, partial, p_o.splits, M, d, m->ffn_norm[l], c.rms_eps, h, s);
+        timed_gemm(h, M, d, m->w_gate_up[l], 2 * (int64_t)c.d_ffn, partial, 2 * (int64_t)c.d_ffn, p_gu, s);
+        launch_silu_mul(partial, p_gu.splits, M, c.d_ffn, act, s);
+        timed_gemm(act, M, c.d_ffn, m->w_down[l], d, partial, d, p_dn, s);
         pending = p_dn.splits;
     }
-    launch_rmsnorm(x, partial, pending, M, d, m->final_norm, c.rms_eps, h, h_lo, d, s);
+    launch_rmsnorm(x, partial, pending, M, d, m->final_norm, c.rms_eps, h, s);
     if (p_lm.splits == 1) {
-        timed_gemm(h, h_lo, M, d, d, m->lm_head, c.vocab, logits, c.vocab, p_lm, s);
+        timed_gemm(h, M, d, m->lm_head, c.vocab, logits, c.vocab, p_lm, s);
     } else {
-        timed_gemm(h, h_lo, M, d, d, m->lm_head, c.vocab, partial, c.vocab, p_lm, s);
+        timed_gemm(h, M, d, m->lm_head, c.vocab, partial, c.vocab, p_lm, s);
         launch_reduce_partials(partial, p_lm.splits, M, c.vocab, c.vocab, logits, s);
     }
     launch_select(logits, batch, td, c.vocab, kmax, d_argmax, n_sel_mask > 0 ? d_topk_ids : nullptr, d_topk_val, s);
@@ -411,16 +410,17 @@ extern "C" int bita_tree_attention(const bita_tree_template *t, const void *d_q,
     float *part_o = (float *)d_ws, *part_ml = (float *)((unsigned char *)d_ws + align_up(p.part_o_bytes, 256));
     launch_tree_attention(t->dev, d_q, d_q_lo, d_k_cache, d_v_cache, d_k_tree, d_v_tree, d_prompt_k, d_prompt_v, d_ctx_len,
                           batch, n_heads, n_kv_heads, head_dim, n_prompt, smax, p, part_o, part_ml, d_out,
-                          nullptr, (hipStream_t)stream);
+                          false, (hipStream_t)stream);
     BITA_HIP_CHECK(hipGetLastError());
     return BITA_OK;
 }
 
 extern "C" void bita_tune_gemm(int32_t variant, int32_t splits) { gemm_force_plan(variant, splits); }
 
-extern "C" size_t bita_gemm_workspace_bytes(int32_t m_rows, int64_t n_rows) {
-    if (m_rows <= 0 || n_rows <= 0) return 0;
-    return (size_t)16 * m_rows * n_rows * 4;              // split-K never exceeds 16
+extern "C" size_t bita_gemm_workspace_bytes(int32_t m_rows, int64_t n_rows, int64_t k) {
+    if (m_rows <= 0 || n_rows <= 0 || k <= 0) return 0;
+    // split-K partials (never more than 32 splits) + the activations re-laid in fragment order
+    return align_up((size_t)32 * m_rows * n_rows * 4, 256) + frag_bytes(m_rows, k);
 }
 
 extern "C" int bita_gemm(const void *d_a, const void *d_a_lo, int32_t m_rows, int64_t k, int64_t lda,
@@ -431,13 +431,16 @@ extern "C" int bita_gemm(const void *d_a, const void *d_a_lo, int32_t m_rows, in
     if (n_rows % 16 || k % 8 || lda % 8)
         return bita_set_error(BITA_ERR_UNSUPPORTED, "bita_gemm: n_rows must be a multiple of 16, k and lda of 8");
     const GemmPlan p = gemm_plan(m_rows, n_rows, k);
-    if (ws_bytes < (size_t)p.splits * m_rows * n_rows * 4)
+    const size_t part_bytes = align_up((size_t)p.splits * m_rows * n_rows * 4, 256);
+    if (ws_bytes < part_bytes + frag_bytes(m_rows, k))
         return bita_set_error(BITA_ERR_CAPACITY, "bita_gemm: workspace too small");
     hipStream_t s = (hipStream_t)stream;
+    void *frag = (unsigned char *)d_ws + part_bytes;
+    launch_to_fragments(d_a, d_a_lo, m_rows, k, lda, frag, s);
     if (p.splits == 1) {
-        launch_gemm(d_a, d_a_lo, m_rows, k, lda, d_w_packed, n_rows, d_out, n_rows, p, s);
+        launch_gemm(frag, d_a_lo != nullptr, m_rows, k, d_w_packed, n_rows, d_out, n_rows, p, s);
     } else {
-        launch_gemm(d_a, d_a_lo, m_rows, k, lda, d_w_packed, n_rows, (float *)d_ws, n_rows, p, s);
+        launch_gemm(frag, d_a_lo != nullptr, m_rows, k, d_w_packed, n_rows, (float *)d_ws, n_rows, p, s);
         launch_reduce_partials((const float *)d_ws, p.splits, m_rows, n_rows, n_rows, d_out, s);
     }
     BITA_HIP_CHECK(hipGetLastError());

@@ -342,7 +342,7 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void tree_attn_kernel(
 // out[b][r][h*HD + i] = sum_s w_s O_s[i] / sum_s w_s l_s,  w_s = 2^(m_s - max m)
 __global__ void attn_merge_kernel(const float *__restrict__ part_o, const float *__restrict__ part_ml,
                                   int R, int Hq, int HD, int n_splits, uint16_t *__restrict__ out,
-                                  uint16_t *__restrict__ out_lo) {
+                                  int as_fragments, int m_tiles) {
     const int r = blockIdx.x, h = blockIdx.y, b = blockIdx.z, i = threadIdx.x;
     const int64_t pbase = ((int64_t)b * Hq + h) * n_splits;
     float m = -INFINITY;
@@ -356,8 +356,13 @@ __global__ void attn_merge_kernel(const float *__restrict__ part_o, const float 
     }
     uint16_t hi, lo;
     split_bf16(l > 0.f ? acc / l : 0.f, hi, lo);
-    out[(((int64_t)b * R + r) * Hq + h) * HD + i] = hi;
-    if (out_lo) out_lo[(((int64_t)b * R + r) * Hq + h) * HD + i] = lo;
+    if (as_fragments) {                     // two planes, the O-projection's activation slab
+        const int m = b * R + r, k = h * HD + i, n_ksteps = (Hq * HD) >> 5;
+        out[frag_index(0, m, k, n_ksteps, m_tiles)] = hi;
+        out[frag_index(1, m, k, n_ksteps, m_tiles)] = lo;
+    } else {
+        out[(((int64_t)b * R + r) * Hq + h) * HD + i] = hi;
+    }
 }
 
 AttnPlan attn_plan(int batch, int rows, int n_heads, int hd, int ctx_hint, int n_prompt) {
@@ -402,7 +407,7 @@ void launch_tree_attention(const TemplateDev &t, const void *q, const void *q_lo
                            const void *k_tree, const void *v_tree, const void *prompt_k,
                            const void *prompt_v, const int32_t *ctx_len, int batch, int Hq, int Hkv, int hd,
                            int P, int smax, const AttnPlan &p, float *part_o, float *part_ml, void *out,
-                           void *out_lo, hipStream_t s) {
+                           bool out_as_fragments, hipStream_t s) {
     const bool small = t.rows <= 16;
     if (hd == 128) {
         if (small) launch_attn_t<128, 1>(t, q, q_lo, k_cache, v_cache, k_tree, v_tree, prompt_k, prompt_v, ctx_len, batch, Hq, Hkv, P, smax, p, part_o, part_ml, s);
@@ -412,5 +417,5 @@ void launch_tree_attention(const TemplateDev &t, const void *q, const void *q_lo
         else launch_attn_t<64, 5>(t, q, q_lo, k_cache, v_cache, k_tree, v_tree, prompt_k, prompt_v, ctx_len, batch, Hq, Hkv, P, smax, p, part_o, part_ml, s);
     }
     hipLaunchKernelGGL(attn_merge_kernel, dim3(t.rows, Hq, batch), dim3(hd), 0, s, part_o, part_ml, t.rows,
-                       Hq, hd, p.splits, (uint16_t *)out, (uint16_t *)out_lo);
+                       Hq, hd, p.splits, (uint16_t *)out, out_as_fragments ? 1 : 0, (batch * t.rows + 15) / 16);
 }

@@ -22,6 +22,13 @@ __device__ __forceinline__ void split_bf16(float x, uint16_t &hi, uint16_t &lo) 
     hi = f32_to_bf16(x);
     lo = f32_to_bf16(x - bf16_to_f32(hi));
 }
+// Position (in bf16 elements) of A[m][k] of plane p inside an activation slab kept in MFMA
+// A-operand fragment order: 1 KiB per (plane, k-step of 32, m-tile of 16), lane l of a
+// fragment holding A[16mt + l%16][32ks + 8(l/16) .. +8].
+__device__ __forceinline__ int64_t frag_index(int plane, int m, int k, int n_ksteps, int m_tiles) {
+    const int ks = k >> 5, kq = (k >> 3) & 3, e = k & 7;
+    return ((((int64_t)plane * n_ksteps + ks) * m_tiles + (m >> 4)) * 64 + kq * 16 + (m & 15)) * 8 + e;
+}
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
     return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
 }
@@ -56,11 +63,12 @@ struct bita_tree_template {
 struct GemmPlan { int splits, ksteps_per_split, variant; };
 void gemm_force_plan(int variant, int splits);   // tuning aid: < 0 restores the heuristic
 GemmPlan gemm_plan(int m_rows, int64_t n_rows, int64_t k);
-// out_partial: [splits][m_rows][ldo] fp32
-// a_lo may be null (single bf16 plane)
-void launch_gemm(const void *a_hi, const void *a_lo, int m_rows, int64_t k, int64_t lda,
-                 const void *w_packed, int64_t n_rows, float *out_partial, int64_t ldo,
-                 const GemmPlan &p, hipStream_t s);
+size_t frag_bytes(int m_rows, int64_t k);        // bytes of a two-plane activation slab
+// a_frag: activations in fragment order (see frag_index); out_partial: [splits][m_rows][ldo] fp32
+void launch_gemm(const void *a_frag, bool two_planes, int m_rows, int64_t k, const void *w_packed,
+                 int64_t n_rows, float *out_partial, int64_t ldo, const GemmPlan &p, hipStream_t s);
+void launch_to_fragments(const void *a_hi, const void *a_lo, int m_rows, int64_t k, int64_t lda, void *dst,
+                         hipStream_t s);
 void launch_reduce_partials(const float *partial, int splits, int m_rows, int64_t n, int64_t ld,
                             float *out, hipStream_t s);
 void launch_pack(const void *src, int64_t n_rows, int64_t k, void *dst, int64_t tile0,
@@ -69,14 +77,15 @@ void launch_pack(const void *src, int64_t n_rows, int64_t k, void *dst, int64_t 
 void launch_embed(const int32_t *token, const TemplateDev &t, int batch, const void *tok_emb,
                   const void *mask_emb, int d, int vocab, float *x, hipStream_t s);
 // x += sum of partials (optional), then h = rmsnorm(x) * gain as bf16 with row stride ldh
+// h: two-plane activation slab in fragment order
 void launch_rmsnorm(float *x, const float *partial, int splits, int m_rows, int d,
-                    const void *gain, float eps, void *h_hi, void *h_lo, int64_t ldh, hipStream_t s);
+                    const void *gain, float eps, void *h_frag, hipStream_t s);
 void launch_qkv_rope(const float *partial, int splits, int batch, const TemplateDev &t,
                      int n_heads, int n_kv_heads, int hd, const int32_t *ctx_len,
                      const float *rope_cos, const float *rope_sin, int max_pos,
                      void *q, void *q_lo, void *k_tree, void *v_tree, hipStream_t s);
-void launch_silu_mul(const float *partial, int splits, int m_rows, int d_ffn, void *act,
-                     void *act_lo, int64_t ld_act, hipStream_t s);
+void launch_silu_mul(const float *partial, int splits, int m_rows, int d_ffn, void *act_frag,
+                     hipStream_t s);
 void launch_select(const float *logits, int batch, const TemplateDev &t, int vocab, int kmax,
                    int32_t *argmax, int32_t *topk_ids, float *topk_val, hipStream_t s);
 
@@ -87,4 +96,4 @@ void launch_tree_attention(const TemplateDev &t, const void *q, const void *q_lo
                            const void *prompt_k, const void *prompt_v, const int32_t *ctx_len,
                            int batch, int n_heads, int n_kv_heads, int hd, int n_prompt, int smax,
                            const AttnPlan &p, float *part_o, float *part_ml, void *out,
-                           void *out_lo, hipStream_t s);
+                           bool out_as_fragments, hipStream_t s);

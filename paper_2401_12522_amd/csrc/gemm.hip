@@ -11,10 +11,12 @@
 //    Waves that run side by side work on neighbouring tiles of the same k range, so what
 //    the chip reads at any moment is one contiguous region (as in a plain copy), instead of
 //    thousands of streams a power-of-two stride apart that would pile onto few HBM channels.
-//  * The activation slab is small and shared by every wave.  It is brought into LDS with
-//    direct global->LDS loads, one 1 KiB A-operand fragment per instruction, so the LDS
-//    image is already in fragment order (conflict-free linear reads) and no VGPRs are spent
-//    on staging.
+//  * The activation slab is small and shared by every wave.  Producers write it to global
+//    memory already in A-operand fragment order (1 KiB per (plane, k-step, m-tile): lane l
+//    holds A[16mt + l%16][32ks + 8(l/16) .. +8]), so one direct global->LDS load per
+//    fragment reads 1 KiB contiguous, lands in LDS in operand order (conflict-free linear
+//    reads) and spends no VGPRs on staging.  Each fragment read from LDS feeds NW weight
+//    tiles; with two planes the slab traffic from L2 is what limits narrow NW.
 //  * Activations may come as two bf16 planes (hi = bf16(x), lo = bf16(x - hi)); both are
 //    multiplied with the same weight fragment.  That removes the activation rounding from
 //    the error budget at the price of 2x MFMA work, which the kernel has to spare (at 68
@@ -69,18 +71,14 @@ struct GemmCfg {
     static constexpr int NFRAG = PL * MT * KC;                  // A fragments per stage
     static constexpr int FPW = (NFRAG + WAVES - 1) / WAVES;     // fetched per wave per stage
     static constexpr int SLOT_FRAGS = FPW * WAVES;              // incl. padding fragments
-#ifdef GEMM_EXP_NO_A
-    static constexpr int LOADS = NW * KC;
-#else
-    static constexpr int LOADS = NW * KC + FPW;                 // VMEM ops per wave per stage
-#endif
+    static constexpr int LOADS = NW * KC + FPW;                 // vector-memory loads per wave per stage
     static constexpr int SMEM = D * SLOT_FRAGS * 1024;
     static_assert((D - 2) * LOADS < 64, "vmcnt counter range");
 };
 
 template <int MT, int NW, bool SPLIT, int KC, int D, int WAVES>
 __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
-    const uint16_t *__restrict__ A_hi, const uint16_t *__restrict__ A_lo, int M, int K, int64_t lda,
+    const uint4 *__restrict__ A_frag, int planes_stride_f, int M, int m_tiles,
     const uint4 *__restrict__ Wp, int NT, int KS, float *__restrict__ out, int64_t ldo,
     int ksteps_per_split) {
     using C = GemmCfg<MT, NW, SPLIT, KC, D, WAVES>;
@@ -92,6 +90,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
     const int ks_end = min(KS, ks_begin + ksteps_per_split);
     const int m_base = blockIdx.z * (MT * 16);
     const int n_stages = (ks_end - ks_begin + KC - 1) / KC;
+    (void)M;
 
     f32x4 acc[MT][NW];
 #pragma unroll
@@ -100,7 +99,6 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
         for (int j = 0; j < NW; j++) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     uint4 w[D][NW][KC];
-    const int a_row = lane & 15, a_kq = lane >> 4;
 
     // Issue all loads of pipeline stage `stage` into ring slot SLOT: NW*KC weight fragments to
     // registers and this wave's FPW activation fragments to LDS.  Every wave issues exactly
@@ -117,21 +115,19 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
                 const uint4 *p = ok ? Wp + packed_block(t, ks, NT) * 64 + lane : &g_zero16;
                 w[SLOT][j][s] = *p;
             }
-#ifndef GEMM_EXP_NO_A
 #pragma unroll
         for (int i = 0; i < C::FPW; i++) {
             const int f = i * WAVES + wave;                       // fragment id inside the stage
             const int plane = f / (MT * KC), mt = (f / KC) % MT, s = f % KC;
-            const int m = m_base + mt * 16 + a_row;
-            const int k = (ks0 + s) * 32 + a_kq * 8;
-            const bool ok = (f < C::NFRAG) && (m < M) && (k < K) && (ks0 + s < ks_end);
-            const uint16_t *base = (SPLIT && plane == 1) ? A_lo : A_hi;
-            const void *src = ok ? (const void *)(base + (int64_t)m * lda + k) : (const void *)&g_zero16;
+            const int mtg = blockIdx.z * MT + mt;                 // m-tile in the whole slab
+            const bool ok = (f < C::NFRAG) && (mtg < m_tiles) && (ks0 + s < ks_end);
+            // fragment (plane, ks, mtg) starts at ((plane * KS + ks) * m_tiles + mtg) * 64 uint4
+            const uint4 *src = ok ? A_frag + ((int64_t)plane * planes_stride_f + (int64_t)(ks0 + s) * m_tiles + mtg) * 64 + lane
+                                  : &g_zero16;
             uint4 *dst = a_lds + ((SLOT * C::SLOT_FRAGS + f) * 64);   // wave-uniform; lane l lands at dst[l]
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
                                              (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
         }
-#endif
     };
     auto compute = [&](auto slot_c, int stage) {
         constexpr int SLOT = decltype(slot_c)::value;
@@ -147,12 +143,8 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
                     const bf16x8 a = __builtin_bit_cast(bf16x8, a_lds[(SLOT * C::SLOT_FRAGS + f) * 64 + lane]);
 #pragma unroll
                     for (int j = 0; j < NW; j++)
-#ifdef GEMM_EXP_NO_MFMA
-                    { if (pl == 0 && i == 0) { acc[i][j][0] += __uint_as_float(w[SLOT][j][s].x ^ w[SLOT][j][s].y ^ w[SLOT][j][s].z ^ w[SLOT][j][s].w); } (void)a; }
-#else
                         acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
                             a, __builtin_bit_cast(bf16x8, w[SLOT][j][s]), acc[i][j], 0, 0, 0);
-#endif
                 }
         }
     };
@@ -167,9 +159,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
             constexpr int J = decltype(j_c)::value;
             if (newer == J) wait_vmcnt<J * C::LOADS>();
         });
-#ifndef GEMM_EXP_NO_BARRIER
         wg_barrier();
-#endif
         if (c + D - 1 < n_stages) issue(std::integral_constant<int, PRE>{}, c + D - 1);
         compute(u_c, c);
     };
@@ -226,40 +216,54 @@ __global__ void pack_weight_kernel(const uint16_t *__restrict__ src, int64_t N, 
     dst[packed_block(tile0 + t * tile_stride, s, total_tiles) * 64 + lane] = v;
 }
 
-// Launch shapes.  variant: 0 = 4 waves x 1 tile, 1 = 4 waves x 2 tiles, 2 = 4 waves x 4 tiles,
-// 3 = 8 waves x 2 tiles (rows per workgroup: 64, 128, 256, 256).
-static const int kVariantWaves[] = {4, 4, 4, 8, 4, 4, 8, 8, 4, 8};
-static const int kVariantNw[] = {1, 2, 4, 2, 2, 2, 1, 2, 4, 1};
-#define GEMM_N_VARIANTS 10
-#define GEMM_RING_KC 2
+// Row-major bf16 planes -> A-operand fragment order (used by the stand-alone GEMM entry point;
+// inside the verify step the producing kernels write this layout directly).
+__global__ void to_fragments_kernel(const uint16_t *__restrict__ a_hi, const uint16_t *__restrict__ a_lo, int M,
+                                    int K, int64_t lda, int KS, int m_tiles, uint4 *__restrict__ dst) {
+    const int ks = blockIdx.x, mt = blockIdx.y, plane = blockIdx.z, lane = threadIdx.x;
+    const uint16_t *src = plane ? a_lo : a_hi;
+    const int m = mt * 16 + (lane & 15), k = ks * 32 + (lane >> 4) * 8;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (src && m < M && k < K) v = *reinterpret_cast<const uint4 *>(src + (int64_t)m * lda + k);
+    dst[(((int64_t)plane * KS + ks) * m_tiles + mt) * 64 + lane] = v;
+}
+
+// Launch shapes: variant v -> NW = 1 << v weight tiles per wave (64, 128, 256 columns per
+// workgroup of 4 waves), one k-step per stage, ring of 4.  Wide groups reuse each activation
+// fragment for more weight tiles (the L2->LDS slab traffic is what limits narrow ones) but
+// produce wider split-K partials, so narrow matrices take the narrower shapes.
+#define GEMM_N_VARIANTS 3
 static int g_force_variant = -1, g_force_splits = -1;
 void gemm_force_plan(int variant, int splits) { g_force_variant = variant; g_force_splits = splits; }
 
 GemmPlan gemm_plan(int m_rows, int64_t n_rows, int64_t k) {
     GemmPlan p;
     const int64_t NT = n_rows / 16, KS = (k + 31) / 32;
-    p.variant = (NT >= 512) ? 1 : 0;
+    // Shapes measured on MI355X at 68 rows: 256-column workgroups for wide matrices, 128 for
+    // narrow ones; as many splits as give one round of <= 512 equal workgroups, but no more
+    // than 8 for the narrow ones, whose partial sums are re-read by a row-wise consumer.
+    p.variant = (NT >= 1024) ? 2 : 1;
     if (g_force_variant >= 0 && g_force_variant < GEMM_N_VARIANTS) p.variant = g_force_variant;
-    const int tiles_wg = kVariantWaves[p.variant] * kVariantNw[p.variant];
+    const int tiles_wg = 4 << p.variant;
     const int64_t wgs_n = (NT + tiles_wg - 1) / tiles_wg;
-    // two workgroups are resident per CU: aim at one full round of 512 workgroups
     int64_t splits = 512 / wgs_n;
-    const int64_t max_splits = KS / (4 * GEMM_RING_KC);       // at least 4 stages per split
+    const int64_t max_splits = KS / 8;                          // at least 8 stages per split
     if (splits > max_splits) splits = max_splits;
-    if (splits > 16) splits = 16;
+    if (NT < 512 && splits > 8) splits = 8;
+    if (splits > 32) splits = 32;
     if (g_force_splits > 0) splits = g_force_splits;
     if (splits < 1) splits = 1;
-    int64_t per = (KS + splits - 1) / splits;
-    per = (per + GEMM_RING_KC - 1) / GEMM_RING_KC * GEMM_RING_KC;   // whole stages
+    const int64_t per = (KS + splits - 1) / splits;
     p.ksteps_per_split = (int)per;
     p.splits = (int)((KS + per - 1) / per);
     (void)m_rows;
     return p;
 }
 
-template <int MT, int NW, bool SPLIT, int KC, int D, int WAVES>
-static void launch_gemm_t(const void *a_hi, const void *a_lo, int M, int64_t K, int64_t lda, const void *w,
-                          int64_t N, float *out, int64_t ldo, const GemmPlan &p, hipStream_t s) {
+template <int MT, int NW, bool SPLIT>
+static void launch_gemm_t(const void *a_frag, int M, int64_t K, const void *w, int64_t N, float *out, int64_t ldo,
+                          const GemmPlan &p, hipStream_t s) {
+    constexpr int KC = 1, D = 4, WAVES = 4;
     using C = GemmCfg<MT, NW, SPLIT, KC, D, WAVES>;
     static bool attr_set = false;
     if (!attr_set) {
@@ -267,40 +271,45 @@ static void launch_gemm_t(const void *a_hi, const void *a_lo, int M, int64_t K, 
                                   hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM);
         attr_set = true;
     }
-    const int NT = (int)(N / 16), KS = (int)((K + 31) / 32);
-    dim3 grid((NT + WAVES * NW - 1) / (WAVES * NW), p.splits, (M + MT * 16 - 1) / (MT * 16));
+    const int NT = (int)(N / 16), KS = (int)((K + 31) / 32), m_tiles = (M + 15) / 16;
+    dim3 grid((NT + WAVES * NW - 1) / (WAVES * NW), p.splits, (m_tiles + MT - 1) / MT);
     hipLaunchKernelGGL((gemm_skinny_kernel<MT, NW, SPLIT, KC, D, WAVES>), grid, dim3(WAVES * 64), C::SMEM, s,
-                       (const uint16_t *)a_hi, (const uint16_t *)a_lo, M, (int)K, lda, (const uint4 *)w, NT,
-                       KS, out, ldo, p.ksteps_per_split);
+                       (const uint4 *)a_frag, KS * m_tiles, M, m_tiles, (const uint4 *)w, NT, KS, out, ldo,
+                       p.ksteps_per_split);
 }
 
 template <int MT, bool SPLIT>
-static void launch_gemm_v(const void *a_hi, const void *a_lo, int M, int64_t K, int64_t lda, const void *w,
-                          int64_t N, float *out, int64_t ldo, const GemmPlan &p, hipStream_t s) {
-    constexpr int KC = GEMM_RING_KC;
+static void launch_gemm_v(const void *a_frag, int M, int64_t K, const void *w, int64_t N, float *out, int64_t ldo,
+                          const GemmPlan &p, hipStream_t s) {
     switch (p.variant) {
-        case 0: launch_gemm_t<MT, 1, SPLIT, KC, 4, 4>(a_hi, a_lo, M, K, lda, w, N, out, ldo, p, s); break;
-        case 1: launch_gemm_t<MT, 2, SPLIT, KC, 3, 4>(a_hi, a_lo, M, K, lda, w, N, out, ldo, p, s); break;
-        case 2: launch_gemm_t<MT, 4, SPLIT, KC, 3, 4>(a_hi, a_lo, M, K, lda, w, N, out, ldo, p, s); break;
-        case 3: launch_gemm_t<MT, 2, SPLIT, KC, 3, 8>(a_hi, a_lo, M, K, lda, w, N, out, ldo, p, s); break;
-        case 4: launch_gemm_t<MT, 2, SPLIT, KC, 4, 4>(a_hi, a_lo, M, K, lda, w, N, out, ldo, p, s); break;
-        case 5: launch_gemm_t<MT, 2, SPLIT, KC, 5, 4>(a_hi, a_lo, M, K, lda, w, N, out, ldo, p, s); break;
-        case 6: launch_gemm_t<MT, 1, SPLIT, KC, 4, 8>(a_hi, a_lo, M, K, lda, w, N, out, ldo, p, s); break;
-        case 7: launch_gemm_t<MT, 2, SPLIT, KC, 4, 8>(a_hi, a_lo, M, K, lda, w, N, out, ldo, p, s); break;
-        case 8: launch_gemm_t<MT, 4, SPLIT, KC, 4, 4>(a_hi, a_lo, M, K, lda, w, N, out, ldo, p, s); break;
-        default: launch_gemm_t<MT, 1, SPLIT, KC, 6, 8>(a_hi, a_lo, M, K, lda, w, N, out, ldo, p, s); break;
+        case 0: launch_gemm_t<MT, 1, SPLIT>(a_frag, M, K, w, N, out, ldo, p, s); break;
+        case 1: launch_gemm_t<MT, 2, SPLIT>(a_frag, M, K, w, N, out, ldo, p, s); break;
+        default: launch_gemm_t<MT, 4, SPLIT>(a_frag, M, K, w, N, out, ldo, p, s); break;
     }
 }
 
-void launch_gemm(const void *a_hi, const void *a_lo, int M, int64_t K, int64_t lda, const void *w, int64_t N,
+// a_frag: activations in fragment order, [planes][k-steps][m-tiles][64] x 16 bytes;
+// out_partial: [splits][M][ldo] fp32.
+void launch_gemm(const void *a_frag, bool two_planes, int M, int64_t K, const void *w, int64_t N,
                  float *out, int64_t ldo, const GemmPlan &p, hipStream_t s) {
     if (M <= 16) {
-        if (a_lo) launch_gemm_v<1, true>(a_hi, a_lo, M, K, lda, w, N, out, ldo, p, s);
-        else launch_gemm_v<1, false>(a_hi, nullptr, M, K, lda, w, N, out, ldo, p, s);
+        if (two_planes) launch_gemm_v<1, true>(a_frag, M, K, w, N, out, ldo, p, s);
+        else launch_gemm_v<1, false>(a_frag, M, K, w, N, out, ldo, p, s);
     } else {
-        if (a_lo) launch_gemm_v<5, true>(a_hi, a_lo, M, K, lda, w, N, out, ldo, p, s);
-        else launch_gemm_v<5, false>(a_hi, nullptr, M, K, lda, w, N, out, ldo, p, s);
+        if (two_planes) launch_gemm_v<5, true>(a_frag, M, K, w, N, out, ldo, p, s);
+        else launch_gemm_v<5, false>(a_frag, M, K, w, N, out, ldo, p, s);
     }
+}
+
+size_t frag_bytes(int m_rows, int64_t k) {                     // two planes
+    return (size_t)2 * ((k + 31) / 32) * ((m_rows + 15) / 16) * 1024;
+}
+
+void launch_to_fragments(const void *a_hi, const void *a_lo, int M, int64_t K, int64_t lda, void *dst,
+                         hipStream_t s) {
+    const int KS = (int)((K + 31) / 32), m_tiles = (M + 15) / 16;
+    hipLaunchKernelGGL(to_fragments_kernel, dim3(KS, m_tiles, 2), dim3(64), 0, s, (const uint16_t *)a_hi,
+                       (const uint16_t *)a_lo, M, (int)K, lda, KS, m_tiles, (uint4 *)dst);
 }
 
 void launch_reduce_partials(const float *partial, int splits, int M, int64_t N, int64_t ld,

@@ -28,17 +28,17 @@ __device__ __forceinline__ float wave_sum(float v) {
 }
 
 // One workgroup per row: x += sum_s partial[s] (fixed order), h = x * rsqrt(mean(x^2)+eps) * g,
-// written as two bf16 planes (hi = bf16(h), lo = bf16(h - hi)) so that the following GEMM sees
-// the activation to ~16 mantissa bits.  Each thread owns float4 columns tid, tid+256, ...; all
+// written as two bf16 planes (hi = bf16(h), lo = bf16(h - hi)) in the GEMM's fragment order, so
+// that the following GEMM sees the activation to ~16 mantissa bits.  Each thread owns float4 columns tid, tid+256, ...; all
 // loads of a column are independent and issued together.
 #define RMS_MAX_V4 8      // d_model <= 8192 is kept in registers, larger rows are re-read
 __global__ __launch_bounds__(256) void rmsnorm_kernel(float *__restrict__ x, const float *__restrict__ partial,
                                                       int splits, int M, int d,
                                                       const uint16_t *__restrict__ gain, float eps,
-                                                      uint16_t *__restrict__ h_hi, uint16_t *__restrict__ h_lo,
-                                                      int64_t ldh) {
+                                                      uint16_t *__restrict__ h_frag) {
     __shared__ float red[4];
     const int row = blockIdx.x, tid = threadIdx.x;
+    const int n_ksteps = (d + 31) >> 5, m_tiles = (M + 15) >> 4;
     const int nv = d >> 2;                                   // float4 columns (d % 4 == 0)
     float4 *xr = reinterpret_cast<float4 *>(x + (int64_t)row * d);
     float4 keep[RMS_MAX_V4];
@@ -82,8 +82,8 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(float *__restrict__ x, con
         uint2 ph, pl;
         ph.x = hi[0] | ((uint32_t)hi[1] << 16); ph.y = hi[2] | ((uint32_t)hi[3] << 16);
         pl.x = lo[0] | ((uint32_t)lo[1] << 16); pl.y = lo[2] | ((uint32_t)lo[3] << 16);
-        reinterpret_cast<uint2 *>(h_hi + (int64_t)row * ldh)[c] = ph;
-        reinterpret_cast<uint2 *>(h_lo + (int64_t)row * ldh)[c] = pl;
+        *reinterpret_cast<uint2 *>(h_frag + frag_index(0, row, 4 * c, n_ksteps, m_tiles)) = ph;
+        *reinterpret_cast<uint2 *>(h_frag + frag_index(1, row, 4 * c, n_ksteps, m_tiles)) = pl;
     };
 #pragma unroll
     for (int it = 0; it < RMS_MAX_V4; it++) {
@@ -143,27 +143,44 @@ __global__ __launch_bounds__(64) void qkv_rope_kernel(
 }
 
 // ---------------------------------------------------------------------------------------
-// SwiGLU gating on the gate/up GEMM output whose 16-column tiles alternate gate, up.
+// SwiGLU gating on the gate/up GEMM output whose 16-column tiles alternate gate, up.  One
+// thread per 8 consecutive features: sums the split-K partials, writes both bf16 planes of
+// silu(gate) * up as one 16-byte store each into the down-projection's activation slab
+// (fragment order; features beyond d_ffn inside the last k-step are written as zeros).
 __global__ void silu_mul_kernel(const float *__restrict__ partial, int splits, int M, int F,
-                                uint16_t *__restrict__ act, uint16_t *__restrict__ act_lo, int64_t ld_act) {
-    const int f = blockIdx.x * blockDim.x + threadIdx.x;
+                                uint16_t *__restrict__ act_frag) {
+    const int f8 = blockIdx.x * blockDim.x + threadIdx.x;
     const int row = blockIdx.y;
-    if (f >= ld_act) return;
-    float out = 0.f;
+    const int n_ksteps = (F + 31) >> 5, m_tiles = (M + 15) >> 4;
+    const int f = f8 * 8;
+    if (f >= n_ksteps * 32) return;
+    float o[8];
+#pragma unroll
+    for (int e = 0; e < 8; e++) o[e] = 0.f;
     if (f < F) {
-        const int64_t cg = (int64_t)(f >> 4) * 32 + (f & 15), cu = cg + 16;
-        float gsum = 0.f, usum = 0.f;
+        const int64_t cg = (int64_t)(f >> 4) * 32 + (f & 15);
+        float g[8], u[8];
+#pragma unroll
+        for (int e = 0; e < 8; e++) g[e] = u[e] = 0.f;
         for (int s = 0; s < splits; s++) {
-            const float *p = partial + ((int64_t)s * M + row) * (2 * (int64_t)F);
-            gsum += p[cg];
-            usum += p[cu];
+            const float4 *p = reinterpret_cast<const float4 *>(partial + ((int64_t)s * M + row) * (2 * (int64_t)F) + cg);
+            const float4 g0 = p[0], g1 = p[1], u0 = p[4], u1 = p[5];
+            g[0] += g0.x; g[1] += g0.y; g[2] += g0.z; g[3] += g0.w; g[4] += g1.x; g[5] += g1.y; g[6] += g1.z; g[7] += g1.w;
+            u[0] += u0.x; u[1] += u0.y; u[2] += u0.z; u[3] += u0.w; u[4] += u1.x; u[5] += u1.y; u[6] += u1.z; u[7] += u1.w;
         }
-        out = gsum / (1.0f + expf(-gsum)) * usum;
+#pragma unroll
+        for (int e = 0; e < 8; e++) o[e] = g[e] / (1.0f + expf(-g[e])) * u[e];
     }
-    uint16_t hi, lo;
-    split_bf16(out, hi, lo);
-    act[(int64_t)row * ld_act + f] = hi;
-    act_lo[(int64_t)row * ld_act + f] = lo;
+    uint16_t hi[8], lo[8];
+#pragma unroll
+    for (int e = 0; e < 8; e++) split_bf16(o[e], hi[e], lo[e]);
+    uint4 ph, pl;
+    ph.x = hi[0] | ((uint32_t)hi[1] << 16); ph.y = hi[2] | ((uint32_t)hi[3] << 16);
+    ph.z = hi[4] | ((uint32_t)hi[5] << 16); ph.w = hi[6] | ((uint32_t)hi[7] << 16);
+    pl.x = lo[0] | ((uint32_t)lo[1] << 16); pl.y = lo[2] | ((uint32_t)lo[3] << 16);
+    pl.z = lo[4] | ((uint32_t)lo[5] << 16); pl.w = lo[6] | ((uint32_t)lo[7] << 16);
+    *reinterpret_cast<uint4 *>(act_frag + frag_index(0, row, f, n_ksteps, m_tiles)) = ph;
+    *reinterpret_cast<uint4 *>(act_frag + frag_index(1, row, f, n_ksteps, m_tiles)) = pl;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -230,9 +247,9 @@ void launch_embed(const int32_t *token, const TemplateDev &t, int batch, const v
                        (const uint16_t *)tok_emb, (const uint16_t *)mask_emb, d, vocab, x);
 }
 void launch_rmsnorm(float *x, const float *partial, int splits, int M, int d, const void *gain,
-                    float eps, void *h_hi, void *h_lo, int64_t ldh, hipStream_t s) {
+                    float eps, void *h_frag, hipStream_t s) {
     hipLaunchKernelGGL(rmsnorm_kernel, dim3(M), dim3(256), 0, s, x, partial, splits, M, d,
-                       (const uint16_t *)gain, eps, (uint16_t *)h_hi, (uint16_t *)h_lo, ldh);
+                       (const uint16_t *)gain, eps, (uint16_t *)h_frag);
 }
 void launch_qkv_rope(const float *partial, int splits, int batch, const TemplateDev &t, int Hq,
                      int Hkv, int hd, const int32_t *ctx_len, const float *rope_cos,
@@ -242,10 +259,10 @@ void launch_qkv_rope(const float *partial, int splits, int batch, const Template
                        splits, batch * t.rows, t, Hq, Hkv, hd, ctx_len, rope_cos, rope_sin, max_pos,
                        (uint16_t *)q, (uint16_t *)q_lo, (uint16_t *)k_tree, (uint16_t *)v_tree);
 }
-void launch_silu_mul(const float *partial, int splits, int M, int F, void *act, void *act_lo,
-                     int64_t ld_act, hipStream_t s) {
-    hipLaunchKernelGGL(silu_mul_kernel, dim3((unsigned)((ld_act + 255) / 256), M), dim3(256), 0, s,
-                       partial, splits, M, F, (uint16_t *)act, (uint16_t *)act_lo, ld_act);
+void launch_silu_mul(const float *partial, int splits, int M, int F, void *act_frag, hipStream_t s) {
+    const int n8 = ((F + 31) / 32) * 4;                       // threads (8 features each) per row
+    hipLaunchKernelGGL(silu_mul_kernel, dim3((n8 + 127) / 128, M), dim3(128), 0, s, partial, splits, M, F,
+                       (uint16_t *)act_frag);
 }
 void launch_select(const float *logits, int batch, const TemplateDev &t, int vocab, int kmax,
                    int32_t *argmax, int32_t *topk_ids, float *topk_val, hipStream_t s) {
