@@ -19,6 +19,17 @@
 #define ATT_WAVES 4
 #define ATT_PAD 8   // bf16 elements of row padding in both LDS tiles
 
+// 2^x for x <= 0 or -inf (softmax arguments): the bare hardware instruction, without the
+// denormal-range fix-up of exp2f (results below 2^-126 flush to zero, which is what we want)
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+// two floats -> packed bf16 pair, round to nearest even (gfx950 has a native conversion)
+__device__ __forceinline__ uint32_t cvt_pk_bf16(float lo, float hi) {
+    typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+    typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+    const f32x2_t v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
+
 template <int HD>
 struct AttSmem {
     static constexpr int K_STRIDE = HD + ATT_PAD;          // bf16 per K row
@@ -33,8 +44,8 @@ struct AttSmem {
 template <int HD, int MT>
 constexpr int att_tile_region() {
     const int tile = AttSmem<HD>::TILE_BYTES;
-    const int merge = MT * 16 * (HD + 4) * 4 + 2 * ATT_WAVES * MT * 16 * 4;
-    return tile > merge ? tile : merge;
+    (void)MT;
+    return tile;
 }
 template <int HD, int MT>
 constexpr int att_smem_bytes() {
@@ -241,15 +252,15 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void tree_attn_kernel(
             mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
             const float m_new = fmaxf(m_run[mt], mx);
             const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-            const float alpha = exp2f(m_run[mt] - m_use);
+            const float alpha = fast_exp2(m_run[mt] - m_use);
             m_run[mt] = m_new;
             float ps = 0.f;
             uint32_t pk2[4];
 #pragma unroll
             for (int e = 0; e < 8; e += 2) {
-                const float p0 = exp2f(sv[e] - m_use), p1 = exp2f(sv[e + 1] - m_use);
+                const float p0 = fast_exp2(sv[e] - m_use), p1 = fast_exp2(sv[e + 1] - m_use);
                 ps += p0 + p1;
-                pk2[e >> 1] = pack_bf16x2(p0, p1);
+                pk2[e >> 1] = cvt_pk_bf16(p0, p1);
             }
             l_run[mt] = l_run[mt] * alpha + ps;
             pf[mt] = __builtin_bit_cast(bf16x8, make_uint4(pk2[0], pk2[1], pk2[2], pk2[3]));
@@ -268,10 +279,14 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void tree_attn_kernel(
     }
 
     // ---- merge the 4 wavefronts (each saw a disjoint key subset) --------------------------
+    // Row statistics go through two small LDS arrays; the O accumulators are added pairwise
+    // (3 <- nothing, 2+3 -> regions, 0 += 2, 1 += 3, then 0 += 1) through LDS in register order,
+    // so every LDS access is a linear 1 KiB sweep, and wave 0 stores the result from registers.
     __syncthreads();
-    constexpr int OSTR = HD + 4;                           // floats per merged row
-    float *o_sum = reinterpret_cast<float *>(smem);
-    float *sm = o_sum + MT * 16 * OSTR, *sl = sm + ATT_WAVES * MT * 16;
+    float *sm = reinterpret_cast<float *>(smem), *sl = sm + ATT_WAVES * MT * 16;
+    float4 *region = reinterpret_cast<float4 *>(smem + 2 * ATT_WAVES * MT * 16 * 4);   // 2 x [NTN*MT][64]
+    constexpr int REGION_F4 = NTN * MT * 64;
+    static_assert(2 * ATT_WAVES * MT * 16 * 4 + 2 * REGION_F4 * 16 <= att_smem_bytes<HD, MT>(), "merge scratch fits");
 #pragma unroll
     for (int mt = 0; mt < MT; mt++) {
         float l = l_run[mt];
@@ -294,44 +309,49 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void tree_attn_kernel(
         float l = 0.f;
 #pragma unroll
         for (int w = 0; w < ATT_WAVES; w++)
-            l += sl[w * MT * 16 + mt * 16 + c] * exp2f(sm[w * MT * 16 + mt * 16 + c] - m_use);
-        const float f = exp2f(m_run[mt] - m_use);
+            l += sl[w * MT * 16 + mt * 16 + c] * fast_exp2(sm[w * MT * 16 + mt * 16 + c] - m_use);
+        const float f = fast_exp2(m_run[mt] - m_use);
         m_tot[mt] = m;
         l_tot[mt] = l;
 #pragma unroll
         for (int nt = 0; nt < NTN; nt++) o_acc[nt][mt] *= f;
     }
-    for (int w = 0; w < ATT_WAVES; w++) {
-        if (wave == w) {
+    auto park = [&](int which) {
+#pragma unroll
+        for (int nt = 0; nt < NTN; nt++)
 #pragma unroll
             for (int mt = 0; mt < MT; mt++)
+                region[which * REGION_F4 + (nt * MT + mt) * 64 + lane] =
+                    make_float4(o_acc[nt][mt][0], o_acc[nt][mt][1], o_acc[nt][mt][2], o_acc[nt][mt][3]);
+    };
+    auto absorb = [&](int which) {
 #pragma unroll
-                for (int nt = 0; nt < NTN; nt++) {
-                    float4 *dst = reinterpret_cast<float4 *>(o_sum + (mt * 16 + c) * OSTR + nt * 16 + 4 * g);
-                    float4 v = make_float4(o_acc[nt][mt][0], o_acc[nt][mt][1], o_acc[nt][mt][2], o_acc[nt][mt][3]);
-                    if (w > 0) {
-                        const float4 old = *dst;
-                        v.x += old.x; v.y += old.y; v.z += old.z; v.w += old.w;
-                    }
-                    *dst = v;
-                }
-        }
-        __syncthreads();
-    }
-    // ---- write the split's partial result --------------------------------------------------
+        for (int nt = 0; nt < NTN; nt++)
+#pragma unroll
+            for (int mt = 0; mt < MT; mt++) {
+                const float4 v = region[which * REGION_F4 + (nt * MT + mt) * 64 + lane];
+                o_acc[nt][mt][0] += v.x; o_acc[nt][mt][1] += v.y; o_acc[nt][mt][2] += v.z; o_acc[nt][mt][3] += v.w;
+            }
+    };
+    if (wave >= 2) park(wave - 2);
+    __syncthreads();
+    if (wave < 2) absorb(wave);
+    __syncthreads();
+    if (wave == 1) park(0);
+    __syncthreads();
+    if (wave != 0) return;
+    absorb(0);
+    // ---- write the split's partial result: lane (g, c) holds O[row c][hd 16nt + 4g .. +4] ------
     const int64_t pbase = (((int64_t)b * Hq + h) * n_splits + split) * R;
-    for (int idx = tid; idx < MT * 16 * (HD / 4); idx += 256) {
-        const int qr = idx / (HD / 4), c4 = idx % (HD / 4);
-        const int r = row0 + qr;
-        if (r < R)
-            *reinterpret_cast<float4 *>(part_o + (pbase + r) * HD + c4 * 4) =
-                *reinterpret_cast<const float4 *>(o_sum + qr * OSTR + c4 * 4);
-    }
-    if (wave == 0 && g == 0) {
 #pragma unroll
-        for (int mt = 0; mt < MT; mt++) {
-            const int r = row0 + mt * 16 + c;
-            if (r < R) {
+    for (int mt = 0; mt < MT; mt++) {
+        const int r = row0 + mt * 16 + c;
+        if (r < R) {
+#pragma unroll
+            for (int nt = 0; nt < NTN; nt++)
+                *reinterpret_cast<float4 *>(part_o + (pbase + r) * HD + nt * 16 + 4 * g) =
+                    make_float4(o_acc[nt][mt][0], o_acc[nt][mt][1], o_acc[nt][mt][2], o_acc[nt][mt][3]);
+            if (g == 0) {
                 part_ml[(pbase + r) * 2] = m_tot[mt];
                 part_ml[(pbase + r) * 2 + 1] = l_tot[mt];
             }
@@ -339,29 +359,42 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void tree_attn_kernel(
     }
 }
 
-// out[b][r][h*HD + i] = sum_s w_s O_s[i] / sum_s w_s l_s,  w_s = 2^(m_s - max m)
+// out[b][r][h*HD + 4i .. +4] = sum_s w_s O_s / sum_s w_s l_s,  w_s = 2^(m_s - max m).
+// One thread per 4 head-dim elements; blockDim = (HD/4) * heads_per_block.
 __global__ void attn_merge_kernel(const float *__restrict__ part_o, const float *__restrict__ part_ml,
                                   int R, int Hq, int HD, int n_splits, uint16_t *__restrict__ out,
                                   int as_fragments, int m_tiles) {
-    const int r = blockIdx.x, h = blockIdx.y, b = blockIdx.z, i = threadIdx.x;
+    const int per_head = HD >> 2;
+    const int r = blockIdx.x, b = blockIdx.z;
+    const int h = blockIdx.y * (blockDim.x / per_head) + threadIdx.x / per_head, i4 = threadIdx.x % per_head;
+    if (h >= Hq) return;
     const int64_t pbase = ((int64_t)b * Hq + h) * n_splits;
     float m = -INFINITY;
     for (int s = 0; s < n_splits; s++) m = fmaxf(m, part_ml[((pbase + s) * R + r) * 2]);
     const float m_use = (m == -INFINITY) ? 0.f : m;
-    float l = 0.f, acc = 0.f;
+    float l = 0.f;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int s = 0; s < n_splits; s++) {
-        const float w = exp2f(part_ml[((pbase + s) * R + r) * 2] - m_use);
-        l += w * part_ml[((pbase + s) * R + r) * 2 + 1];
-        acc += w * part_o[((pbase + s) * R + r) * HD + i];
+        const float2 ml = *reinterpret_cast<const float2 *>(part_ml + ((pbase + s) * R + r) * 2);
+        const float w = fast_exp2(ml.x - m_use);
+        const float4 o = *reinterpret_cast<const float4 *>(part_o + ((pbase + s) * R + r) * HD + i4 * 4);
+        l += w * ml.y;
+        acc.x += w * o.x; acc.y += w * o.y; acc.z += w * o.z; acc.w += w * o.w;
     }
-    uint16_t hi, lo;
-    split_bf16(l > 0.f ? acc / l : 0.f, hi, lo);
+    const float inv = l > 0.f ? 1.0f / l : 0.f;
+    const float v[4] = {acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv};
+    uint16_t hi[4], lo[4];
+#pragma unroll
+    for (int e = 0; e < 4; e++) split_bf16(v[e], hi[e], lo[e]);
+    uint2 ph, pl;
+    ph.x = hi[0] | ((uint32_t)hi[1] << 16); ph.y = hi[2] | ((uint32_t)hi[3] << 16);
+    pl.x = lo[0] | ((uint32_t)lo[1] << 16); pl.y = lo[2] | ((uint32_t)lo[3] << 16);
     if (as_fragments) {                     // two planes, the O-projection's activation slab
-        const int m = b * R + r, k = h * HD + i, n_ksteps = (Hq * HD) >> 5;
-        out[frag_index(0, m, k, n_ksteps, m_tiles)] = hi;
-        out[frag_index(1, m, k, n_ksteps, m_tiles)] = lo;
+        const int mrow = b * R + r, k = h * HD + i4 * 4, n_ksteps = (Hq * HD) >> 5;
+        *reinterpret_cast<uint2 *>(out + frag_index(0, mrow, k, n_ksteps, m_tiles)) = ph;
+        *reinterpret_cast<uint2 *>(out + frag_index(1, mrow, k, n_ksteps, m_tiles)) = pl;
     } else {
-        out[(((int64_t)b * R + r) * Hq + h) * HD + i] = hi;
+        *reinterpret_cast<uint2 *>(out + (((int64_t)b * R + r) * Hq + h) * HD + i4 * 4) = ph;
     }
 }
 
@@ -371,10 +404,14 @@ AttnPlan attn_plan(int batch, int rows, int n_heads, int hd, int ctx_hint, int n
     const int n_tiles = (n_keys + ATT_TK - 1) / ATT_TK;
     const int n_qblk = (rows + 79) / 80;
     const int wgs = batch * n_heads * n_qblk;
-    int splits = (512 + wgs - 1) / wgs;                   // aim at ~2 workgroups per CU
+    // the kernel's LDS footprint allows one workgroup per CU: ask for one round of <= 256
+    int splits = 256 / wgs;
     if (splits > n_tiles) splits = n_tiles;
     if (splits < 1) splits = 1;
     if (splits > 32) splits = 32;
+    // equal shares: with per = ceil(tiles/splits) tiles each, drop the splits left without work
+    const int per = (n_tiles + splits - 1) / splits;
+    splits = (n_tiles + per - 1) / per;
     p.splits = splits;
     p.part_o_bytes = (size_t)batch * n_heads * splits * rows * hd * sizeof(float);
     p.part_ml_bytes = (size_t)batch * n_heads * splits * rows * 2 * sizeof(float);
@@ -416,6 +453,8 @@ void launch_tree_attention(const TemplateDev &t, const void *q, const void *q_lo
         if (small) launch_attn_t<64, 1>(t, q, q_lo, k_cache, v_cache, k_tree, v_tree, prompt_k, prompt_v, ctx_len, batch, Hq, Hkv, P, smax, p, part_o, part_ml, s);
         else launch_attn_t<64, 5>(t, q, q_lo, k_cache, v_cache, k_tree, v_tree, prompt_k, prompt_v, ctx_len, batch, Hq, Hkv, P, smax, p, part_o, part_ml, s);
     }
-    hipLaunchKernelGGL(attn_merge_kernel, dim3(t.rows, Hq, batch), dim3(hd), 0, s, part_o, part_ml, t.rows,
+    const int heads_per_block = (256 / (hd / 4)) < Hq ? (256 / (hd / 4)) : Hq;
+    hipLaunchKernelGGL(attn_merge_kernel, dim3(t.rows, (Hq + heads_per_block - 1) / heads_per_block, batch),
+                       dim3(heads_per_block * (hd / 4)), 0, s, part_o, part_ml, t.rows,
                        Hq, hd, p.splits, (uint16_t *)out, out_as_fragments ? 1 : 0, (batch * t.rows + 15) / 16);
 }
