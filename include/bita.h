@@ -53,8 +53,8 @@ extern "C" {
 /* Decoder shape.  LLaMA-2 architecture (the paper's base models, Sec. 4.1.2):
  * RMSNorm, rotary embeddings in the half-split pairing (i, i + head_dim/2),
  * SwiGLU, grouped-query attention, no biases, untied LM head.
- * Supported: head_dim 64 or 128; d_model, d_ffn multiples of 8; (n_heads +
- * 2 n_kv_heads) * head_dim, d_model, d_ffn and vocab multiples of 16. */
+ * Supported: head_dim 64 or 128; d_model a multiple of 32, at most 16384; d_ffn and
+ * vocab multiples of 16. */
 typedef struct bita_config {
     int32_t n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab;
     int32_t n_prompt;   /* P: prompt-prefix tokens per layer (may be 0)             */

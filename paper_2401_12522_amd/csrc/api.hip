@@ -53,9 +53,11 @@ extern "C" int bita_model_create(const bita_config *cfg, const bita_weights *w, 
     if (c.n_layers <= 0 || c.d_model <= 0 || c.n_heads <= 0 || c.n_kv_heads <= 0 || c.d_ffn <= 0 ||
         c.vocab <= 0 || c.n_prompt < 0 || c.n_mask < 0 || c.max_pos <= 0 || c.n_heads % c.n_kv_heads)
         return bita_set_error(BITA_ERR_INVALID_ARG, "bita_model_create: non-positive or inconsistent shape");
-    if ((c.head_dim != 64 && c.head_dim != 128) || c.d_model % 16 || c.d_ffn % 16 || c.vocab % 16)
+    if ((c.head_dim != 64 && c.head_dim != 128) || c.d_model % 32 || c.d_ffn % 16 || c.vocab % 16 ||
+        c.d_model > 1024 * RMS_MAX_CHUNKS)
         return bita_set_error(BITA_ERR_UNSUPPORTED,
-                              "bita_model_create: head_dim must be 64 or 128; d_model, d_ffn, vocab multiples of 16");
+                              "bita_model_create: head_dim must be 64 or 128; d_model a multiple of 32 and <= %d; "
+                              "d_ffn, vocab multiples of 16", 1024 * RMS_MAX_CHUNKS);
     if (!w->tok_emb || !w->final_norm || !w->lm_head || !w->attn_norm || !w->ffn_norm || !w->wqkv ||
         !w->wo || !w->w_gate_up || !w->w_down || (c.n_mask > 0 && !w->mask_emb) ||
         (c.n_prompt > 0 && (!w->prompt_k || !w->prompt_v)))
@@ -247,7 +249,7 @@ static void timed_gemm(const void *a_frag, int M, int64_t K, const void *w, int6
 
 // ------------------------------------------------------------------------------------------
 struct WsLayout {
-    size_t x, h, q, attn_out, act, partial, part_o, part_ml, logits, total;
+    size_t x, h, q, attn_out, act, partial, part_o, part_ml, logits, ssq, total;
     size_t partial_bytes;
 };
 #define ATTN_MAX_SPLITS 32
@@ -277,6 +279,7 @@ static WsLayout ws_layout(const bita_config &c, int batch, int rows) {
     L.part_o = take((size_t)batch * c.n_heads * ATTN_MAX_SPLITS * rows * c.head_dim * 4);
     L.part_ml = take((size_t)batch * c.n_heads * ATTN_MAX_SPLITS * rows * 2 * 4);
     L.logits = take(M * c.vocab * 4);
+    L.ssq = take(M * RMS_MAX_CHUNKS * 4);
     L.total = off;
     return L;
 }
@@ -319,7 +322,9 @@ extern "C" int bita_verify_step(bita_model *m, const bita_kv *kv, const bita_tre
     unsigned char *h = ws + L.h, *q = ws + L.q, *attn_out = ws + L.attn_out, *act = ws + L.act;
     float *part_o = (float *)(ws + L.part_o), *part_ml = (float *)(ws + L.part_ml);
     float *logits = d_logits ? d_logits : (float *)(ws + L.logits);
+    float *ssq = (float *)(ws + L.ssq);
     const int M = batch * td.rows, d = c.d_model, hd = c.head_dim;
+    const RowScale rs_norm = {ssq, (d / 4 + 255) / 256, 1.0f / (float)d, c.rms_eps};
     const int64_t nq = (int64_t)c.n_heads * hd, nqkv = (int64_t)(c.n_heads + 2 * c.n_kv_heads) * hd;
     unsigned char *q_lo = q + (size_t)M * nq * 2;
     const GemmPlan p_qkv = gemm_plan(M, nqkv, d), p_o = gemm_plan(M, d, nq),
@@ -333,29 +338,26 @@ extern "C" int bita_verify_step(bita_model *m, const bita_kv *kv, const bita_tre
     launch_embed(d_token, td, batch, m->tok_emb, m->mask_emb, d, c.vocab, x, s);
     int pending = 0;                                    // split-K partials waiting to be added to x
     for (int l = 0; l < c.n_layers; l++) {
-        launch_rmsnorm(x, partial, pending, M, d, m->attn_norm[l], c.rms_eps, h, s);
+        launch_rmsnorm_prep(x, partial, pending, M, d, m->attn_norm[l], h, ssq, s);
         timed_gemm(h, M, d, m->wqkv[l], nqkv, partial, nqkv, p_qkv, s);
         void *kt = (unsigned char *)kv->k_tree + l * kv_layer_tree, *vt = (unsigned char *)kv->v_tree + l * kv_layer_tree;
         launch_qkv_rope(partial, p_qkv.splits, batch, td, c.n_heads, c.n_kv_heads, hd, d_ctx_len, m->rope_cos,
-                        m->rope_sin, c.max_pos, q, q_lo, kt, vt, s);
+                        m->rope_sin, c.max_pos, q, q_lo, kt, vt, rs_norm, s);
         launch_tree_attention(td, q, q_lo, (unsigned char *)kv->k_cache + l * kv_layer_cache,
                               (unsigned char *)kv->v_cache + l * kv_layer_cache, kt, vt, m->prompt_k[l],
                               m->prompt_v[l], d_ctx_len, batch, c.n_heads, c.n_kv_heads, hd, c.n_prompt, kv->smax,
                               ap, part_o, part_ml, attn_out, true, s);
         timed_gemm(attn_out, M, nq, m->wo[l], d, partial, d, p_o, s);
-        launch_rmsnorm(x, partial, p_o.splits, M, d, m->ffn_norm[l], c.rms_eps, h, s);
+        launch_rmsnorm_prep(x, partial, p_o.splits, M, d, m->ffn_norm[l], h, ssq, s);
         timed_gemm(h, M, d, m->w_gate_up[l], 2 * (int64_t)c.d_ffn, partial, 2 * (int64_t)c.d_ffn, p_gu, s);
-        launch_silu_mul(partial, p_gu.splits, M, c.d_ffn, act, s);
+        launch_silu_mul(partial, p_gu.splits, M, c.d_ffn, act, rs_norm, s);
         timed_gemm(act, M, c.d_ffn, m->w_down[l], d, partial, d, p_dn, s);
         pending = p_dn.splits;
     }
-    launch_rmsnorm(x, partial, pending, M, d, m->final_norm, c.rms_eps, h, s);
-    if (p_lm.splits == 1) {
-        timed_gemm(h, M, d, m->lm_head, c.vocab, logits, c.vocab, p_lm, s);
-    } else {
-        timed_gemm(h, M, d, m->lm_head, c.vocab, partial, c.vocab, p_lm, s);
-        launch_reduce_partials(partial, p_lm.splits, M, c.vocab, c.vocab, logits, s);
-    }
+    launch_rmsnorm_prep(x, partial, pending, M, d, m->final_norm, h, ssq, s);
+    // the LM head always goes through the reduce kernel: it applies the final norm's row factor
+    timed_gemm(h, M, d, m->lm_head, c.vocab, partial, c.vocab, p_lm, s);
+    launch_reduce_partials(partial, p_lm.splits, M, c.vocab, c.vocab, logits, rs_norm, s);
     launch_select(logits, batch, td, c.vocab, kmax, d_argmax, n_sel_mask > 0 ? d_topk_ids : nullptr, d_topk_val, s);
     BITA_HIP_CHECK(hipGetLastError());
     return BITA_OK;
@@ -441,7 +443,7 @@ extern "C" int bita_gemm(const void *d_a, const void *d_a_lo, int32_t m_rows, in
         launch_gemm(frag, d_a_lo != nullptr, m_rows, k, d_w_packed, n_rows, d_out, n_rows, p, s);
     } else {
         launch_gemm(frag, d_a_lo != nullptr, m_rows, k, d_w_packed, n_rows, (float *)d_ws, n_rows, p, s);
-        launch_reduce_partials((const float *)d_ws, p.splits, m_rows, n_rows, n_rows, d_out, s);
+        launch_reduce_partials((const float *)d_ws, p.splits, m_rows, n_rows, n_rows, d_out, RowScale{nullptr, 0, 0.f, 0.f}, s);
     }
     BITA_HIP_CHECK(hipGetLastError());
     return BITA_OK;

@@ -60,6 +60,15 @@ struct bita_tree_template {
 };
 
 // ---- kernel launchers (each only enqueues) --------------------------------------
+#define RMS_MAX_CHUNKS 16          // 1024 columns each: d_model <= 16384
+struct RowScale { const float *ssq; int chunks; float inv_d, eps; };   // ssq == nullptr: no scaling
+// second half of RMSNorm: rsqrt(mean(x^2) + eps) of row m from the per-chunk sums of squares
+__device__ __forceinline__ float row_scale(const RowScale &rs, int m) {
+    if (!rs.ssq) return 1.0f;
+    float tot = 0.f;
+    for (int ch = 0; ch < rs.chunks; ch++) tot += rs.ssq[(int64_t)m * RMS_MAX_CHUNKS + ch];
+    return 1.0f / sqrtf(tot * rs.inv_d + rs.eps);
+}
 struct GemmPlan { int splits, ksteps_per_split, variant; };
 void gemm_force_plan(int variant, int splits);   // tuning aid: < 0 restores the heuristic
 GemmPlan gemm_plan(int m_rows, int64_t n_rows, int64_t k);
@@ -70,22 +79,24 @@ void launch_gemm(const void *a_frag, bool two_planes, int m_rows, int64_t k, con
 void launch_to_fragments(const void *a_hi, const void *a_lo, int m_rows, int64_t k, int64_t lda, void *dst,
                          hipStream_t s);
 void launch_reduce_partials(const float *partial, int splits, int m_rows, int64_t n, int64_t ld,
-                            float *out, hipStream_t s);
+                            float *out, const RowScale &rs, hipStream_t s);
 void launch_pack(const void *src, int64_t n_rows, int64_t k, void *dst, int64_t tile0,
                  int64_t tile_stride, int64_t total_tiles, hipStream_t s);
 
 void launch_embed(const int32_t *token, const TemplateDev &t, int batch, const void *tok_emb,
                   const void *mask_emb, int d, int vocab, float *x, hipStream_t s);
 // x += sum of partials (optional), then h = rmsnorm(x) * gain as bf16 with row stride ldh
-// h: two-plane activation slab in fragment order
-void launch_rmsnorm(float *x, const float *partial, int splits, int m_rows, int d,
-                    const void *gain, float eps, void *h_frag, hipStream_t s);
+// RMSNorm is split: the prep kernel writes x*gain (two planes, fragment order) and per-chunk
+// sums of squares ssq[m_rows][RMS_MAX_CHUNKS]; the row factor rsqrt(sum(ssq)/d + eps) commutes
+// with the matrix product and is applied by the kernel that consumes the GEMM output.
+void launch_rmsnorm_prep(float *x, const float *partial, int splits, int m_rows, int d,
+                         const void *gain, void *h_frag, float *ssq, hipStream_t s);
 void launch_qkv_rope(const float *partial, int splits, int batch, const TemplateDev &t,
                      int n_heads, int n_kv_heads, int hd, const int32_t *ctx_len,
                      const float *rope_cos, const float *rope_sin, int max_pos,
-                     void *q, void *q_lo, void *k_tree, void *v_tree, hipStream_t s);
+                     void *q, void *q_lo, void *k_tree, void *v_tree, const RowScale &rs, hipStream_t s);
 void launch_silu_mul(const float *partial, int splits, int m_rows, int d_ffn, void *act_frag,
-                     hipStream_t s);
+                     const RowScale &rs, hipStream_t s);
 void launch_select(const float *logits, int batch, const TemplateDev &t, int vocab, int kmax,
                    int32_t *argmax, int32_t *topk_ids, float *topk_val, hipStream_t s);
 

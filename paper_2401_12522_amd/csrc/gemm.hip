@@ -192,15 +192,15 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
     }
 }
 
-// out[m][n] = sum over splits of partial[s][m][n], in split order
+// out[m][n] = rowscale(m) * sum over splits of partial[s][m][n], in split order
 __global__ void reduce_partials_kernel(const float *__restrict__ partial, int splits, int M,
-                                       int64_t N, int64_t ld, float *__restrict__ out) {
+                                       int64_t N, int64_t ld, float *__restrict__ out, RowScale rs) {
     const int64_t n = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int m = blockIdx.y;
     if (n >= N) return;
     float acc = 0.f;
     for (int s = 0; s < splits; s++) acc += partial[((int64_t)s * M + m) * ld + n];
-    out[(int64_t)m * N + n] = acc;
+    out[(int64_t)m * N + n] = acc * row_scale(rs, m);
 }
 
 // Pure permutation: row-major [N][K] bf16 -> packed tiles (see file header).
@@ -313,9 +313,9 @@ void launch_to_fragments(const void *a_hi, const void *a_lo, int M, int64_t K, i
 }
 
 void launch_reduce_partials(const float *partial, int splits, int M, int64_t N, int64_t ld,
-                            float *out, hipStream_t s) {
+                            float *out, const RowScale &rs, hipStream_t s) {
     dim3 grid((unsigned)((N + 255) / 256), M);
-    hipLaunchKernelGGL(reduce_partials_kernel, grid, dim3(256), 0, s, partial, splits, M, N, ld, out);
+    hipLaunchKernelGGL(reduce_partials_kernel, grid, dim3(256), 0, s, partial, splits, M, N, ld, out, rs);
 }
 
 void launch_pack(const void *src, int64_t N, int64_t K, void *dst, int64_t tile0, int64_t tile_stride,

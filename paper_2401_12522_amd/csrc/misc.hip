@@ -27,55 +27,33 @@ __device__ __forceinline__ float wave_sum(float v) {
     return v;
 }
 
-// One workgroup per row: x += sum_s partial[s] (fixed order), h = x * rsqrt(mean(x^2)+eps) * g,
-// written as two bf16 planes (hi = bf16(h), lo = bf16(h - hi)) in the GEMM's fragment order, so
-// that the following GEMM sees the activation to ~16 mantissa bits.  Each thread owns float4 columns tid, tid+256, ...; all
-// loads of a column are independent and issued together.
-#define RMS_MAX_V4 8      // d_model <= 8192 is kept in registers, larger rows are re-read
-__global__ __launch_bounds__(256) void rmsnorm_kernel(float *__restrict__ x, const float *__restrict__ partial,
-                                                      int splits, int M, int d,
-                                                      const uint16_t *__restrict__ gain, float eps,
-                                                      uint16_t *__restrict__ h_frag) {
+// RMSNorm, first half.  Grid (row, 1024-column chunk): x += sum_s partial[s] (fixed order), then
+// the *unnormalised* x * gain is written as two bf16 planes (hi, lo) in the GEMM's fragment
+// order, and the chunk's sum of squares goes to ssq[row][chunk].  The row factor
+// rsqrt(mean(x^2) + eps) is a scalar per row and commutes with the matrix product, so the GEMM
+// applies it to its output rows; that keeps this kernel free of any row-wide reduction and
+// lets all CUs share the split-K partial traffic.
+__global__ __launch_bounds__(256) void rmsnorm_prep_kernel(float *__restrict__ x, const float *__restrict__ partial,
+                                                           int splits, int M, int d,
+                                                           const uint16_t *__restrict__ gain,
+                                                           uint16_t *__restrict__ h_frag, float *__restrict__ ssq) {
     __shared__ float red[4];
-    const int row = blockIdx.x, tid = threadIdx.x;
+    const int row = blockIdx.x, chunk = blockIdx.y, tid = threadIdx.x;
     const int n_ksteps = (d + 31) >> 5, m_tiles = (M + 15) >> 4;
-    const int nv = d >> 2;                                   // float4 columns (d % 4 == 0)
-    float4 *xr = reinterpret_cast<float4 *>(x + (int64_t)row * d);
-    float4 keep[RMS_MAX_V4];
+    const int c = chunk * 256 + tid;                         // float4 column
     float ss = 0.f;
-#pragma unroll
-    for (int it = 0; it < RMS_MAX_V4; it++) {
-        const int c = it * 256 + tid;
-        if (c < nv) {
-            float4 v = xr[c];
-            for (int s = 0; s < splits; s++) {
-                const float4 p = reinterpret_cast<const float4 *>(partial + ((int64_t)s * M + row) * d)[c];
-                v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
-            }
-            if (splits > 0) xr[c] = v;
-            keep[it] = v;
-            ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
-        }
-    }
-    for (int c = RMS_MAX_V4 * 256 + tid; c < nv; c += 256) {   // rows wider than the register budget
+    if (c < (d >> 2)) {
+        float4 *xr = reinterpret_cast<float4 *>(x + (int64_t)row * d);
         float4 v = xr[c];
         for (int s = 0; s < splits; s++) {
             const float4 p = reinterpret_cast<const float4 *>(partial + ((int64_t)s * M + row) * d)[c];
             v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
         }
         if (splits > 0) xr[c] = v;
-        ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
-    }
-    ss = wave_sum(ss);
-    if ((tid & 63) == 0) red[tid >> 6] = ss;
-    __syncthreads();
-    const float tot = red[0] + red[1] + red[2] + red[3];
-    const float scale = 1.0f / sqrtf(tot / (float)d + eps);
-    auto emit = [&](int c, float4 v) {
+        ss = v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
         const uint2 gq = reinterpret_cast<const uint2 *>(gain)[c];
-        const float g0 = bf16_to_f32((uint16_t)(gq.x & 0xFFFFu)), g1 = bf16_to_f32((uint16_t)(gq.x >> 16));
-        const float g2 = bf16_to_f32((uint16_t)(gq.y & 0xFFFFu)), g3 = bf16_to_f32((uint16_t)(gq.y >> 16));
-        const float o[4] = {v.x * scale * g0, v.y * scale * g1, v.z * scale * g2, v.w * scale * g3};
+        const float o[4] = {v.x * bf16_to_f32((uint16_t)(gq.x & 0xFFFFu)), v.y * bf16_to_f32((uint16_t)(gq.x >> 16)),
+                            v.z * bf16_to_f32((uint16_t)(gq.y & 0xFFFFu)), v.w * bf16_to_f32((uint16_t)(gq.y >> 16))};
         uint16_t hi[4], lo[4];
 #pragma unroll
         for (int e = 0; e < 4; e++) split_bf16(o[e], hi[e], lo[e]);
@@ -84,13 +62,11 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(float *__restrict__ x, con
         pl.x = lo[0] | ((uint32_t)lo[1] << 16); pl.y = lo[2] | ((uint32_t)lo[3] << 16);
         *reinterpret_cast<uint2 *>(h_frag + frag_index(0, row, 4 * c, n_ksteps, m_tiles)) = ph;
         *reinterpret_cast<uint2 *>(h_frag + frag_index(1, row, 4 * c, n_ksteps, m_tiles)) = pl;
-    };
-#pragma unroll
-    for (int it = 0; it < RMS_MAX_V4; it++) {
-        const int c = it * 256 + tid;
-        if (c < nv) emit(c, keep[it]);
     }
-    for (int c = RMS_MAX_V4 * 256 + tid; c < nv; c += 256) emit(c, xr[c]);
+    ss = wave_sum(ss);
+    if ((tid & 63) == 0) red[tid >> 6] = ss;
+    __syncthreads();
+    if (tid == 0) ssq[(int64_t)row * RMS_MAX_CHUNKS + chunk] = red[0] + red[1] + red[2] + red[3];
 }
 
 // ---------------------------------------------------------------------------------------
@@ -101,7 +77,7 @@ __global__ __launch_bounds__(64) void qkv_rope_kernel(
     const float *__restrict__ partial, int splits, int M, TemplateDev t, int Hq, int Hkv, int hd,
     const int32_t *__restrict__ ctx_len, const float *__restrict__ rope_cos,
     const float *__restrict__ rope_sin, int max_pos, uint16_t *__restrict__ q,
-    uint16_t *__restrict__ q_lo, uint16_t *__restrict__ k_tree, uint16_t *__restrict__ v_tree) {
+    uint16_t *__restrict__ q_lo, uint16_t *__restrict__ k_tree, uint16_t *__restrict__ v_tree, RowScale rs) {
     const int row = blockIdx.x, head = blockIdx.y;       // head over Hq + 2*Hkv
     const int b = row / t.rows, r = row % t.rows;
     const int half = hd >> 1, i = threadIdx.x;
@@ -114,6 +90,9 @@ __global__ __launch_bounds__(64) void qkv_rope_kernel(
         lo += p[0];
         hi += p[half];
     }
+    const float sc = row_scale(rs, row);          // RMSNorm's row factor, deferred past the GEMM
+    lo *= sc;
+    hi *= sc;
     uint16_t *dst, *dst_lo = nullptr;
     if (head < Hq) {
         dst = q + ((int64_t)row * Hq + head) * hd;
@@ -148,7 +127,7 @@ __global__ __launch_bounds__(64) void qkv_rope_kernel(
 // silu(gate) * up as one 16-byte store each into the down-projection's activation slab
 // (fragment order; features beyond d_ffn inside the last k-step are written as zeros).
 __global__ void silu_mul_kernel(const float *__restrict__ partial, int splits, int M, int F,
-                                uint16_t *__restrict__ act_frag) {
+                                uint16_t *__restrict__ act_frag, RowScale rs) {
     const int f8 = blockIdx.x * blockDim.x + threadIdx.x;
     const int row = blockIdx.y;
     const int n_ksteps = (F + 31) >> 5, m_tiles = (M + 15) >> 4;
@@ -168,8 +147,12 @@ __global__ void silu_mul_kernel(const float *__restrict__ partial, int splits, i
             g[0] += g0.x; g[1] += g0.y; g[2] += g0.z; g[3] += g0.w; g[4] += g1.x; g[5] += g1.y; g[6] += g1.z; g[7] += g1.w;
             u[0] += u0.x; u[1] += u0.y; u[2] += u0.z; u[3] += u0.w; u[4] += u1.x; u[5] += u1.y; u[6] += u1.z; u[7] += u1.w;
         }
+        const float sc = row_scale(rs, row);      // RMSNorm's row factor, deferred past the GEMM
 #pragma unroll
-        for (int e = 0; e < 8; e++) o[e] = g[e] / (1.0f + expf(-g[e])) * u[e];
+        for (int e = 0; e < 8; e++) {
+            const float gs = g[e] * sc;
+            o[e] = gs / (1.0f + expf(-gs)) * (u[e] * sc);
+        }
     }
     uint16_t hi[8], lo[8];
 #pragma unroll
@@ -246,23 +229,25 @@ void launch_embed(const int32_t *token, const TemplateDev &t, int batch, const v
     hipLaunchKernelGGL(embed_kernel, dim3(batch * t.rows), dim3(256), 0, s, token, t,
                        (const uint16_t *)tok_emb, (const uint16_t *)mask_emb, d, vocab, x);
 }
-void launch_rmsnorm(float *x, const float *partial, int splits, int M, int d, const void *gain,
-                    float eps, void *h_frag, hipStream_t s) {
-    hipLaunchKernelGGL(rmsnorm_kernel, dim3(M), dim3(256), 0, s, x, partial, splits, M, d,
-                       (const uint16_t *)gain, eps, (uint16_t *)h_frag);
+void launch_rmsnorm_prep(float *x, const float *partial, int splits, int M, int d, const void *gain,
+                         void *h_frag, float *ssq, hipStream_t s) {
+    const int chunks = (d / 4 + 255) / 256;
+    hipLaunchKernelGGL(rmsnorm_prep_kernel, dim3(M, chunks), dim3(256), 0, s, x, partial, splits, M, d,
+                       (const uint16_t *)gain, (uint16_t *)h_frag, ssq);
 }
 void launch_qkv_rope(const float *partial, int splits, int batch, const TemplateDev &t, int Hq,
                      int Hkv, int hd, const int32_t *ctx_len, const float *rope_cos,
                      const float *rope_sin, int max_pos, void *q, void *q_lo, void *k_tree, void *v_tree,
-                     hipStream_t s) {
+                     const RowScale &rs, hipStream_t s) {
     hipLaunchKernelGGL(qkv_rope_kernel, dim3(batch * t.rows, Hq + 2 * Hkv), dim3(64), 0, s, partial,
                        splits, batch * t.rows, t, Hq, Hkv, hd, ctx_len, rope_cos, rope_sin, max_pos,
-                       (uint16_t *)q, (uint16_t *)q_lo, (uint16_t *)k_tree, (uint16_t *)v_tree);
+                       (uint16_t *)q, (uint16_t *)q_lo, (uint16_t *)k_tree, (uint16_t *)v_tree, rs);
 }
-void launch_silu_mul(const float *partial, int splits, int M, int F, void *act_frag, hipStream_t s) {
+void launch_silu_mul(const float *partial, int splits, int M, int F, void *act_frag, const RowScale &rs,
+                     hipStream_t s) {
     const int n8 = ((F + 31) / 32) * 4;                       // threads (8 features each) per row
     hipLaunchKernelGGL(silu_mul_kernel, dim3((n8 + 127) / 128, M), dim3(128), 0, s, partial, splits, M, F,
-                       (uint16_t *)act_frag);
+                       (uint16_t *)act_frag, rs);
 }
 void launch_select(const float *logits, int batch, const TemplateDev &t, int vocab, int kmax,
                    int32_t *argmax, int32_t *topk_ids, float *topk_val, hipStream_t s) {
