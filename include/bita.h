@@ -194,13 +194,16 @@ int bita_compact_kv(const bita_model *m, const bita_kv *kv, const int32_t *d_pat
 /* Tree-masked attention alone (the kernel bita_verify_step runs per layer), for
  * kernel-level tests and measurement.  d_q [B][R][n_heads][hd] (already rotated; d_q_lo
  * is an optional second bf16 plane of the same shape with the rounding residual),
- * K/V arguments are one layer's slices laid out as in bita_kv; d_out
+ * K/V arguments are one layer's slices laid out as in bita_kv; d_k_tree_lo / d_v_tree_lo
+ * are optional second planes of d_k_tree / d_v_tree (the pass rows' K/V before they are
+ * rounded to the cache format: value = hi + lo; NULL = zero); d_out
  * [B][R][n_heads*hd] bf16.  d_ws needs bita_attention_workspace_bytes(). */
 size_t bita_attention_workspace_bytes(int32_t batch, int32_t rows, int32_t n_heads,
                                       int32_t head_dim, int32_t ctx_hint, int32_t n_prompt);
 int bita_tree_attention(const bita_tree_template *t, const void *d_q, const void *d_q_lo,
                         const void *d_k_cache, const void *d_v_cache,
                         const void *d_k_tree, const void *d_v_tree,
+                        const void *d_k_tree_lo, const void *d_v_tree_lo,
                         const void *d_prompt_k, const void *d_prompt_v,
                         const int32_t *d_ctx_len, int32_t batch, int32_t n_heads,
                         int32_t n_kv_heads, int32_t head_dim, int32_t n_prompt, int32_t smax,

@@ -249,7 +249,7 @@ static void timed_gemm(const void *a_frag, int M, int64_t K, const void *w, int6
 
 // ------------------------------------------------------------------------------------------
 struct WsLayout {
-    size_t x, h, q, attn_out, act, partial, part_o, part_ml, logits, ssq, total;
+    size_t x, h, q, attn_out, act, partial, part_o, part_ml, logits, ssq, kv_lo, total;
     size_t partial_bytes;
 };
 #define ATTN_MAX_SPLITS 32
@@ -280,6 +280,7 @@ static WsLayout ws_layout(const bita_config &c, int batch, int rows) {
     L.part_ml = take((size_t)batch * c.n_heads * ATTN_MAX_SPLITS * rows * 2 * 4);
     L.logits = take(M * c.vocab * 4);
     L.ssq = take(M * RMS_MAX_CHUNKS * 4);
+    L.kv_lo = take(2 * M * c.n_kv_heads * c.head_dim * 2);   // low planes of one layer's pass-row K and V
     L.total = off;
     return L;
 }
@@ -323,10 +324,12 @@ extern "C" int bita_verify_step(bita_model *m, const bita_kv *kv, const bita_tre
     float *part_o = (float *)(ws + L.part_o), *part_ml = (float *)(ws + L.part_ml);
     float *logits = d_logits ? d_logits : (float *)(ws + L.logits);
     float *ssq = (float *)(ws + L.ssq);
+    unsigned char *k_lo = ws + L.kv_lo;
     const int M = batch * td.rows, d = c.d_model, hd = c.head_dim;
     const RowScale rs_norm = {ssq, (d / 4 + 255) / 256, 1.0f / (float)d, c.rms_eps};
     const int64_t nq = (int64_t)c.n_heads * hd, nqkv = (int64_t)(c.n_heads + 2 * c.n_kv_heads) * hd;
     unsigned char *q_lo = q + (size_t)M * nq * 2;
+    unsigned char *v_lo = k_lo + (size_t)M * c.n_kv_heads * hd * 2;
     const GemmPlan p_qkv = gemm_plan(M, nqkv, d), p_o = gemm_plan(M, d, nq),
                    p_gu = gemm_plan(M, 2 * (int64_t)c.d_ffn, d), p_dn = gemm_plan(M, d, c.d_ffn),
                    p_lm = gemm_plan(M, c.vocab, d);
@@ -342,9 +345,9 @@ extern "C" int bita_verify_step(bita_model *m, const bita_kv *kv, const bita_tre
         timed_gemm(h, M, d, m->wqkv[l], nqkv, partial, nqkv, p_qkv, s);
         void *kt = (unsigned char *)kv->k_tree + l * kv_layer_tree, *vt = (unsigned char *)kv->v_tree + l * kv_layer_tree;
         launch_qkv_rope(partial, p_qkv.splits, batch, td, c.n_heads, c.n_kv_heads, hd, d_ctx_len, m->rope_cos,
-                        m->rope_sin, c.max_pos, q, q_lo, kt, vt, rs_norm, s);
+                        m->rope_sin, c.max_pos, q, q_lo, kt, vt, k_lo, v_lo, rs_norm, s);
         launch_tree_attention(td, q, q_lo, (unsigned char *)kv->k_cache + l * kv_layer_cache,
-                              (unsigned char *)kv->v_cache + l * kv_layer_cache, kt, vt, m->prompt_k[l],
+                              (unsigned char *)kv->v_cache + l * kv_layer_cache, kt, vt, k_lo, v_lo, m->prompt_k[l],
                               m->prompt_v[l], d_ctx_len, batch, c.n_heads, c.n_kv_heads, hd, c.n_prompt, kv->smax,
                               ap, part_o, part_ml, attn_out, true, s);
         timed_gemm(attn_out, M, nq, m->wo[l], d, partial, d, p_o, s);
@@ -394,7 +397,7 @@ extern "C" size_t bita_attention_workspace_bytes(int32_t batch, int32_t rows, in
 extern "C" int bita_tree_attention(const bita_tree_template *t, const void *d_q, const void *d_q_lo,
                                    const void *d_k_cache,
                                    const void *d_v_cache, const void *d_k_tree, const void *d_v_tree,
-                                   const void *d_prompt_k, const void *d_prompt_v, const int32_t *d_ctx_len,
+                                   const void *d_k_tree_lo, const void *d_v_tree_lo, const void *d_prompt_k, const void *d_prompt_v, const int32_t *d_ctx_len,
                                    int32_t batch, int32_t n_heads, int32_t n_kv_heads, int32_t head_dim,
                                    int32_t n_prompt, int32_t smax, int32_t ctx_hint, void *d_ws, size_t ws_bytes,
                                    void *d_out, void *stream) {
@@ -410,7 +413,7 @@ extern "C" int bita_tree_attention(const bita_tree_template *t, const void *d_q,
     const size_t need = align_up(p.part_o_bytes, 256) + align_up(p.part_ml_bytes, 256);
     if (ws_bytes < need) return bita_set_error(BITA_ERR_CAPACITY, "bita_tree_attention: workspace %zu < %zu", ws_bytes, need);
     float *part_o = (float *)d_ws, *part_ml = (float *)((unsigned char *)d_ws + align_up(p.part_o_bytes, 256));
-    launch_tree_attention(t->dev, d_q, d_q_lo, d_k_cache, d_v_cache, d_k_tree, d_v_tree, d_prompt_k, d_prompt_v, d_ctx_len,
+    launch_tree_attention(t->dev, d_q, d_q_lo, d_k_cache, d_v_cache, d_k_tree, d_v_tree, d_k_tree_lo, d_v_tree_lo, d_prompt_k, d_prompt_v, d_ctx_len,
                           batch, n_heads, n_kv_heads, head_dim, n_prompt, smax, p, part_o, part_ml, d_out,
                           false, (hipStream_t)stream);
     BITA_HIP_CHECK(hipGetLastError());

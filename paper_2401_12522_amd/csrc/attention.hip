@@ -11,7 +11,11 @@
 //  * S^T = K Q^T is computed so that its accumulator layout is already the B-operand layout
 //    of O^T = V^T P^T: the probabilities never leave registers;
 //  * the tree mask is derived from per-row ancestor bitsets and only evaluated in tiles that
-//    touch the prefix or the pass rows; pure cache tiles take an unmasked path.
+//    touch the prefix or the pass rows; pure cache tiles take an unmasked path;
+//  * the K/V of the pass rows are not yet rounded to the cache format: they come as two bf16
+//    planes.  Tiles over the pass rows hold 64 keys, each followed (4 slots later inside a
+//    lane's 8-key group) by a partner slot carrying the low plane; the two scores are added
+//    and the probability is copied to the partner before P.V, all lane-locally.
 // Partial (m, l, O) per split are combined by attn_merge_kernel.
 #include "common.h"
 
@@ -57,7 +61,8 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void tree_attn_kernel(
     TemplateDev t, const uint16_t *__restrict__ q, const uint16_t *__restrict__ q_lo,
     const uint16_t *__restrict__ k_cache,
     const uint16_t *__restrict__ v_cache, const uint16_t *__restrict__ k_tree,
-    const uint16_t *__restrict__ v_tree, const uint16_t *__restrict__ prompt_k,
+    const uint16_t *__restrict__ v_tree, const uint16_t *__restrict__ k_tree_lo,
+    const uint16_t *__restrict__ v_tree_lo, const uint16_t *__restrict__ prompt_k,
     const uint16_t *__restrict__ prompt_v, const int32_t *__restrict__ ctx_len, int Hq, int Hkv,
     int P, int smax, int n_splits, int n_qblk, float scale_log2, float *__restrict__ part_o,
     float *__restrict__ part_ml) {
@@ -75,8 +80,11 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void tree_attn_kernel(
     const int split = blockIdx.x, h = blockIdx.y / n_qblk, qblk = blockIdx.y % n_qblk, b = blockIdx.z;
     const int kvh = h / (Hq / Hkv);
     const int R = t.rows, Lc = ctx_len[b];
-    const int n_keys = P + Lc + R;
-    const int n_tiles = (n_keys + ATT_TK - 1) / ATT_TK;
+    // key axis: tiles over [prefix | cache] (128 keys each), then tiles over the pass rows
+    // (64 keys + 64 low-plane partner slots each)
+    const int n_ctx_keys = P + Lc;
+    const int n_ct = (n_ctx_keys + ATT_TK - 1) / ATT_TK;
+    const int n_tiles = n_ct + (R + ATT_TK / 2 - 1) / (ATT_TK / 2);
     const int per_split = (n_tiles + n_splits - 1) / n_splits;
     const int tile_begin = split * per_split;
     const int tile_end = min(n_tiles, tile_begin + per_split);
@@ -85,8 +93,10 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void tree_attn_kernel(
     const uint16_t *pk = prompt_k + (int64_t)kvh * P * HD, *pv = prompt_v + (int64_t)kvh * P * HD;
     const uint16_t *ck = k_cache + ((int64_t)b * Hkv + kvh) * smax * HD;
     const uint16_t *cv = v_cache + ((int64_t)b * Hkv + kvh) * smax * HD;
-    const uint16_t *tk = k_tree + ((int64_t)b * Hkv + kvh) * R * HD;
-    const uint16_t *tv = v_tree + ((int64_t)b * Hkv + kvh) * R * HD;
+    const int64_t tree_off = ((int64_t)b * Hkv + kvh) * R * HD;
+    const uint16_t *tk = k_tree + tree_off, *tv = v_tree + tree_off;
+    const uint16_t *tk_lo = k_tree_lo ? k_tree_lo + tree_off : nullptr;
+    const uint16_t *tv_lo = v_tree_lo ? v_tree_lo + tree_off : nullptr;
 
     // Query fragments (B operand of S^T = K Q^T) go to LDS once, as two bf16 planes (value and
     // rounding residual): fragment (plane, mt, ks) holds, for lane (g, c),
@@ -119,18 +129,25 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void tree_attn_kernel(
     }
 
     uint4 k_stage[K_IT], v_stage[V_IT][2];
-    auto src_row = [&](int kidx, const uint16_t *pp, const uint16_t *cp, const uint16_t *tp) -> const uint16_t * {
-        if (kidx < P) return pp + (int64_t)kidx * HD;
-        if (kidx < P + Lc) return cp + (int64_t)(kidx - P) * HD;
-        if (kidx < n_keys) return tp + (int64_t)(kidx - P - Lc) * HD;
-        return nullptr;
+    // source row of slot `slot` of tile `tile` (nullptr: padding, staged as zeros)
+    auto src_row = [&](int tile, int slot, const uint16_t *pp, const uint16_t *cp, const uint16_t *tp,
+                       const uint16_t *tp_lo) -> const uint16_t * {
+        if (tile < n_ct) {
+            const int kidx = tile * ATT_TK + slot;
+            if (kidx < P) return pp + (int64_t)kidx * HD;
+            if (kidx < n_ctx_keys) return cp + (int64_t)(kidx - P) * HD;
+            return nullptr;
+        }
+        const int j = (tile - n_ct) * (ATT_TK / 2) + (slot >> 3) * 4 + (slot & 3);   // pass row
+        if (j >= R) return nullptr;
+        if (slot & 4) return tp_lo ? tp_lo + (int64_t)j * HD : nullptr;            // partner slot
+        return tp + (int64_t)j * HD;
     };
     auto prefetch = [&](int tile) {
-        const int base = tile * ATT_TK;
 #pragma unroll
         for (int it = 0; it < K_IT; it++) {
             const int id = it * 256 + tid, key = id / GPK, part = id % GPK;
-            const uint16_t *p = src_row(base + key, pk, ck, tk);
+            const uint16_t *p = src_row(tile, key, pk, ck, tk, tk_lo);
             k_stage[it] = p ? *reinterpret_cast<const uint4 *>(p + part * 8) : make_uint4(0, 0, 0, 0);
         }
 #pragma unroll
@@ -138,7 +155,7 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void tree_attn_kernel(
             const int id = it * 256 + tid, kp = id / GPK, part = id % GPK;
 #pragma unroll
             for (int e = 0; e < 2; e++) {
-                const uint16_t *p = src_row(base + 2 * kp + e, pv, cv, tv);
+                const uint16_t *p = src_row(tile, 2 * kp + e, pv, cv, tv, tv_lo);
                 v_stage[it][e] = p ? *reinterpret_cast<const uint4 *>(p + part * 8) : make_uint4(0, 0, 0, 0);
             }
         }
@@ -173,7 +190,9 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void tree_attn_kernel(
         __syncthreads();
         if (tile + 1 < tile_end) prefetch(tile + 1);
         const int base = tile * ATT_TK;
-        if (base + kb >= n_keys) continue;                   // nothing but padding for this wave
+        const bool tree_tile = tile >= n_ct;
+        const int tree_j0 = (tile - n_ct) * (ATT_TK / 2);   // first pass row of a pass-row tile
+        if (tree_tile ? (tree_j0 + (kb >> 1) >= R) : (base + kb >= n_ctx_keys)) continue;   // only padding
 
         // S^T[key][q]: rows of sub-tile tt are keys 8*(i/4) + 4*tt + i%4, so that a lane ends
         // up with 8 consecutive keys (8g .. 8g+7) for its query row.
@@ -202,8 +221,8 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void tree_attn_kernel(
                 }
             }
 
-        const bool need_mask = (base < P) || (base + ATT_TK > P + Lc);
-        bf16x8 pf[MT];
+        const bool need_mask = tree_tile || (base < P) || (base + ATT_TK > n_ctx_keys);
+        bf16x8 pf[MT], pf_lo[MT];
 #pragma unroll
         for (int mt = 0; mt < MT; mt++) {
             float sv[8];
@@ -211,35 +230,32 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void tree_attn_kernel(
             for (int tt = 0; tt < 2; tt++)
 #pragma unroll
                 for (int r = 0; r < 4; r++) sv[tt * 4 + r] = s_acc[mt][tt][r] * scale_log2;
+            if (tree_tile) {                 // score = q.k_hi + q.k_lo; partner slots leave the softmax
+#pragma unroll
+                for (int e = 0; e < 4; e++) sv[e] += sv[e + 4];
+            }
             if (need_mask) {
-                // 8-bit visibility word for this lane's keys k0 .. k0+7, built with integer
-                // selects only: prefix -> mask rows, cache -> all rows, pass rows -> ancestor bits.
+                // 8-bit visibility word for this lane's slots, built with integer selects only:
+                // prefix -> mask rows, cache -> all rows, pass rows -> ancestor bits.
                 const int rq = row0 + mt * 16 + c;
-                const int k0 = base + kb + 8 * g;
                 uint32_t bits = 0;
                 if (row_ok[mt]) {
-                    const int j0 = k0 - P - Lc;                  // first key relative to the pass rows
-                    uint64_t win = 0;                            // ancestor bits j0 .. j0+7 in bits 0..7
-                    const uint64_t *a = t.anc + (int64_t)rq * t.words;
-                    if (j0 > -8 && j0 < R) {
-                        if (j0 < 0) {
-                            win = a[0] << (-j0);
-                        } else {
-                            const int w = j0 >> 6, sh = j0 & 63;
-                            win = a[w] >> sh;
-                            if (sh > 56 && w + 1 < t.words) win |= a[w + 1] << (64 - sh);
-                        }
-                    }
-                    const uint32_t tree_bits = (uint32_t)win & 0xFFu;
+                    if (tree_tile) {
+                        const int j0 = tree_j0 + ((kb >> 3) + g) * 4;     // this lane's 4 pass rows (4-aligned)
+                        uint32_t four = 0;
+                        if (j0 < R) four = (uint32_t)(t.anc[(int64_t)rq * t.words + (j0 >> 6)] >> (j0 & 63)) & 0xFu;
 #pragma unroll
-                    for (int e = 0; e < 8; e++) {
-                        const int kidx = k0 + e;
-                        const uint32_t in_prefix = kidx < P ? 1u : 0u;
-                        const uint32_t in_cache = (kidx >= P && kidx < P + Lc) ? 1u : 0u;
-                        const uint32_t in_tree = (kidx >= P + Lc && kidx < n_keys) ? 1u : 0u;
-                        const uint32_t v = (in_prefix & (row_mask[mt] ? 1u : 0u)) | in_cache |
-                                           (in_tree & (tree_bits >> e));
-                        bits |= (v & 1u) << e;
+                        for (int e = 0; e < 4; e++)
+                            bits |= ((j0 + e < R) ? ((four >> e) & 1u) : 0u) << e;
+                    } else {
+                        const int k0 = base + kb + 8 * g;
+#pragma unroll
+                        for (int e = 0; e < 8; e++) {
+                            const int kidx = k0 + e;
+                            const uint32_t in_prefix = kidx < P ? 1u : 0u;
+                            const uint32_t in_cache = (kidx >= P && kidx < n_ctx_keys) ? 1u : 0u;
+                            bits |= ((in_prefix & (row_mask[mt] ? 1u : 0u)) | in_cache) << e;
+                        }
                     }
                 }
 #pragma unroll
@@ -254,16 +270,27 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void tree_attn_kernel(
             const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
             const float alpha = fast_exp2(m_run[mt] - m_use);
             m_run[mt] = m_new;
+            // probabilities as two bf16 planes (value and rounding residual), like every other
+            // MFMA input of the pass
             float ps = 0.f;
-            uint32_t pk2[4];
+            uint32_t pk2[4], pl2[4];
 #pragma unroll
             for (int e = 0; e < 8; e += 2) {
                 const float p0 = fast_exp2(sv[e] - m_use), p1 = fast_exp2(sv[e + 1] - m_use);
                 ps += p0 + p1;
-                pk2[e >> 1] = cvt_pk_bf16(p0, p1);
+                const uint32_t hi = cvt_pk_bf16(p0, p1);
+                pk2[e >> 1] = hi;
+                pl2[e >> 1] = cvt_pk_bf16(p0 - __uint_as_float(hi << 16), p1 - __uint_as_float(hi & 0xFFFF0000u));
+            }
+            if (tree_tile) {                 // the low-plane value rows take the same probabilities
+                pk2[2] = pk2[0];
+                pk2[3] = pk2[1];
+                pl2[2] = pl2[0];
+                pl2[3] = pl2[1];
             }
             l_run[mt] = l_run[mt] * alpha + ps;
             pf[mt] = __builtin_bit_cast(bf16x8, make_uint4(pk2[0], pk2[1], pk2[2], pk2[3]));
+            pf_lo[mt] = __builtin_bit_cast(bf16x8, make_uint4(pl2[0], pl2[1], pl2[2], pl2[3]));
 #pragma unroll
             for (int nt = 0; nt < NTN; nt++) o_acc[nt][mt] *= alpha;
         }
@@ -273,8 +300,10 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void tree_attn_kernel(
             const bf16x8 vf = __builtin_bit_cast(
                 bf16x8, *reinterpret_cast<const uint4 *>(vt_lds + (nt * 16 + c) * VSTR + (kb + 8 * g) * 2));
 #pragma unroll
-            for (int mt = 0; mt < MT; mt++)
+            for (int mt = 0; mt < MT; mt++) {
                 o_acc[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[mt], o_acc[nt][mt], 0, 0, 0);
+                o_acc[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf_lo[mt], o_acc[nt][mt], 0, 0, 0);
+            }
         }
     }
 
@@ -400,8 +429,7 @@ __global__ void attn_merge_kernel(const float *__restrict__ part_o, const float 
 
 AttnPlan attn_plan(int batch, int rows, int n_heads, int hd, int ctx_hint, int n_prompt) {
     AttnPlan p;
-    const int n_keys = n_prompt + ctx_hint + rows;
-    const int n_tiles = (n_keys + ATT_TK - 1) / ATT_TK;
+    const int n_tiles = (n_prompt + ctx_hint + ATT_TK - 1) / ATT_TK + (rows + ATT_TK / 2 - 1) / (ATT_TK / 2);
     const int n_qblk = (rows + 79) / 80;
     const int wgs = batch * n_heads * n_qblk;
     // the kernel's LDS footprint allows one workgroup per CU: ask for one round of <= 256
@@ -420,7 +448,8 @@ AttnPlan attn_plan(int batch, int rows, int n_heads, int hd, int ctx_hint, int n
 
 template <int HD, int MT>
 static void launch_attn_t(const TemplateDev &t, const void *q, const void *q_lo, const void *k_cache, const void *v_cache,
-                          const void *k_tree, const void *v_tree, const void *prompt_k,
+                          const void *k_tree, const void *v_tree, const void *k_tree_lo, const void *v_tree_lo,
+                          const void *prompt_k,
                           const void *prompt_v, const int32_t *ctx_len, int batch, int Hq, int Hkv, int P,
                           int smax, const AttnPlan &p, float *part_o, float *part_ml, hipStream_t s) {
     constexpr int smem = att_smem_bytes<HD, MT>();
@@ -435,23 +464,25 @@ static void launch_attn_t(const TemplateDev &t, const void *q, const void *q_lo,
     dim3 grid(p.splits, Hq * n_qblk, batch);
     hipLaunchKernelGGL((tree_attn_kernel<HD, MT>), grid, dim3(ATT_WAVES * 64), smem, s, t,
                        (const uint16_t *)q, (const uint16_t *)q_lo, (const uint16_t *)k_cache, (const uint16_t *)v_cache,
-                       (const uint16_t *)k_tree, (const uint16_t *)v_tree, (const uint16_t *)prompt_k,
+                       (const uint16_t *)k_tree, (const uint16_t *)v_tree, (const uint16_t *)k_tree_lo,
+                       (const uint16_t *)v_tree_lo, (const uint16_t *)prompt_k,
                        (const uint16_t *)prompt_v, ctx_len, Hq, Hkv, P, smax, p.splits, n_qblk, scale_log2,
                        part_o, part_ml);
 }
 
 void launch_tree_attention(const TemplateDev &t, const void *q, const void *q_lo, const void *k_cache, const void *v_cache,
-                           const void *k_tree, const void *v_tree, const void *prompt_k,
+                           const void *k_tree, const void *v_tree, const void *k_tree_lo, const void *v_tree_lo,
+                           const void *prompt_k,
                            const void *prompt_v, const int32_t *ctx_len, int batch, int Hq, int Hkv, int hd,
                            int P, int smax, const AttnPlan &p, float *part_o, float *part_ml, void *out,
                            bool out_as_fragments, hipStream_t s) {
     const bool small = t.rows <= 16;
     if (hd == 128) {
-        if (small) launch_attn_t<128, 1>(t, q, q_lo, k_cache, v_cache, k_tree, v_tree, prompt_k, prompt_v, ctx_len, batch, Hq, Hkv, P, smax, p, part_o, part_ml, s);
-        else launch_attn_t<128, 5>(t, q, q_lo, k_cache, v_cache, k_tree, v_tree, prompt_k, prompt_v, ctx_len, batch, Hq, Hkv, P, smax, p, part_o, part_ml, s);
+        if (small) launch_attn_t<128, 1>(t, q, q_lo, k_cache, v_cache, k_tree, v_tree, k_tree_lo, v_tree_lo, prompt_k, prompt_v, ctx_len, batch, Hq, Hkv, P, smax, p, part_o, part_ml, s);
+        else launch_attn_t<128, 5>(t, q, q_lo, k_cache, v_cache, k_tree, v_tree, k_tree_lo, v_tree_lo, prompt_k, prompt_v, ctx_len, batch, Hq, Hkv, P, smax, p, part_o, part_ml, s);
     } else {
-        if (small) launch_attn_t<64, 1>(t, q, q_lo, k_cache, v_cache, k_tree, v_tree, prompt_k, prompt_v, ctx_len, batch, Hq, Hkv, P, smax, p, part_o, part_ml, s);
-        else launch_attn_t<64, 5>(t, q, q_lo, k_cache, v_cache, k_tree, v_tree, prompt_k, prompt_v, ctx_len, batch, Hq, Hkv, P, smax, p, part_o, part_ml, s);
+        if (small) launch_attn_t<64, 1>(t, q, q_lo, k_cache, v_cache, k_tree, v_tree, k_tree_lo, v_tree_lo, prompt_k, prompt_v, ctx_len, batch, Hq, Hkv, P, smax, p, part_o, part_ml, s);
+        else launch_attn_t<64, 5>(t, q, q_lo, k_cache, v_cache, k_tree, v_tree, k_tree_lo, v_tree_lo, prompt_k, prompt_v, ctx_len, batch, Hq, Hkv, P, smax, p, part_o, part_ml, s);
     }
     const int heads_per_block = (256 / (hd / 4)) < Hq ? (256 / (hd / 4)) : Hq;
     hipLaunchKernelGGL(attn_merge_kernel, dim3(t.rows, (Hq + heads_per_block - 1) / heads_per_block, batch),

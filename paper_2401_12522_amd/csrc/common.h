@@ -94,7 +94,8 @@ void launch_rmsnorm_prep(float *x, const float *partial, int splits, int m_rows,
 void launch_qkv_rope(const float *partial, int splits, int batch, const TemplateDev &t,
                      int n_heads, int n_kv_heads, int hd, const int32_t *ctx_len,
                      const float *rope_cos, const float *rope_sin, int max_pos,
-                     void *q, void *q_lo, void *k_tree, void *v_tree, const RowScale &rs, hipStream_t s);
+                     void *q, void *q_lo, void *k_tree, void *v_tree, void *k_tree_lo, void *v_tree_lo,
+                     const RowScale &rs, hipStream_t s);
 void launch_silu_mul(const float *partial, int splits, int m_rows, int d_ffn, void *act_frag,
                      const RowScale &rs, hipStream_t s);
 void launch_select(const float *logits, int batch, const TemplateDev &t, int vocab, int kmax,
@@ -102,8 +103,10 @@ void launch_select(const float *logits, int batch, const TemplateDev &t, int voc
 
 struct AttnPlan { int splits; size_t part_o_bytes, part_ml_bytes; };
 AttnPlan attn_plan(int batch, int rows, int n_heads, int hd, int ctx_hint, int n_prompt);
+// k_tree_lo / v_tree_lo: low bf16 plane of the pass rows' K/V (nullable)
 void launch_tree_attention(const TemplateDev &t, const void *q, const void *q_lo, const void *k_cache,
                            const void *v_cache, const void *k_tree, const void *v_tree,
+                           const void *k_tree_lo, const void *v_tree_lo,
                            const void *prompt_k, const void *prompt_v, const int32_t *ctx_len,
                            int batch, int n_heads, int n_kv_heads, int hd, int n_prompt, int smax,
                            const AttnPlan &p, float *part_o, float *part_ml, void *out,

@@ -72,12 +72,14 @@ __global__ __launch_bounds__(256) void rmsnorm_prep_kernel(float *__restrict__ x
 // ---------------------------------------------------------------------------------------
 // QKV epilogue: sum split-K partials, rotate q and k by the row's position
 // ctx_len + depth(row) in the half-split pairing, write q [B][R][Hq][hd] and the rows'
-// k/v into the per-pass tree scratch [B][Hkv][R][hd].  q is written as hi and lo bf16 planes.
+// k/v into the per-pass tree scratch [B][Hkv][R][hd].  q, k and v are all written as hi and lo
+// bf16 planes; only the hi planes of accepted rows are ever committed to the cache.
 __global__ __launch_bounds__(64) void qkv_rope_kernel(
     const float *__restrict__ partial, int splits, int M, TemplateDev t, int Hq, int Hkv, int hd,
     const int32_t *__restrict__ ctx_len, const float *__restrict__ rope_cos,
     const float *__restrict__ rope_sin, int max_pos, uint16_t *__restrict__ q,
-    uint16_t *__restrict__ q_lo, uint16_t *__restrict__ k_tree, uint16_t *__restrict__ v_tree, RowScale rs) {
+    uint16_t *__restrict__ q_lo, uint16_t *__restrict__ k_tree, uint16_t *__restrict__ v_tree,
+    uint16_t *__restrict__ k_tree_lo, uint16_t *__restrict__ v_tree_lo, RowScale rs) {
     const int row = blockIdx.x, head = blockIdx.y;       // head over Hq + 2*Hkv
     const int b = row / t.rows, r = row % t.rows;
     const int half = hd >> 1, i = threadIdx.x;
@@ -98,9 +100,13 @@ __global__ __launch_bounds__(64) void qkv_rope_kernel(
         dst = q + ((int64_t)row * Hq + head) * hd;
         dst_lo = q_lo + ((int64_t)row * Hq + head) * hd;
     } else if (head < Hq + Hkv) {
-        dst = k_tree + (((int64_t)b * Hkv + (head - Hq)) * t.rows + r) * hd;
+        const int64_t o = (((int64_t)b * Hkv + (head - Hq)) * t.rows + r) * hd;
+        dst = k_tree + o;
+        dst_lo = k_tree_lo + o;      // the pass keeps the rounding residual of its own K/V rows
     } else {
-        dst = v_tree + (((int64_t)b * Hkv + (head - Hq - Hkv)) * t.rows + r) * hd;
+        const int64_t o = (((int64_t)b * Hkv + (head - Hq - Hkv)) * t.rows + r) * hd;
+        dst = v_tree + o;
+        dst_lo = v_tree_lo + o;
     }
     if (head < Hq + Hkv) {
         int pos = ctx_len[b] + t.depth[r];
@@ -115,7 +121,7 @@ __global__ __launch_bounds__(64) void qkv_rope_kernel(
     split_bf16(hi, b_hi, b_lo);
     dst[i] = a_hi;
     dst[i + half] = b_hi;
-    if (dst_lo) {                                   // queries keep their rounding residual as well
+    if (dst_lo) {
         dst_lo[i] = a_lo;
         dst_lo[i + half] = b_lo;
     }
@@ -238,10 +244,11 @@ void launch_rmsnorm_prep(float *x, const float *partial, int splits, int M, int 
 void launch_qkv_rope(const float *partial, int splits, int batch, const TemplateDev &t, int Hq,
                      int Hkv, int hd, const int32_t *ctx_len, const float *rope_cos,
                      const float *rope_sin, int max_pos, void *q, void *q_lo, void *k_tree, void *v_tree,
-                     const RowScale &rs, hipStream_t s) {
+                     void *k_tree_lo, void *v_tree_lo, const RowScale &rs, hipStream_t s) {
     hipLaunchKernelGGL(qkv_rope_kernel, dim3(batch * t.rows, Hq + 2 * Hkv), dim3(64), 0, s, partial,
                        splits, batch * t.rows, t, Hq, Hkv, hd, ctx_len, rope_cos, rope_sin, max_pos,
-                       (uint16_t *)q, (uint16_t *)q_lo, (uint16_t *)k_tree, (uint16_t *)v_tree, rs);
+                       (uint16_t *)q, (uint16_t *)q_lo, (uint16_t *)k_tree, (uint16_t *)v_tree,
+                       (uint16_t *)k_tree_lo, (uint16_t *)v_tree_lo, rs);
 }
 void launch_silu_mul(const float *partial, int splits, int M, int F, void *act_frag, const RowScale &rs,
                      hipStream_t s) {

@@ -67,14 +67,20 @@ def _attention_case(bita, B, Hq, Hkv, hd, P, ctx_lens, tree_parent, attach, n_ma
     q = q_hi + (q_lo if two_plane_q else 0.0)          # what the kernel is given, exactly
     kc, vc = r16(B, Hkv, smax, hd), r16(B, Hkv, smax, hd)
     kt, vt = r16(B, Hkv, R, hd), r16(B, Hkv, R, hd)
+    kt_lo = vt_lo = None
+    if two_plane_q:     # the pass rows' K/V carry a second plane too (large here, so that a
+        kt_lo = r16(B, Hkv, R, hd) * 0.25               # dropped or misplaced plane fails the test)
+        vt_lo = r16(B, Hkv, R, hd) * 0.25
     pk, pv = (r16(Hkv, P, hd), r16(Hkv, P, hd)) if P else (None, None)
     tmpl = bita.TreeTemplate(tin.parent, tin.is_mask, tin.n_tree, n_mask)
     tb = lambda a: None if a is None else torch.tensor(a).to(torch.bfloat16).cuda()   # noqa: E731
     out = bita.tree_attention(tmpl, tb(q_hi), tb(kc), tb(vc), tb(kt), tb(vt), tb(pk), tb(pv),
                               torch.tensor(ctx_lens, dtype=torch.int32, device="cuda"), max(ctx_lens),
-                              q_lo=tb(q_lo))
+                              q_lo=tb(q_lo), k_tree_lo=tb(kt_lo), v_tree_lo=tb(vt_lo))
     torch.cuda.synchronize()
     out = out.to(torch.float64).cpu().numpy().reshape(B, R, Hq, hd)
+    if two_plane_q:
+        kt, vt = kt + kt_lo, vt + vt_lo                 # what the kernel is given, exactly
     worst = 0.0
     for b in range(B):
         Lc = ctx_lens[b]
