@@ -36,18 +36,19 @@ __host__ __device__ __forceinline__ int64_t packed_block(int64_t t, int64_t ks, 
     return ((ks >> 1) * n_tiles + t) * 2 + (ks & 1);
 }
 
-// wait until at most N vector-memory operations of this wave are outstanding
+// wait until at most N vector-memory operations of this wave are outstanding and all of its
+// LDS reads have returned
 template <int N>
-__device__ __forceinline__ void wait_vmcnt() {
+__device__ __forceinline__ void wait_vmcnt_lds() {
     static_assert(N >= 0 && N < 64, "vmcnt range");
-    __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0xF << 8));
+    __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0x0 << 8));
 }
 
 // Workgroup barrier without the memory fences of __syncthreads(): those would drain every
 // outstanding vector-memory operation (vmcnt(0)) and with it the prefetched stages.  The
-// data hazards are covered explicitly: the wave waits for its own LDS-bound loads of the
-// stage about to be read (wait_vmcnt) before arriving, and its LDS reads of the previous
-// stage have been consumed by MFMAs, hence completed, before it arrives.
+// data hazards are covered explicitly by the wait that precedes it: the wave's own LDS-bound
+// loads of the stage about to be read have landed, and its LDS reads of the previous stage
+// (whose slot is refilled after the barrier) have returned.
 __device__ __forceinline__ void wg_barrier() {
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_barrier();
@@ -70,9 +71,10 @@ struct GemmCfg {
     static constexpr int PL = SPLIT ? 2 : 1;
     static constexpr int NFRAG = PL * MT * KC;                  // A fragments per stage
     static constexpr int FPW = (NFRAG + WAVES - 1) / WAVES;     // fetched per wave per stage
-    static constexpr int SLOT_FRAGS = FPW * WAVES;              // incl. padding fragments
     static constexpr int LOADS = NW * KC + FPW;                 // vector-memory loads per wave per stage
-    static constexpr int SMEM = D * SLOT_FRAGS * 1024;
+    // every wave issues FPW fragment loads per stage (the vmcnt bookkeeping counts on it);
+    // those beyond NFRAG land in one shared dump slot after the ring
+    static constexpr int SMEM = (D * NFRAG + 1) * 1024;
     static_assert((D - 2) * LOADS < 64, "vmcnt counter range");
 };
 
@@ -82,7 +84,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
     const uint4 *__restrict__ Wp, int NT, int KS, float *__restrict__ out, int64_t ldo,
     int ksteps_per_split) {
     using C = GemmCfg<MT, NW, SPLIT, KC, D, WAVES>;
-    extern __shared__ __attribute__((aligned(16))) uint4 a_lds[];   // [D][SLOT_FRAGS][64]
+    extern __shared__ __attribute__((aligned(16))) uint4 a_lds[];   // [D][NFRAG][64] + dump slot
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int t0 = (blockIdx.x * WAVES + wave) * NW;
@@ -124,23 +126,22 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
             // fragment (plane, ks, mtg) starts at ((plane * KS + ks) * m_tiles + mtg) * 64 uint4
             const uint4 *src = ok ? A_frag + ((int64_t)plane * planes_stride_f + (int64_t)(ks0 + s) * m_tiles + mtg) * 64 + lane
                                   : &g_zero16;
-            uint4 *dst = a_lds + ((SLOT * C::SLOT_FRAGS + f) * 64);   // wave-uniform; lane l lands at dst[l]
+            uint4 *dst = a_lds + (f < C::NFRAG ? SLOT * C::NFRAG + f : D * C::NFRAG) * 64;   // wave-uniform; lane l lands at dst[l]
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
                                              (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
         }
     };
     auto compute = [&](auto slot_c, int stage) {
         constexpr int SLOT = decltype(slot_c)::value;
-        const int ks0 = ks_begin + stage * KC;
+        (void)stage;
 #pragma unroll
-        for (int s = 0; s < KC; s++) {
-            if (ks0 + s >= ks_end) break;
+        for (int s = 0; s < KC; s++) {          // k-steps past the end were loaded as zeros
 #pragma unroll
             for (int pl = 0; pl < C::PL; pl++)
 #pragma unroll
                 for (int i = 0; i < MT; i++) {
                     const int f = (pl * MT + i) * KC + s;
-                    const bf16x8 a = __builtin_bit_cast(bf16x8, a_lds[(SLOT * C::SLOT_FRAGS + f) * 64 + lane]);
+                    const bf16x8 a = __builtin_bit_cast(bf16x8, a_lds[(SLOT * C::NFRAG + f) * 64 + lane]);
 #pragma unroll
                     for (int j = 0; j < NW; j++)
                         acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
@@ -148,32 +149,37 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
                 }
         }
     };
-    // One pipeline step for stage c living in slot U: wait for its data (leaving the newer
+    // One pipeline step for stage c living in slot U: wait for its data (leaving the D-2 newer
     // stages in flight), make it visible to the workgroup, refill the slot freed by stage
-    // c-1, multiply.
+    // c-1, multiply.  Every step issues exactly C::LOADS loads, also for stages past the end
+    // (those read the zero granule), so the wait count is a compile-time constant and the
+    // compiler's own wait-count analysis sees every register dependency satisfied by it; with
+    // data-dependent counts it drains the whole ring at the loop head instead.
     auto step = [&](auto u_c, int c) {
         constexpr int U = decltype(u_c)::value;
         constexpr int PRE = (U + D - 1) % D;
-        const int newer = min(D - 2, n_stages - 1 - c);
-        static_for<0, D - 1>([&](auto j_c) {
-            constexpr int J = decltype(j_c)::value;
-            if (newer == J) wait_vmcnt<J * C::LOADS>();
-        });
+        wait_vmcnt_lds<(D - 2) * C::LOADS>();
         wg_barrier();
-        if (c + D - 1 < n_stages) issue(std::integral_constant<int, PRE>{}, c + D - 1);
+        issue(std::integral_constant<int, PRE>{}, c + D - 1);
         compute(u_c, c);
     };
 
+    static_for<0, D - 1>([&](auto u_c) { issue(u_c, decltype(u_c)::value); });
+    int c = 0;
+    for (; c + D <= n_stages; c += D)            // branch-free body: D steps, slots 0..D-1
+        static_for<0, D>([&](auto u_c) { step(u_c, c + decltype(u_c)::value); });
+    // Remaining n_stages % D steps: nothing more to fetch.  Stages c .. c+D-2 were issued by the
+    // loop above (or the prologue) with C::LOADS loads each, so step U leaves D-2-U stages in
+    // flight.  (Issuing dummy loads here instead would not keep the count: the compiler drops
+    // the register loads whose values are never used, and the wait would then cover too little.)
     static_for<0, D - 1>([&](auto u_c) {
         constexpr int U = decltype(u_c)::value;
-        if (U < n_stages) issue(u_c, U);
+        if (c + U < n_stages) {
+            wait_vmcnt_lds<(D - 2 - U) * C::LOADS>();
+            wg_barrier();
+            compute(u_c, c + U);
+        }
     });
-    for (int c = 0; c < n_stages; c += D) {
-        static_for<0, D>([&](auto u_c) {
-            constexpr int U = decltype(u_c)::value;
-            if (c + U < n_stages) step(u_c, c + U);
-        });
-    }
 
     // D layout: lane (g = lane/16, c = lane%16) holds rows 4g..4g+3, column c of each tile.
     const int g = lane >> 4, cc = lane & 15;
@@ -228,11 +234,14 @@ __global__ void to_fragments_kernel(const uint16_t *__restrict__ a_hi, const uin
     dst[(((int64_t)plane * KS + ks) * m_tiles + mt) * 64 + lane] = v;
 }
 
-// Launch shapes: variant v -> NW = 1 << v weight tiles per wave (64, 128, 256 columns per
-// workgroup of 4 waves), one k-step per stage, ring of 4.  Wide groups reuse each activation
-// fragment for more weight tiles (the L2->LDS slab traffic is what limits narrow ones) but
-// produce wider split-K partials, so narrow matrices take the narrower shapes.
-#define GEMM_N_VARIANTS 3
+// Launch shapes.  Wide groups reuse each activation fragment for more weight tiles (the
+// L2->LDS slab traffic is what limits narrow ones) but produce wider split-K partials; deep
+// rings and more waves keep more weight bytes in flight per CU.
+struct GemmVariant { int nw, waves, depth; };
+static const GemmVariant g_variants[] = {
+    {1, 4, 4}, {2, 4, 4}, {4, 4, 4}, {2, 8, 6}, {4, 8, 6},
+};
+#define GEMM_N_VARIANTS ((int)(sizeof(g_variants) / sizeof(g_variants[0])))
 static int g_force_variant = -1, g_force_splits = -1;
 void gemm_force_plan(int variant, int splits) { g_force_variant = variant; g_force_splits = splits; }
 
@@ -244,9 +253,10 @@ GemmPlan gemm_plan(int m_rows, int64_t n_rows, int64_t k) {
     // than 8 for the narrow ones, whose partial sums are re-read by a row-wise consumer.
     p.variant = (NT >= 1024) ? 2 : 1;
     if (g_force_variant >= 0 && g_force_variant < GEMM_N_VARIANTS) p.variant = g_force_variant;
-    const int tiles_wg = 4 << p.variant;
+    const GemmVariant &v = g_variants[p.variant];
+    const int tiles_wg = v.nw * v.waves;
     const int64_t wgs_n = (NT + tiles_wg - 1) / tiles_wg;
-    int64_t splits = 512 / wgs_n;
+    int64_t splits = (v.waves > 4 ? 256 : 512) / wgs_n;
     const int64_t max_splits = KS / 8;                          // at least 8 stages per split
     if (splits > max_splits) splits = max_splits;
     if (NT < 512 && splits > 8) splits = 8;
@@ -260,10 +270,10 @@ GemmPlan gemm_plan(int m_rows, int64_t n_rows, int64_t k) {
     return p;
 }
 
-template <int MT, int NW, bool SPLIT>
+template <int MT, int NW, bool SPLIT, int WAVES, int D>
 static void launch_gemm_t(const void *a_frag, int M, int64_t K, const void *w, int64_t N, float *out, int64_t ldo,
                           const GemmPlan &p, hipStream_t s) {
-    constexpr int KC = 1, D = 4, WAVES = 4;
+    constexpr int KC = 1;
     using C = GemmCfg<MT, NW, SPLIT, KC, D, WAVES>;
     static bool attr_set = false;
     if (!attr_set) {
@@ -281,11 +291,11 @@ static void launch_gemm_t(const void *a_frag, int M, int64_t K, const void *w, i
 template <int MT, bool SPLIT>
 static void launch_gemm_v(const void *a_frag, int M, int64_t K, const void *w, int64_t N, float *out, int64_t ldo,
                           const GemmPlan &p, hipStream_t s) {
+#define V(i, nw, waves, d) case i: launch_gemm_t<MT, nw, SPLIT, waves, d>(a_frag, M, K, w, N, out, ldo, p, s); break;
     switch (p.variant) {
-        case 0: launch_gemm_t<MT, 1, SPLIT>(a_frag, M, K, w, N, out, ldo, p, s); break;
-        case 1: launch_gemm_t<MT, 2, SPLIT>(a_frag, M, K, w, N, out, ldo, p, s); break;
-        default: launch_gemm_t<MT, 4, SPLIT>(a_frag, M, K, w, N, out, ldo, p, s); break;
+        V(0, 1, 4, 4) V(1, 2, 4, 4) V(2, 4, 4, 4) V(3, 2, 8, 6) V(4, 4, 8, 6)
     }
+#undef V
 }
 
 // a_frag: activations in fragment order, [planes][k-steps][m-tiles][64] x 16 bytes;
