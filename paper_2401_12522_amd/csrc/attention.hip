@@ -2,26 +2,39 @@
 // the pass attends to all cached tokens and to its ancestors-or-self among the rows of the
 // pass; mask-token rows additionally attend to the per-layer prompt prefix.
 //
-// Flash-style, one workgroup per (sequence, query head, key split):
-//  * the key axis [prefix | cache | pass rows] is cut into 128-key tiles; K tiles are staged
-//    in LDS row-major, V tiles transposed, so both feed v_mfma_f32_16x16x32_bf16 with one
-//    16-byte LDS read per operand;
-//  * the 4 wavefronts split each tile's keys (32 each) and keep their own online-softmax
-//    state for all query rows, merged through LDS at the end (fixed order, deterministic);
+// Flash-style, one workgroup per (sequence, query head, 16 query rows, key split):
+//  * A workgroup owns one m-tile of 16 query rows and walks the key axis
+//    [prefix | cache | pass rows] in chunks of 32 key slots.  Its 4 wavefronts take chunks
+//    round-robin and never synchronise inside the loop: each keeps its own online-softmax
+//    state, merged through LDS once at the end (fixed order, deterministic).  With 16 rows
+//    per workgroup no split over the keys is needed to fill the chip at the verify shapes,
+//    so the output is normalised and written in place (no partial results, no second kernel)
+//    unless the context is long enough for the planner to ask for key splits.
+//  * Workgroups that read the same K/V head are placed on the same XCD (consecutive workgroup
+//    ids go round-robin over the 8 XCDs), so a head's K/V comes from HBM once and from that
+//    XCD's L2 for the other m-tiles and query heads of the group.
+//  * K chunks go from global memory straight into MFMA A-operand registers (16 bytes per
+//    lane and k-step); V chunks go straight into LDS with global->LDS loads, row-major, and
+//    are read back transposed (ds_read_tr16_b64) as the A operand of O^T = V^T P^T.  Each
+//    wave runs a ring of chunks in flight with compile-time wait counts.
 //  * S^T = K Q^T is computed so that its accumulator layout is already the B-operand layout
-//    of O^T = V^T P^T: the probabilities never leave registers;
-//  * the tree mask is derived from per-row ancestor bitsets and only evaluated in tiles that
-//    touch the prefix or the pass rows; pure cache tiles take an unmasked path;
-//  * the K/V of the pass rows are not yet rounded to the cache format: they come as two bf16
-//    planes.  Tiles over the pass rows hold 64 keys, each followed (4 slots later inside a
-//    lane's 8-key group) by a partner slot carrying the low plane; the two scores are added
-//    and the probability is copied to the partner before P.V, all lane-locally.
-// Partial (m, l, O) per split are combined by attn_merge_kernel.
+//    of O^T = V^T P^T: the probabilities never leave registers.  Queries, probabilities and
+//    the pass rows' K/V are each two bf16 planes (value and rounding residual).
+//  * The K/V of the pass rows are not yet rounded to the cache format.  A chunk over the pass
+//    rows holds 16 keys, each followed (4 slots later inside a lane's 8-slot group) by a
+//    partner slot carrying the low plane; the two scores are added and the probability is
+//    copied to the partner before P.V, all lane-locally.
+//  * The tree mask is derived from per-row ancestor bitsets and only evaluated in chunks that
+//    touch the prefix, the ragged end of the cache or the pass rows.  A parent always has a
+//    smaller row index than its child, so m-tile mt skips pass-row chunks beyond its own.
 #include "common.h"
+#include <type_traits>
 
-#define ATT_TK 128
-#define ATT_WAVES 4
-#define ATT_PAD 8   // bf16 elements of row padding in both LDS tiles
+#define ATT_WAVES 8
+#define ATT_CHUNK 32            // key slots per chunk
+
+// one all-zero K/V row (head dim <= 128): padding slots read it like any other row
+static __device__ uint4 g_att_zero_row[16] = {};
 
 // 2^x for x <= 0 or -inf (softmax arguments): the bare hardware instruction, without the
 // denormal-range fix-up of exp2f (results below 2^-126 flush to zero, which is what we want)
@@ -34,61 +47,120 @@ __device__ __forceinline__ uint32_t cvt_pk_bf16(float lo, float hi) {
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
 
-template <int HD>
-struct AttSmem {
-    static constexpr int K_STRIDE = HD + ATT_PAD;          // bf16 per K row
-    static constexpr int V_STRIDE = ATT_TK + ATT_PAD;      // bf16 per V^T row
-    static constexpr int K_BYTES = ATT_TK * K_STRIDE * 2;
-    static constexpr int V_BYTES = HD * V_STRIDE * 2;
-    static constexpr int TILE_BYTES = K_BYTES + V_BYTES;
+// wait until at most N vector-memory operations of this wave are outstanding and all of its
+// LDS reads have returned; nothing may be moved across it
+template <int N>
+__device__ __forceinline__ void att_wait() {
+    static_assert(N >= 0 && N < 64, "vmcnt range");
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0x0 << 8));
+    asm volatile("" ::: "memory");
+}
+template <int I, int N, typename F>
+__device__ __forceinline__ void att_static_for(F &&f) {
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        att_static_for<I + 1, N>(f);
+    }
+}
+
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+
+// Transposed 16-bit LDS read (ds_read_b64_tr_b16): lane j of a 16-lane group receives, as
+// element e, column j%4 of the four 16-bit values that lane 4e + j/4 of the group addressed.
+// Issued as bare instructions: the V chunks reach LDS through global->LDS loads whose
+// completion this kernel tracks itself (att_wait), and the compiler, unable to tell the ring
+// slots apart, would otherwise drain every outstanding load before each such read.  The
+// results are only valid after lds_wait_all().
+template <int OFFSET>
+__device__ __forceinline__ s16x4 lds_read_tr16(uint32_t lds_addr) {
+    static_assert(OFFSET >= 0 && OFFSET < 65536, "ds offset field");
+    s16x4 v;
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(lds_addr), "n"(OFFSET));
+    return v;
+}
+// wait for every LDS read of this wave; the registers pass through the statement so that no
+// use of them can be scheduled ahead of it
+template <int N>
+__device__ __forceinline__ void lds_wait_all(s16x4 (&v)[N][2]) {
+    static_assert(N == 4 || N == 8, "head dim 64 or 128");
+    if constexpr (N == 8)
+        asm volatile("s_waitcnt lgkmcnt(0)"
+                     : "+v"(v[0][0]), "+v"(v[0][1]), "+v"(v[1][0]), "+v"(v[1][1]), "+v"(v[2][0]), "+v"(v[2][1]),
+                       "+v"(v[3][0]), "+v"(v[3][1]), "+v"(v[4][0]), "+v"(v[4][1]), "+v"(v[5][0]), "+v"(v[5][1]),
+                       "+v"(v[6][0]), "+v"(v[6][1]), "+v"(v[7][0]), "+v"(v[7][1]));
+    else
+        asm volatile("s_waitcnt lgkmcnt(0)"
+                     : "+v"(v[0][0]), "+v"(v[0][1]), "+v"(v[1][0]), "+v"(v[1][1]), "+v"(v[2][0]), "+v"(v[2][1]),
+                       "+v"(v[3][0]), "+v"(v[3][1]));
+}
+
+template <int HD, int D>
+struct AttCfg {
+    static constexpr int KSN = HD / 32;                       // k-steps of the QK^T contraction
+    static constexpr int NTN = HD / 16;                       // 16-wide tiles of the head dimension
+    static constexpr int GPR = HD / 8;                        // 16-byte granules per K/V row
+    static constexpr int RPI = 64 / GPR;                      // V rows per global->LDS instruction
+    static constexpr int NVI = ATT_CHUNK / RPI;               // such instructions per chunk
+    static constexpr int LOADS = 2 * KSN + NVI + 1;           // vector-memory loads per wave per chunk (K, V, mask word)
+    static constexpr int CHUNK_BYTES = ATT_CHUNK * HD * 2;    // one V chunk in LDS
+    static constexpr int RING_BYTES = ATT_WAVES * D * CHUNK_BYTES;
+    static constexpr int MERGE_BYTES = 2 * ATT_WAVES * 16 * 4 + (ATT_WAVES - 1) * NTN * 64 * 16;
+    static constexpr int SMEM = RING_BYTES > MERGE_BYTES ? RING_BYTES : MERGE_BYTES;
+    static_assert((D - 2) * LOADS < 64, "vmcnt counter range");
 };
 
-// LDS map: [K tile | V^T tile] (reused by the final merge) followed by the query fragments
-// (two bf16 planes, MFMA operand order).
-template <int HD, int MT>
-constexpr int att_tile_region() {
-    const int tile = AttSmem<HD>::TILE_BYTES;
-    (void)MT;
-    return tile;
-}
-template <int HD, int MT>
-constexpr int att_smem_bytes() {
-    return att_tile_region<HD, MT>() + 2 * MT * (HD / 32) * 1024;
-}
+// LDS row of key slot s inside a V chunk: the two 4-slot halves of each lane group's 8 slots
+// are kept 16 rows apart, so that one transposed read (16 rows x 32 bytes per half wave)
+// touches 8 consecutive rows per 32 lanes.
+__device__ __forceinline__ int att_slot_of_row(int rho) { return 8 * ((rho & 15) >> 2) + 4 * (rho >> 4) + (rho & 3); }
+// XOR swizzle of the 32-byte column pairs of an LDS row (in 16-byte granules): 8 consecutive
+// rows land on 8 different bank groups
+template <int HD>
+__device__ __forceinline__ int att_swizzle(int rho) { return HD == 128 ? 2 * (rho & 7) : 2 * ((rho >> 1) & 3); }
 
-template <int HD, int MT>
-__global__ __launch_bounds__(ATT_WAVES * 64) void tree_attn_kernel(
+template <int HD, int D>
+__global__ __launch_bounds__(ATT_WAVES * 64) __attribute__((amdgpu_waves_per_eu(ATT_WAVES / 4, ATT_WAVES / 4))) void tree_attn_kernel(
     TemplateDev t, const uint16_t *__restrict__ q, const uint16_t *__restrict__ q_lo,
-    const uint16_t *__restrict__ k_cache,
-    const uint16_t *__restrict__ v_cache, const uint16_t *__restrict__ k_tree,
-    const uint16_t *__restrict__ v_tree, const uint16_t *__restrict__ k_tree_lo,
-    const uint16_t *__restrict__ v_tree_lo, const uint16_t *__restrict__ prompt_k,
-    const uint16_t *__restrict__ prompt_v, const int32_t *__restrict__ ctx_len, int Hq, int Hkv,
-    int P, int smax, int n_splits, int n_qblk, float scale_log2, float *__restrict__ part_o,
-    float *__restrict__ part_ml) {
+    const uint16_t *__restrict__ k_cache, const uint16_t *__restrict__ v_cache,
+    const uint16_t *__restrict__ k_tree, const uint16_t *__restrict__ v_tree,
+    const uint16_t *__restrict__ k_tree_lo, const uint16_t *__restrict__ v_tree_lo,
+    const uint16_t *__restrict__ prompt_k, const uint16_t *__restrict__ prompt_v,
+    const int32_t *__restrict__ ctx_len, int batch, int Hq, int Hkv, int P, int smax, int n_splits, int n_mt,
+    float scale_log2, float *__restrict__ part_o, float *__restrict__ part_ml, uint16_t *__restrict__ out,
+    int as_fragments, int m_tiles_out) {
+    using C = AttCfg<HD, D>;
+    constexpr int KSN = C::KSN, NTN = C::NTN, GPR = C::GPR, RPI = C::RPI, NVI = C::NVI;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    constexpr int GPK = HD / 8;                    // 16-byte granules per key row
-    constexpr int KSN = HD / 32;                   // k-steps of the QK^T contraction
-    constexpr int NTN = HD / 16;                   // 16-wide tiles of the head dimension
-    constexpr int K_IT = ATT_TK * GPK / 256;       // K granules per thread per tile
-    constexpr int V_IT = ATT_TK / 2 * GPK / 256;   // V key-pair granules per thread per tile
-    constexpr int KSTR = AttSmem<HD>::K_STRIDE * 2, VSTR = AttSmem<HD>::V_STRIDE * 2;   // bytes
-    unsigned char *ks_lds = smem, *vt_lds = smem + AttSmem<HD>::K_BYTES;
-    uint4 *q_lds = reinterpret_cast<uint4 *>(smem + att_tile_region<HD, MT>());   // [2][MT][KSN][64]
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 4, c = lane & 15;
-    const int split = blockIdx.x, h = blockIdx.y / n_qblk, qblk = blockIdx.y % n_qblk, b = blockIdx.z;
-    const int kvh = h / (Hq / Hkv);
+    const int tid = threadIdx.x, lane = tid & 63, g = lane >> 4, c = lane & 15;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, and known to be
+    // ---- workgroup id -> (kv group, query head of the group, m-tile, split), kv groups dealt
+    //      round-robin to the XCDs
+    const int qpk = Hq / Hkv;                                // query heads per K/V head
+    const int per_group = qpk * n_mt * n_splits;
+    const int xcd = blockIdx.x & 7, slot_in_xcd = blockIdx.x >> 3;
+    const int group = xcd + 8 * (slot_in_xcd / per_group);  // (sequence, kv head)
+    if (group >= batch * Hkv) return;
+    int w_in = slot_in_xcd % per_group;
+    const int split = w_in % n_splits; w_in /= n_splits;
+    const int mt = n_mt - 1 - (w_in % n_mt);                 // long m-tiles first
+    const int qh = w_in / n_mt;
+    const int b = group / Hkv, kvh = group % Hkv, h = kvh * qpk + qh;
+
     const int R = t.rows, Lc = ctx_len[b];
-    // key axis: tiles over [prefix | cache] (128 keys each), then tiles over the pass rows
-    // (64 keys + 64 low-plane partner slots each)
+    const int row0 = mt * 16;
     const int n_ctx_keys = P + Lc;
-    const int n_ct = (n_ctx_keys + ATT_TK - 1) / ATT_TK;
-    const int n_tiles = n_ct + (R + ATT_TK / 2 - 1) / (ATT_TK / 2);
-    const int per_split = (n_tiles + n_splits - 1) / n_splits;
-    const int tile_begin = split * per_split;
-    const int tile_end = min(n_tiles, tile_begin + per_split);
-    const int row0 = qblk * MT * 16;
+    const int n_cc = (n_ctx_keys + ATT_CHUNK - 1) / ATT_CHUNK;           // chunks over [prefix | cache]
+    const int n_tc = min((R + 15) >> 4, mt + 1);                         // chunks over the pass rows
+    const int n_chunks = n_cc + n_tc;
+    const int per_split = (n_chunks + n_splits - 1) / n_splits;
+    const int chunk_begin = split * per_split;
+    const int chunk_end = min(n_chunks, chunk_begin + per_split);
+    // this wave's chunks: chunk_begin + wave + ATT_WAVES * i, i < n_my
+    const int n_my = max(0, (chunk_end - chunk_begin - wave + ATT_WAVES - 1) / ATT_WAVES);
 
     const uint16_t *pk = prompt_k + (int64_t)kvh * P * HD, *pv = prompt_v + (int64_t)kvh * P * HD;
     const uint16_t *ck = k_cache + ((int64_t)b * Hkv + kvh) * smax * HD;
@@ -97,293 +169,310 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void tree_attn_kernel(
     const uint16_t *tk = k_tree + tree_off, *tv = v_tree + tree_off;
     const uint16_t *tk_lo = k_tree_lo ? k_tree_lo + tree_off : nullptr;
     const uint16_t *tv_lo = v_tree_lo ? v_tree_lo + tree_off : nullptr;
+    const uint16_t *zero = reinterpret_cast<const uint16_t *>(g_att_zero_row);
 
-    // Query fragments (B operand of S^T = K Q^T) go to LDS once, as two bf16 planes (value and
-    // rounding residual): fragment (plane, mt, ks) holds, for lane (g, c),
-    // Q[row0 + 16mt + c][32ks + 8g .. +8].  Rows beyond R are zero.
-    bool row_ok[MT], row_mask[MT];
+    // ---- query fragments (B operand of S^T = K Q^T) stay in registers: lane (g, c) holds
+    //      Q[row0 + c][32ks + 8g .. +8] of both planes; rows beyond R are zero
+    const int rq = row0 + c;
+    const bool row_ok = rq < R;
+    const bool row_mask = row_ok && t.is_mask[rq];
+    bf16x8 qf[2][KSN];
 #pragma unroll
-    for (int mt = 0; mt < MT; mt++) {
-        const int r = row0 + mt * 16 + c;
-        row_ok[mt] = r < R;
-        row_mask[mt] = row_ok[mt] && t.is_mask[r];
-    }
-    for (int f = wave; f < 2 * MT * KSN; f += ATT_WAVES) {
-        const int plane = f / (MT * KSN), mt = (f / KSN) % MT, ks = f % KSN;
-        const int r = row0 + mt * 16 + c;
-        const uint16_t *src = plane ? q_lo : q;
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (r < R && src)
-            v = *reinterpret_cast<const uint4 *>(src + (((int64_t)b * R + r) * Hq + h) * HD + ks * 32 + g * 8);
-        q_lds[f * 64 + lane] = v;
-    }
-
-    f32x4 o_acc[NTN][MT];
-    float m_run[MT], l_run[MT];
+    for (int pl = 0; pl < 2; pl++) {
+        const uint16_t *src = pl ? q_lo : q;
 #pragma unroll
-    for (int mt = 0; mt < MT; mt++) {
-        m_run[mt] = -INFINITY;
-        l_run[mt] = 0.f;
-#pragma unroll
-        for (int nt = 0; nt < NTN; nt++) o_acc[nt][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
-    }
-
-    uint4 k_stage[K_IT], v_stage[V_IT][2];
-    // source row of slot `slot` of tile `tile` (nullptr: padding, staged as zeros)
-    auto src_row = [&](int tile, int slot, const uint16_t *pp, const uint16_t *cp, const uint16_t *tp,
-                       const uint16_t *tp_lo) -> const uint16_t * {
-        if (tile < n_ct) {
-            const int kidx = tile * ATT_TK + slot;
-            if (kidx < P) return pp + (int64_t)kidx * HD;
-            if (kidx < n_ctx_keys) return cp + (int64_t)(kidx - P) * HD;
-            return nullptr;
+        for (int ks = 0; ks < KSN; ks++) {
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (row_ok && src)
+                v = *reinterpret_cast<const uint4 *>(src + (((int64_t)b * R + rq) * Hq + h) * HD + ks * 32 + g * 8);
+            qf[pl][ks] = __builtin_bit_cast(bf16x8, v);
         }
-        const int j = (tile - n_ct) * (ATT_TK / 2) + (slot >> 3) * 4 + (slot & 3);   // pass row
-        if (j >= R) return nullptr;
-        if (slot & 4) return tp_lo ? tp_lo + (int64_t)j * HD : nullptr;            // partner slot
-        return tp + (int64_t)j * HD;
+    }
+
+    f32x4 o_acc[NTN];
+#pragma unroll
+    for (int nt = 0; nt < NTN; nt++) o_acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float m_run = -INFINITY, l_run = 0.f;
+
+    // Source row of key slot `slot` of chunk `chunk` (branch-free; padding reads the zero row)
+    auto src_row = [&](int chunk, int slot, const uint16_t *pp, const uint16_t *cp, const uint16_t *tp,
+                       const uint16_t *tp_lo, bool valid_stage) __attribute__((always_inline)) -> const uint16_t * {
+        const int kidx = chunk * ATT_CHUNK + slot;
+        const uint16_t *ctx_ptr = kidx < P ? pp + (int64_t)kidx * HD
+                                           : (kidx < n_ctx_keys ? cp + (int64_t)(kidx - P) * HD : zero);
+        const int j = (chunk - n_cc) * 16 + (slot >> 3) * 4 + (slot & 3);       // pass row
+        const bool lo = (slot & 4) != 0;                                         // partner slot
+        const uint16_t *plane = lo ? tp_lo : tp;
+        const uint16_t *tree_ptr = (j < R && plane) ? plane + (int64_t)j * HD : zero;
+        const uint16_t *p = chunk < n_cc ? ctx_ptr : tree_ptr;
+        return valid_stage ? p : zero;
     };
-    auto prefetch = [&](int tile) {
+
+    u32x4 kf[D][2][KSN];
+    uint64_t anc_word[D];                                              // ancestor bits of row rq for a pass-row chunk
+    unsigned char *v_ring = smem + wave * D * C::CHUNK_BYTES;          // this wave's private ring
+    // LDS addresses of this lane's transposed V reads inside ring slot 0: lane (g, c) addresses
+    // V[slot 8g + 4half + c/4][16nt + 4(c%4) .. +4] and receives V[slots 8g + 4half .. +4][16nt + c]
+    uint32_t v_addr[NTN][2];
 #pragma unroll
-        for (int it = 0; it < K_IT; it++) {
-            const int id = it * 256 + tid, key = id / GPK, part = id % GPK;
-            const uint16_t *p = src_row(tile, key, pk, ck, tk, tk_lo);
-            k_stage[it] = p ? *reinterpret_cast<const uint4 *>(p + part * 8) : make_uint4(0, 0, 0, 0);
+    for (int nt = 0; nt < NTN; nt++)
+#pragma unroll
+        for (int half = 0; half < 2; half++) {
+            const int rho = 16 * half + 4 * g + (c >> 2);
+            const int gran = (2 * nt + ((c & 3) >> 1)) ^ att_swizzle<HD>(rho);
+            v_addr[nt][half] = (uint32_t)(size_t)((__attribute__((address_space(3))) unsigned char *)v_ring) +
+                               rho * (HD * 2) + gran * 16 + (c & 1) * 8;
         }
+
+    // Per-lane byte offsets of the fast path (a chunk that lies wholly inside the cache): K rows
+    // of S^T sub-tile tt are slots 8*(c/4) + 4*tt + c%4, so that a lane of the accumulator holds
+    // 8 consecutive slots (8g .. 8g+7) for its query; the V row a lane copies in global->LDS
+    // instruction iv is slot v_slot_base(iv) + v_slot_lane, granule (lane%GPR) ^ swizzle(row).
+    uint32_t k_off[2], v_off[2];
 #pragma unroll
-        for (int it = 0; it < V_IT; it++) {
-            const int id = it * 256 + tid, kp = id / GPK, part = id % GPK;
+    for (int tt = 0; tt < 2; tt++) k_off[tt] = (8 * (c >> 2) + 4 * tt + (c & 3)) * (HD * 2) + g * 16;
+    const int v_lane_row = lane / GPR;                                  // row inside one instruction
 #pragma unroll
-            for (int e = 0; e < 2; e++) {
-                const uint16_t *p = src_row(tile, 2 * kp + e, pv, cv, tv, tv_lo);
-                v_stage[it][e] = p ? *reinterpret_cast<const uint4 *>(p + part * 8) : make_uint4(0, 0, 0, 0);
+    for (int par = 0; par < 2; par++) {
+        const int rho = par * RPI + v_lane_row;                          // swizzle depends on iv only through iv&1
+        v_off[par] = (att_slot_of_row(v_lane_row)) * (HD * 2) + (((lane % GPR) ^ att_swizzle<HD>(rho)) * 16);
+    }
+
+    // Issue all loads of this wave's stage i into ring slot SLOT: always exactly C::LOADS
+    // vector-memory operations, in one straight-line run (stages past the end read the zero
+    // row).  Only the address computation branches: a chunk wholly inside the cache takes
+    // one uniform base per operand plus the constant lane offsets.
+    auto issue = [&](auto slot_c, int i) __attribute__((always_inline)) {
+        constexpr int SLOT = decltype(slot_c)::value;
+        const int chunk = chunk_begin + wave + ATT_WAVES * i;
+        const bool valid = i < n_my;
+        const int base = chunk * ATT_CHUNK;
+        const unsigned char *zero_b = reinterpret_cast<const unsigned char *>(zero);
+        typedef const __attribute__((address_space(1))) unsigned char *gptr;   // keeps the loads global, not flat
+        gptr k_src[2], v_src[NVI], a_src = (gptr)(zero_b + (lane & 1) * 8);
+        if (valid && base >= P && base + ATT_CHUNK <= n_ctx_keys) {
+            const unsigned char *ubk = reinterpret_cast<const unsigned char *>(ck + (int64_t)(base - P) * HD);
+            const unsigned char *ubv = reinterpret_cast<const unsigned char *>(cv + (int64_t)(base - P) * HD);
+#pragma unroll
+            for (int tt = 0; tt < 2; tt++) k_src[tt] = (gptr)(ubk + k_off[tt]);
+#pragma unroll
+            for (int iv = 0; iv < NVI; iv++) v_src[iv] = (gptr)(ubv + att_slot_of_row(iv * RPI) * (HD * 2) + v_off[iv & 1]);
+        } else {
+#pragma unroll
+            for (int tt = 0; tt < 2; tt++) {
+                const int slot = 8 * (c >> 2) + 4 * tt + (c & 3);
+                const uint16_t *row = src_row(chunk, slot, pk, ck, tk, tk_lo, valid);
+                k_src[tt] = (gptr)(row + g * 8);
+            }
+            // the 64-bit word of this row's ancestor bitset that covers the chunk's 16 pass rows
+            if (valid && row_ok && chunk >= n_cc)
+                a_src = (gptr)(t.anc + (int64_t)rq * t.words + (((chunk - n_cc) * 16) >> 6));
+#pragma unroll
+            for (int iv = 0; iv < NVI; iv++) {
+                const int rho = iv * RPI + v_lane_row;                   // LDS row written by this lane
+                const uint16_t *row = src_row(chunk, att_slot_of_row(rho), pv, cv, tv, tv_lo, valid);
+                const int gran = (lane % GPR) ^ att_swizzle<HD>(rho);    // source granule for this position
+                v_src[iv] = (gptr)(row + gran * 8);
             }
         }
-    };
-    auto stage_to_lds = [&]() {
 #pragma unroll
-        for (int it = 0; it < K_IT; it++) {
-            const int id = it * 256 + tid, key = id / GPK, part = id % GPK;
-            *reinterpret_cast<uint4 *>(ks_lds + key * KSTR + part * 16) = k_stage[it];
-        }
-#pragma unroll
-        for (int it = 0; it < V_IT; it++) {
-            const int id = it * 256 + tid, kp = id / GPK, part = id % GPK;
-            const uint32_t a[4] = {v_stage[it][0].x, v_stage[it][0].y, v_stage[it][0].z, v_stage[it][0].w};
-            const uint32_t d[4] = {v_stage[it][1].x, v_stage[it][1].y, v_stage[it][1].z, v_stage[it][1].w};
-#pragma unroll
-            for (int j = 0; j < 4; j++) {
-                // hd element 2j of both keys, then element 2j+1
-                const uint32_t even = (a[j] & 0xFFFFu) | (d[j] << 16);
-                const uint32_t odd = (a[j] >> 16) | (d[j] & 0xFFFF0000u);
-                *reinterpret_cast<uint32_t *>(vt_lds + (part * 8 + 2 * j) * VSTR + kp * 4) = even;
-                *reinterpret_cast<uint32_t *>(vt_lds + (part * 8 + 2 * j + 1) * VSTR + kp * 4) = odd;
-            }
-        }
-    };
-
-    if (tile_begin < tile_end) prefetch(tile_begin);
-    const int kb = wave * 32;                                // this wave's keys inside a tile
-    for (int tile = tile_begin; tile < tile_end; tile++) {
-        __syncthreads();                                     // previous tile fully consumed
-        stage_to_lds();
-        __syncthreads();
-        if (tile + 1 < tile_end) prefetch(tile + 1);
-        const int base = tile * ATT_TK;
-        const bool tree_tile = tile >= n_ct;
-        const int tree_j0 = (tile - n_ct) * (ATT_TK / 2);   // first pass row of a pass-row tile
-        if (tree_tile ? (tree_j0 + (kb >> 1) >= R) : (base + kb >= n_ctx_keys)) continue;   // only padding
-
-        // S^T[key][q]: rows of sub-tile tt are keys 8*(i/4) + 4*tt + i%4, so that a lane ends
-        // up with 8 consecutive keys (8g .. 8g+7) for its query row.
-        f32x4 s_acc[MT][2];
-#pragma unroll
-        for (int mt = 0; mt < MT; mt++) s_acc[mt][0] = s_acc[mt][1] = f32x4{0.f, 0.f, 0.f, 0.f};
-        bf16x8 kf[2][KSN];
-#pragma unroll
-        for (int tt = 0; tt < 2; tt++) {
-            const int key = kb + 8 * (c >> 2) + 4 * tt + (c & 3);
+        for (int tt = 0; tt < 2; tt++)
 #pragma unroll
             for (int ks = 0; ks < KSN; ks++)
-                kf[tt][ks] = __builtin_bit_cast(
-                    bf16x8, *reinterpret_cast<const uint4 *>(ks_lds + key * KSTR + (ks * 32 + g * 8) * 2));
-        }
+                kf[SLOT][tt][ks] = *(const __attribute__((address_space(1))) u32x4 *)(k_src[tt] + ks * 64);
+        anc_word[SLOT] = *(const __attribute__((address_space(1))) uint64_t *)a_src;
+        unsigned char *dst0 = v_ring + SLOT * C::CHUNK_BYTES;           // wave-uniform; lane l lands at +16l
+#pragma unroll
+        for (int iv = 0; iv < NVI; iv++)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)v_src[iv],
+                                             (__attribute__((address_space(3))) void *)(dst0 + iv * 1024), 16, 0, 0);
+    };
+
+    auto compute = [&](auto slot_c, int i) __attribute__((always_inline)) {
+        constexpr int SLOT = decltype(slot_c)::value;
+        const int chunk = chunk_begin + wave + ATT_WAVES * i;
+        const bool tree_chunk = chunk >= n_cc;
+        const int base = chunk * ATT_CHUNK;
+        f32x4 s_acc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
         for (int ks = 0; ks < KSN; ks++)
 #pragma unroll
-            for (int mt = 0; mt < MT; mt++) {
-                const bf16x8 qh = __builtin_bit_cast(bf16x8, q_lds[((0 * MT + mt) * KSN + ks) * 64 + lane]);
-                const bf16x8 ql = __builtin_bit_cast(bf16x8, q_lds[((1 * MT + mt) * KSN + ks) * 64 + lane]);
-#pragma unroll
-                for (int tt = 0; tt < 2; tt++) {
-                    s_acc[mt][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[tt][ks], qh, s_acc[mt][tt], 0, 0, 0);
-                    s_acc[mt][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[tt][ks], ql, s_acc[mt][tt], 0, 0, 0);
-                }
+            for (int tt = 0; tt < 2; tt++) {
+                const bf16x8 ka = __builtin_bit_cast(bf16x8, kf[SLOT][tt][ks]);
+                s_acc[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qf[0][ks], s_acc[tt], 0, 0, 0);
+                s_acc[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qf[1][ks], s_acc[tt], 0, 0, 0);
             }
-
-        const bool need_mask = tree_tile || (base < P) || (base + ATT_TK > n_ctx_keys);
-        bf16x8 pf[MT], pf_lo[MT];
+        float sv[8];
 #pragma unroll
-        for (int mt = 0; mt < MT; mt++) {
-            float sv[8];
+        for (int tt = 0; tt < 2; tt++)
 #pragma unroll
-            for (int tt = 0; tt < 2; tt++)
+            for (int r = 0; r < 4; r++) sv[tt * 4 + r] = s_acc[tt][r] * scale_log2;
+        if (tree_chunk) {                    // score = q.k_hi + q.k_lo; partner slots leave the softmax
 #pragma unroll
-                for (int r = 0; r < 4; r++) sv[tt * 4 + r] = s_acc[mt][tt][r] * scale_log2;
-            if (tree_tile) {                 // score = q.k_hi + q.k_lo; partner slots leave the softmax
+            for (int e = 0; e < 4; e++) sv[e] += sv[e + 4];
+        }
+        const bool need_mask = tree_chunk || (base < P) || (base + ATT_CHUNK > n_ctx_keys);
+        if (need_mask) {
+            // 8-bit visibility word for this lane's slots, built with integer selects only:
+            // prefix -> mask rows, cache -> all rows, pass rows -> ancestor bits.
+            uint32_t bits = 0;
+            if (row_ok) {
+                if (tree_chunk) {
+                    const int j0 = (chunk - n_cc) * 16 + 4 * g;          // this lane's 4 pass rows (4-aligned)
+                    const uint32_t four = (uint32_t)(anc_word[SLOT] >> (j0 & 63)) & 0xFu;
 #pragma unroll
-                for (int e = 0; e < 4; e++) sv[e] += sv[e + 4];
-            }
-            if (need_mask) {
-                // 8-bit visibility word for this lane's slots, built with integer selects only:
-                // prefix -> mask rows, cache -> all rows, pass rows -> ancestor bits.
-                const int rq = row0 + mt * 16 + c;
-                uint32_t bits = 0;
-                if (row_ok[mt]) {
-                    if (tree_tile) {
-                        const int j0 = tree_j0 + ((kb >> 3) + g) * 4;     // this lane's 4 pass rows (4-aligned)
-                        uint32_t four = 0;
-                        if (j0 < R) four = (uint32_t)(t.anc[(int64_t)rq * t.words + (j0 >> 6)] >> (j0 & 63)) & 0xFu;
+                    for (int e = 0; e < 4; e++) bits |= ((j0 + e < R) ? ((four >> e) & 1u) : 0u) << e;
+                } else {
+                    const int k0 = base + 8 * g;
 #pragma unroll
-                        for (int e = 0; e < 4; e++)
-                            bits |= ((j0 + e < R) ? ((four >> e) & 1u) : 0u) << e;
-                    } else {
-                        const int k0 = base + kb + 8 * g;
-#pragma unroll
-                        for (int e = 0; e < 8; e++) {
-                            const int kidx = k0 + e;
-                            const uint32_t in_prefix = kidx < P ? 1u : 0u;
-                            const uint32_t in_cache = (kidx >= P && kidx < n_ctx_keys) ? 1u : 0u;
-                            bits |= ((in_prefix & (row_mask[mt] ? 1u : 0u)) | in_cache) << e;
-                        }
+                    for (int e = 0; e < 8; e++) {
+                        const int kidx = k0 + e;
+                        const uint32_t in_prefix = kidx < P ? 1u : 0u;
+                        const uint32_t in_cache = (kidx >= P && kidx < n_ctx_keys) ? 1u : 0u;
+                        bits |= ((in_prefix & (row_mask ? 1u : 0u)) | in_cache) << e;
                     }
                 }
-#pragma unroll
-                for (int e = 0; e < 8; e++) sv[e] = ((bits >> e) & 1u) ? sv[e] : -INFINITY;
             }
-            float mx = sv[0];
 #pragma unroll
-            for (int e = 1; e < 8; e++) mx = fmaxf(mx, sv[e]);
-            mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-            const float m_new = fmaxf(m_run[mt], mx);
-            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-            const float alpha = fast_exp2(m_run[mt] - m_use);
-            m_run[mt] = m_new;
-            // probabilities as two bf16 planes (value and rounding residual), like every other
-            // MFMA input of the pass
-            float ps = 0.f;
-            uint32_t pk2[4], pl2[4];
-#pragma unroll
-            for (int e = 0; e < 8; e += 2) {
-                const float p0 = fast_exp2(sv[e] - m_use), p1 = fast_exp2(sv[e + 1] - m_use);
-                ps += p0 + p1;
-                const uint32_t hi = cvt_pk_bf16(p0, p1);
-                pk2[e >> 1] = hi;
-                pl2[e >> 1] = cvt_pk_bf16(p0 - __uint_as_float(hi << 16), p1 - __uint_as_float(hi & 0xFFFF0000u));
-            }
-            if (tree_tile) {                 // the low-plane value rows take the same probabilities
-                pk2[2] = pk2[0];
-                pk2[3] = pk2[1];
-                pl2[2] = pl2[0];
-                pl2[3] = pl2[1];
-            }
-            l_run[mt] = l_run[mt] * alpha + ps;
-            pf[mt] = __builtin_bit_cast(bf16x8, make_uint4(pk2[0], pk2[1], pk2[2], pk2[3]));
-            pf_lo[mt] = __builtin_bit_cast(bf16x8, make_uint4(pl2[0], pl2[1], pl2[2], pl2[3]));
-#pragma unroll
-            for (int nt = 0; nt < NTN; nt++) o_acc[nt][mt] *= alpha;
+            for (int e = 0; e < 8; e++) sv[e] = ((bits >> e) & 1u) ? sv[e] : -INFINITY;
         }
-        // O^T[hd][q] += V^T[hd][keys 8g..8g+7] * P^T
+        float mx = sv[0];
+#pragma unroll
+        for (int e = 1; e < 8; e++) mx = fmaxf(mx, sv[e]);
+        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float m_new = fmaxf(m_run, mx);
+        const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+        const float alpha = fast_exp2(m_run - m_use);
+        m_run = m_new;
+        // probabilities as two bf16 planes (value and rounding residual), like every other
+        // MFMA input of the pass
+        float ps = 0.f;
+        uint32_t pk2[4], pl2[4];
+#pragma unroll
+        for (int e = 0; e < 8; e += 2) {
+            const float p0 = fast_exp2(sv[e] - m_use), p1 = fast_exp2(sv[e + 1] - m_use);
+            ps += p0 + p1;
+            const uint32_t hi = cvt_pk_bf16(p0, p1);
+            pk2[e >> 1] = hi;
+            pl2[e >> 1] = cvt_pk_bf16(p0 - __uint_as_float(hi << 16), p1 - __uint_as_float(hi & 0xFFFF0000u));
+        }
+        if (tree_chunk) {                    // the low-plane value rows take the same probabilities
+            pk2[2] = pk2[0];
+            pk2[3] = pk2[1];
+            pl2[2] = pl2[0];
+            pl2[3] = pl2[1];
+        }
+        l_run = l_run * alpha + ps;
+        const bf16x8 pf = __builtin_bit_cast(bf16x8, make_uint4(pk2[0], pk2[1], pk2[2], pk2[3]));
+        const bf16x8 pf_lo = __builtin_bit_cast(bf16x8, make_uint4(pl2[0], pl2[1], pl2[2], pl2[3]));
+        // O^T[hd][q] = alpha * O^T + V^T[hd][slots 8g..8g+7] * P^T
+        s16x4 vh[NTN][2];
 #pragma unroll
         for (int nt = 0; nt < NTN; nt++) {
-            const bf16x8 vf = __builtin_bit_cast(
-                bf16x8, *reinterpret_cast<const uint4 *>(vt_lds + (nt * 16 + c) * VSTR + (kb + 8 * g) * 2));
-#pragma unroll
-            for (int mt = 0; mt < MT; mt++) {
-                o_acc[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[mt], o_acc[nt][mt], 0, 0, 0);
-                o_acc[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf_lo[mt], o_acc[nt][mt], 0, 0, 0);
-            }
+            vh[nt][0] = lds_read_tr16<SLOT * C::CHUNK_BYTES>(v_addr[nt][0]);
+            vh[nt][1] = lds_read_tr16<SLOT * C::CHUNK_BYTES>(v_addr[nt][1]);
         }
-    }
+        lds_wait_all(vh);
+#pragma unroll
+        for (int nt = 0; nt < NTN; nt++) {
+            const s16x8 v8 = {vh[nt][0][0], vh[nt][0][1], vh[nt][0][2], vh[nt][0][3],
+                              vh[nt][1][0], vh[nt][1][1], vh[nt][1][2], vh[nt][1][3]};
+            const bf16x8 vf = __builtin_bit_cast(bf16x8, v8);
+            o_acc[nt] *= alpha;
+            o_acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf, o_acc[nt], 0, 0, 0);
+            o_acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf_lo, o_acc[nt], 0, 0, 0);
+        }
+    };
 
-    // ---- merge the 4 wavefronts (each saw a disjoint key subset) --------------------------
-    // Row statistics go through two small LDS arrays; the O accumulators are added pairwise
-    // (3 <- nothing, 2+3 -> regions, 0 += 2, 1 += 3, then 0 += 1) through LDS in register order,
-    // so every LDS access is a linear 1 KiB sweep, and wave 0 stores the result from registers.
-    __syncthreads();
-    float *sm = reinterpret_cast<float *>(smem), *sl = sm + ATT_WAVES * MT * 16;
-    float4 *region = reinterpret_cast<float4 *>(smem + 2 * ATT_WAVES * MT * 16 * 4);   // 2 x [NTN*MT][64]
-    constexpr int REGION_F4 = NTN * MT * 64;
-    static_assert(2 * ATT_WAVES * MT * 16 * 4 + 2 * REGION_F4 * 16 <= att_smem_bytes<HD, MT>(), "merge scratch fits");
-#pragma unroll
-    for (int mt = 0; mt < MT; mt++) {
-        float l = l_run[mt];
-        l += __shfl_xor(l, 16, 64);
-        l += __shfl_xor(l, 32, 64);
-        l_run[mt] = l;
-        if (g == 0) {
-            sm[wave * MT * 16 + mt * 16 + c] = m_run[mt];
-            sl[wave * MT * 16 + mt * 16 + c] = l;
+    // ---- per-wave ring: D-1 chunks in flight behind the one being multiplied.  Every step
+    //      issues exactly C::LOADS loads, so the wait count is a compile-time constant; the
+    //      wait also retires this wave's LDS reads of the slot about to be refilled.
+    auto step = [&](auto u_c, int i) __attribute__((always_inline)) {
+        constexpr int U = decltype(u_c)::value;
+        constexpr int PRE = (U + D - 1) % D;
+        att_wait<(D - 2) * C::LOADS>();
+        issue(std::integral_constant<int, PRE>{}, i + D - 1);
+        compute(u_c, i);
+    };
+    att_static_for<0, D - 1>([&](auto u_c) __attribute__((always_inline)) { issue(u_c, decltype(u_c)::value); });
+    int i = 0;
+    for (; i + D <= n_my; i += D)
+        att_static_for<0, D>([&](auto u_c) __attribute__((always_inline)) { step(u_c, i + decltype(u_c)::value); });
+    att_static_for<0, D - 1>([&](auto u_c) __attribute__((always_inline)) {          // remaining n_my % D chunks: nothing more to fetch
+        constexpr int U = decltype(u_c)::value;
+        if (i + U < n_my) {
+            att_wait<(D - 2 - U) * C::LOADS>();
+            compute(u_c, i + U);
         }
+    });
+    att_wait<0>();                                      // also the loads of stages past the end
+
+    // ---- merge the 4 wavefronts (disjoint key subsets); wave 0 sums in wave order ----------
+    __syncthreads();
+    float *sm = reinterpret_cast<float *>(smem), *sl = sm + ATT_WAVES * 16;
+    float4 *region = reinterpret_cast<float4 *>(smem + 2 * ATT_WAVES * 16 * 4);   // [WAVES-1][NTN][64]
+    float l = l_run;
+    l += __shfl_xor(l, 16, 64);
+    l += __shfl_xor(l, 32, 64);
+    if (g == 0) {
+        sm[wave * 16 + c] = m_run;
+        sl[wave * 16 + c] = l;
     }
     __syncthreads();
-    float m_tot[MT], l_tot[MT];
+    float m_tot = -INFINITY;
 #pragma unroll
-    for (int mt = 0; mt < MT; mt++) {
-        float m = -INFINITY;
+    for (int w = 0; w < ATT_WAVES; w++) m_tot = fmaxf(m_tot, sm[w * 16 + c]);
+    const float m_use = (m_tot == -INFINITY) ? 0.f : m_tot;
+    float l_tot = 0.f;
 #pragma unroll
-        for (int w = 0; w < ATT_WAVES; w++) m = fmaxf(m, sm[w * MT * 16 + mt * 16 + c]);
-        const float m_use = (m == -INFINITY) ? 0.f : m;
-        float l = 0.f;
+    for (int w = 0; w < ATT_WAVES; w++) l_tot += sl[w * 16 + c] * fast_exp2(sm[w * 16 + c] - m_use);
+    const float f = fast_exp2(m_run - m_use);
 #pragma unroll
-        for (int w = 0; w < ATT_WAVES; w++)
-            l += sl[w * MT * 16 + mt * 16 + c] * fast_exp2(sm[w * MT * 16 + mt * 16 + c] - m_use);
-        const float f = fast_exp2(m_run[mt] - m_use);
-        m_tot[mt] = m;
-        l_tot[mt] = l;
+    for (int nt = 0; nt < NTN; nt++) o_acc[nt] *= f;
+    if (wave > 0) {
 #pragma unroll
-        for (int nt = 0; nt < NTN; nt++) o_acc[nt][mt] *= f;
+        for (int nt = 0; nt < NTN; nt++)
+            region[((wave - 1) * NTN + nt) * 64 + lane] = make_float4(o_acc[nt][0], o_acc[nt][1], o_acc[nt][2], o_acc[nt][3]);
     }
-    auto park = [&](int which) {
+    __syncthreads();
+    if (wave != 0 || !row_ok) return;
+#pragma unroll
+    for (int w = 1; w < ATT_WAVES; w++)
+#pragma unroll
+        for (int nt = 0; nt < NTN; nt++) {
+            const float4 v = region[((w - 1) * NTN + nt) * 64 + lane];
+            o_acc[nt][0] += v.x; o_acc[nt][1] += v.y; o_acc[nt][2] += v.z; o_acc[nt][3] += v.w;
+        }
+    // ---- lane (g, c) holds O[row rq][hd 16nt + 4g .. +4] ---------------------------------------
+    if (n_splits > 1) {                      // unnormalised partial for attn_merge_kernel
+        const int64_t prow = (((int64_t)b * Hq + h) * n_splits + split) * R + rq;
 #pragma unroll
         for (int nt = 0; nt < NTN; nt++)
+            *reinterpret_cast<float4 *>(part_o + prow * HD + nt * 16 + 4 * g) =
+                make_float4(o_acc[nt][0], o_acc[nt][1], o_acc[nt][2], o_acc[nt][3]);
+        if (g == 0) {
+            part_ml[prow * 2] = m_tot;
+            part_ml[prow * 2 + 1] = l_tot;
+        }
+        return;
+    }
+    const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+    const int mrow = b * R + rq, n_ksteps = (Hq * HD) >> 5;
 #pragma unroll
-            for (int mt = 0; mt < MT; mt++)
-                region[which * REGION_F4 + (nt * MT + mt) * 64 + lane] =
-                    make_float4(o_acc[nt][mt][0], o_acc[nt][mt][1], o_acc[nt][mt][2], o_acc[nt][mt][3]);
-    };
-    auto absorb = [&](int which) {
+    for (int nt = 0; nt < NTN; nt++) {
+        uint16_t hi[4], lo[4];
 #pragma unroll
-        for (int nt = 0; nt < NTN; nt++)
-#pragma unroll
-            for (int mt = 0; mt < MT; mt++) {
-                const float4 v = region[which * REGION_F4 + (nt * MT + mt) * 64 + lane];
-                o_acc[nt][mt][0] += v.x; o_acc[nt][mt][1] += v.y; o_acc[nt][mt][2] += v.z; o_acc[nt][mt][3] += v.w;
-            }
-    };
-    if (wave >= 2) park(wave - 2);
-    __syncthreads();
-    if (wave < 2) absorb(wave);
-    __syncthreads();
-    if (wave == 1) park(0);
-    __syncthreads();
-    if (wave != 0) return;
-    absorb(0);
-    // ---- write the split's partial result: lane (g, c) holds O[row c][hd 16nt + 4g .. +4] ------
-    const int64_t pbase = (((int64_t)b * Hq + h) * n_splits + split) * R;
-#pragma unroll
-    for (int mt = 0; mt < MT; mt++) {
-        const int r = row0 + mt * 16 + c;
-        if (r < R) {
-#pragma unroll
-            for (int nt = 0; nt < NTN; nt++)
-                *reinterpret_cast<float4 *>(part_o + (pbase + r) * HD + nt * 16 + 4 * g) =
-                    make_float4(o_acc[nt][mt][0], o_acc[nt][mt][1], o_acc[nt][mt][2], o_acc[nt][mt][3]);
-            if (g == 0) {
-                part_ml[(pbase + r) * 2] = m_tot[mt];
-                part_ml[(pbase + r) * 2 + 1] = l_tot[mt];
-            }
+        for (int e = 0; e < 4; e++) split_bf16(o_acc[nt][e] * inv, hi[e], lo[e]);
+        uint2 ph, pl;
+        ph.x = hi[0] | ((uint32_t)hi[1] << 16); ph.y = hi[2] | ((uint32_t)hi[3] << 16);
+        pl.x = lo[0] | ((uint32_t)lo[1] << 16); pl.y = lo[2] | ((uint32_t)lo[3] << 16);
+        const int k = h * HD + nt * 16 + 4 * g;
+        if (as_fragments) {                  // two planes, the O-projection's activation slab
+            *reinterpret_cast<uint2 *>(out + frag_index(0, mrow, k, n_ksteps, m_tiles_out)) = ph;
+            *reinterpret_cast<uint2 *>(out + frag_index(1, mrow, k, n_ksteps, m_tiles_out)) = pl;
+        } else {
+            *reinterpret_cast<uint2 *>(out + (int64_t)mrow * Hq * HD + k) = ph;
         }
     }
 }
@@ -429,45 +518,52 @@ __global__ void attn_merge_kernel(const float *__restrict__ part_o, const float 
 
 AttnPlan attn_plan(int batch, int rows, int n_heads, int hd, int ctx_hint, int n_prompt) {
     AttnPlan p;
-    const int n_tiles = (n_prompt + ctx_hint + ATT_TK - 1) / ATT_TK + (rows + ATT_TK / 2 - 1) / (ATT_TK / 2);
-    const int n_qblk = (rows + 79) / 80;
-    const int wgs = batch * n_heads * n_qblk;
-    // the kernel's LDS footprint allows one workgroup per CU: ask for one round of <= 256
-    int splits = 256 / wgs;
-    if (splits > n_tiles) splits = n_tiles;
+    const int n_mt = (rows + 15) / 16;
+    const int n_chunks = (n_prompt + ctx_hint + ATT_CHUNK - 1) / ATT_CHUNK + n_mt;
+    const int wgs = batch * n_heads * n_mt;
+    // No key split while one workgroup's walk stays short (64 chunks = 2048 keys); beyond that,
+    // or when the row tiles alone leave most CUs idle on a long context, split the key axis
+    // (partials + merge kernel) into shares of at least 16 chunks.
+    int splits = (n_chunks + 63) / 64;
+    if (wgs * splits < 128) {
+        int fill = 256 / wgs;
+        if (fill > n_chunks / 16) fill = n_chunks / 16;
+        if (fill > splits) splits = fill;
+    }
     if (splits < 1) splits = 1;
-    if (splits > 32) splits = 32;
-    // equal shares: with per = ceil(tiles/splits) tiles each, drop the splits left without work
-    const int per = (n_tiles + splits - 1) / splits;
-    splits = (n_tiles + per - 1) / per;
+    if (splits > 64) splits = 64;
+    const int per = (n_chunks + splits - 1) / splits;
+    splits = (n_chunks + per - 1) / per;
     p.splits = splits;
     p.part_o_bytes = (size_t)batch * n_heads * splits * rows * hd * sizeof(float);
     p.part_ml_bytes = (size_t)batch * n_heads * splits * rows * 2 * sizeof(float);
     return p;
 }
 
-template <int HD, int MT>
+template <int HD>
 static void launch_attn_t(const TemplateDev &t, const void *q, const void *q_lo, const void *k_cache, const void *v_cache,
                           const void *k_tree, const void *v_tree, const void *k_tree_lo, const void *v_tree_lo,
-                          const void *prompt_k,
-                          const void *prompt_v, const int32_t *ctx_len, int batch, int Hq, int Hkv, int P,
-                          int smax, const AttnPlan &p, float *part_o, float *part_ml, hipStream_t s) {
-    constexpr int smem = att_smem_bytes<HD, MT>();
+                          const void *prompt_k, const void *prompt_v, const int32_t *ctx_len, int batch, int Hq,
+                          int Hkv, int P, int smax, const AttnPlan &p, float *part_o, float *part_ml, void *out,
+                          bool out_as_fragments, hipStream_t s) {
+    constexpr int D = 2;
+    using C = AttCfg<HD, D>;
     static bool attr_set = false;
     if (!attr_set) {
-        (void)hipFuncSetAttribute((const void *)tree_attn_kernel<HD, MT>,
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+        (void)hipFuncSetAttribute((const void *)tree_attn_kernel<HD, D>,
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM);
         attr_set = true;
     }
-    const int n_qblk = (t.rows + MT * 16 - 1) / (MT * 16);
+    const int n_mt = (t.rows + 15) / 16;
     const float scale_log2 = 1.4426950408889634f / sqrtf((float)HD);
-    dim3 grid(p.splits, Hq * n_qblk, batch);
-    hipLaunchKernelGGL((tree_attn_kernel<HD, MT>), grid, dim3(ATT_WAVES * 64), smem, s, t,
+    const int groups = batch * Hkv, per_group = (Hq / Hkv) * n_mt * p.splits;
+    const int grid = 8 * ((groups + 7) / 8) * per_group;
+    hipLaunchKernelGGL((tree_attn_kernel<HD, D>), dim3(grid), dim3(ATT_WAVES * 64), C::SMEM, s, t,
                        (const uint16_t *)q, (const uint16_t *)q_lo, (const uint16_t *)k_cache, (const uint16_t *)v_cache,
                        (const uint16_t *)k_tree, (const uint16_t *)v_tree, (const uint16_t *)k_tree_lo,
-                       (const uint16_t *)v_tree_lo, (const uint16_t *)prompt_k,
-                       (const uint16_t *)prompt_v, ctx_len, Hq, Hkv, P, smax, p.splits, n_qblk, scale_log2,
-                       part_o, part_ml);
+                       (const uint16_t *)v_tree_lo, (const uint16_t *)prompt_k, (const uint16_t *)prompt_v, ctx_len,
+                       batch, Hq, Hkv, P, smax, p.splits, n_mt, scale_log2, part_o, part_ml, (uint16_t *)out,
+                       out_as_fragments ? 1 : 0, (batch * t.rows + 15) / 16);
 }
 
 void launch_tree_attention(const TemplateDev &t, const void *q, const void *q_lo, const void *k_cache, const void *v_cache,
@@ -476,16 +572,16 @@ void launch_tree_attention(const TemplateDev &t, const void *q, const void *q_lo
                            const void *prompt_v, const int32_t *ctx_len, int batch, int Hq, int Hkv, int hd,
                            int P, int smax, const AttnPlan &p, float *part_o, float *part_ml, void *out,
                            bool out_as_fragments, hipStream_t s) {
-    const bool small = t.rows <= 16;
-    if (hd == 128) {
-        if (small) launch_attn_t<128, 1>(t, q, q_lo, k_cache, v_cache, k_tree, v_tree, k_tree_lo, v_tree_lo, prompt_k, prompt_v, ctx_len, batch, Hq, Hkv, P, smax, p, part_o, part_ml, s);
-        else launch_attn_t<128, 5>(t, q, q_lo, k_cache, v_cache, k_tree, v_tree, k_tree_lo, v_tree_lo, prompt_k, prompt_v, ctx_len, batch, Hq, Hkv, P, smax, p, part_o, part_ml, s);
-    } else {
-        if (small) launch_attn_t<64, 1>(t, q, q_lo, k_cache, v_cache, k_tree, v_tree, k_tree_lo, v_tree_lo, prompt_k, prompt_v, ctx_len, batch, Hq, Hkv, P, smax, p, part_o, part_ml, s);
-        else launch_attn_t<64, 5>(t, q, q_lo, k_cache, v_cache, k_tree, v_tree, k_tree_lo, v_tree_lo, prompt_k, prompt_v, ctx_len, batch, Hq, Hkv, P, smax, p, part_o, part_ml, s);
+    if (hd == 128)
+        launch_attn_t<128>(t, q, q_lo, k_cache, v_cache, k_tree, v_tree, k_tree_lo, v_tree_lo, prompt_k, prompt_v,
+                           ctx_len, batch, Hq, Hkv, P, smax, p, part_o, part_ml, out, out_as_fragments, s);
+    else
+        launch_attn_t<64>(t, q, q_lo, k_cache, v_cache, k_tree, v_tree, k_tree_lo, v_tree_lo, prompt_k, prompt_v,
+                          ctx_len, batch, Hq, Hkv, P, smax, p, part_o, part_ml, out, out_as_fragments, s);
+    if (p.splits > 1) {
+        const int heads_per_block = (256 / (hd / 4)) < Hq ? (256 / (hd / 4)) : Hq;
+        hipLaunchKernelGGL(attn_merge_kernel, dim3(t.rows, (Hq + heads_per_block - 1) / heads_per_block, batch),
+                           dim3(heads_per_block * (hd / 4)), 0, s, part_o, part_ml, t.rows,
+                           Hq, hd, p.splits, (uint16_t *)out, out_as_fragments ? 1 : 0, (batch * t.rows + 15) / 16);
     }
-    const int heads_per_block = (256 / (hd / 4)) < Hq ? (256 / (hd / 4)) : Hq;
-    hipLaunchKernelGGL(attn_merge_kernel, dim3(t.rows, (Hq + heads_per_block - 1) / heads_per_block, batch),
-                       dim3(heads_per_block * (hd / 4)), 0, s, part_o, part_ml, t.rows,
-                       Hq, hd, p.splits, (uint16_t *)out, out_as_fragments ? 1 : 0, (batch * t.rows + 15) / 16);
 }
