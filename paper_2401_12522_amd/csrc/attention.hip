@@ -4,19 +4,21 @@
 //
 // Flash-style, one workgroup per (sequence, query head, 16 query rows, key split):
 //  * A workgroup owns one m-tile of 16 query rows and walks the key axis
-//    [prefix | cache | pass rows] in chunks of 32 key slots.  Its 4 wavefronts take chunks
-//    round-robin and never synchronise inside the loop: each keeps its own online-softmax
-//    state, merged through LDS once at the end (fixed order, deterministic).  With 16 rows
+//    [prefix | cache | pass rows] in chunks of 32 key slots.  Its 8 wavefronts (two per SIMD,
+//    so that one wave's softmax arithmetic overlaps the other's matrix instructions) take
+//    chunks round-robin and never synchronise inside the loop: each keeps its own
+//    online-softmax state, merged through LDS once at the end (fixed order, deterministic).  With 16 rows
 //    per workgroup no split over the keys is needed to fill the chip at the verify shapes,
 //    so the output is normalised and written in place (no partial results, no second kernel)
 //    unless the context is long enough for the planner to ask for key splits.
 //  * Workgroups that read the same K/V head are placed on the same XCD (consecutive workgroup
 //    ids go round-robin over the 8 XCDs), so a head's K/V comes from HBM once and from that
 //    XCD's L2 for the other m-tiles and query heads of the group.
-//  * K chunks go from global memory straight into MFMA A-operand registers (16 bytes per
-//    lane and k-step); V chunks go straight into LDS with global->LDS loads, row-major, and
-//    are read back transposed (ds_read_tr16_b64) as the A operand of O^T = V^T P^T.  Each
-//    wave runs a ring of chunks in flight with compile-time wait counts.
+//  * K and V chunks go straight into LDS with global->LDS loads, row-major with an XOR swizzle
+//    of the 16-byte columns; K is read back as A-operand fragments, V transposed
+//    (ds_read_tr16_b64) as the A operand of O^T = V^T P^T.  A wave owns one 16 KiB chunk buffer:
+//    it pulls all fragments of a chunk into registers first and refills the buffer with the
+//    next chunk while it multiplies, the loads interleaved with the QK^T matrix instructions.
 //  * S^T = K Q^T is computed so that its accumulator layout is already the B-operand layout
 //    of O^T = V^T P^T: the probabilities never leave registers.  Queries, probabilities and
 //    the pass rows' K/V are each two bf16 planes (value and rounding residual).
@@ -47,6 +49,24 @@ __device__ __forceinline__ uint32_t cvt_pk_bf16(float lo, float hi) {
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
 
+// max / sum over the 4 lanes l, l^16, l^32, l^48 (the 16-lane groups of a wave) with the
+// gfx950 row swaps: permlane32_swap(a, b) returns ([a.lanes0-31, b.lanes0-31],
+// [a.lanes32-63, b.lanes32-63]); permlane16_swap does the same with rows 1 and 2 of each half
+__device__ __forceinline__ float max_over_lane_groups(float x) {
+    typedef __attribute__((ext_vector_type(2))) unsigned u32x2_t;
+    u32x2_t r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    x = fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+    r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float sum_over_lane_groups(float x) {
+    typedef __attribute__((ext_vector_type(2))) unsigned u32x2_t;
+    u32x2_t r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    x = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+    r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 // wait until at most N vector-memory operations of this wave are outstanding and all of its
 // LDS reads have returned; nothing may be moved across it
 template <int N>
@@ -65,8 +85,8 @@ __device__ __forceinline__ void att_static_for(F &&f) {
 }
 
 typedef __attribute__((ext_vector_type(4))) short s16x4;
-typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 // Transposed 16-bit LDS read (ds_read_b64_tr_b16): lane j of a 16-lane group receives, as
 // element e, column j%4 of the four 16-bit values that lane 4e + j/4 of the group addressed.
@@ -81,20 +101,31 @@ __device__ __forceinline__ s16x4 lds_read_tr16(uint32_t lds_addr) {
     asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(lds_addr), "n"(OFFSET));
     return v;
 }
-// wait for every LDS read of this wave; the registers pass through the statement so that no
-// use of them can be scheduled ahead of it
-template <int N>
-__device__ __forceinline__ void lds_wait_all(s16x4 (&v)[N][2]) {
-    static_assert(N == 4 || N == 8, "head dim 64 or 128");
-    if constexpr (N == 8)
+template <int OFFSET>
+__device__ __forceinline__ u32x4 lds_read_b128(uint32_t lds_addr) {
+    static_assert(OFFSET >= 0 && OFFSET < 65536, "ds offset field");
+    u32x4 v;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(lds_addr), "n"(OFFSET));
+    return v;
+}
+// wait for every LDS read of this wave; the registers pass through the statements so that no
+// use of them can be scheduled ahead of the wait
+template <int N, int M>
+__device__ __forceinline__ void lds_wait_all(u32x4 (&k)[2][N], s16x4 (&v)[M][2]) {
+    static_assert((N == 2 && M == 4) || (N == 4 && M == 8), "head dim 64 or 128");
+    if constexpr (N == 4) {
         asm volatile("s_waitcnt lgkmcnt(0)"
-                     : "+v"(v[0][0]), "+v"(v[0][1]), "+v"(v[1][0]), "+v"(v[1][1]), "+v"(v[2][0]), "+v"(v[2][1]),
-                       "+v"(v[3][0]), "+v"(v[3][1]), "+v"(v[4][0]), "+v"(v[4][1]), "+v"(v[5][0]), "+v"(v[5][1]),
-                       "+v"(v[6][0]), "+v"(v[6][1]), "+v"(v[7][0]), "+v"(v[7][1]));
-    else
-        asm volatile("s_waitcnt lgkmcnt(0)"
-                     : "+v"(v[0][0]), "+v"(v[0][1]), "+v"(v[1][0]), "+v"(v[1][1]), "+v"(v[2][0]), "+v"(v[2][1]),
-                       "+v"(v[3][0]), "+v"(v[3][1]));
+                     : "+v"(k[0][0]), "+v"(k[0][1]), "+v"(k[0][2]), "+v"(k[0][3]), "+v"(k[1][0]), "+v"(k[1][1]),
+                       "+v"(k[1][2]), "+v"(k[1][3]));
+        asm volatile("" : "+v"(v[0][0]), "+v"(v[0][1]), "+v"(v[1][0]), "+v"(v[1][1]), "+v"(v[2][0]), "+v"(v[2][1]),
+                          "+v"(v[3][0]), "+v"(v[3][1]));
+        asm volatile("" : "+v"(v[4][0]), "+v"(v[4][1]), "+v"(v[5][0]), "+v"(v[5][1]), "+v"(v[6][0]), "+v"(v[6][1]),
+                          "+v"(v[7][0]), "+v"(v[7][1]));
+    } else {
+        asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(k[0][0]), "+v"(k[0][1]), "+v"(k[1][0]), "+v"(k[1][1]));
+        asm volatile("" : "+v"(v[0][0]), "+v"(v[0][1]), "+v"(v[1][0]), "+v"(v[1][1]), "+v"(v[2][0]), "+v"(v[2][1]),
+                          "+v"(v[3][0]), "+v"(v[3][1]));
+    }
 }
 
 template <int HD, int D>
@@ -104,12 +135,12 @@ struct AttCfg {
     static constexpr int GPR = HD / 8;                        // 16-byte granules per K/V row
     static constexpr int RPI = 64 / GPR;                      // V rows per global->LDS instruction
     static constexpr int NVI = ATT_CHUNK / RPI;               // such instructions per chunk
-    static constexpr int LOADS = 2 * KSN + NVI + 1;           // vector-memory loads per wave per chunk (K, V, mask word)
-    static constexpr int CHUNK_BYTES = ATT_CHUNK * HD * 2;    // one V chunk in LDS
-    static constexpr int RING_BYTES = ATT_WAVES * D * CHUNK_BYTES;
+    static constexpr int LOADS = 2 * NVI + 1;                 // vector-memory loads per wave per chunk (K, V, mask word)
+    static constexpr int KV_BYTES = ATT_CHUNK * HD * 2;       // the K (or V) rows of one chunk
+    static constexpr int CHUNK_BYTES = 2 * KV_BYTES;          // one ring slot: [K rows | V rows]
+    static constexpr int RING_BYTES = ATT_WAVES * CHUNK_BYTES;       // one buffer per wave
     static constexpr int MERGE_BYTES = 2 * ATT_WAVES * 16 * 4 + (ATT_WAVES - 1) * NTN * 64 * 16;
     static constexpr int SMEM = RING_BYTES > MERGE_BYTES ? RING_BYTES : MERGE_BYTES;
-    static_assert((D - 2) * LOADS < 64, "vmcnt counter range");
 };
 
 // LDS row of key slot s inside a V chunk: the two 4-slot halves of each lane group's 8 slots
@@ -120,6 +151,10 @@ __device__ __forceinline__ int att_slot_of_row(int rho) { return 8 * ((rho & 15)
 // rows land on 8 different bank groups
 template <int HD>
 __device__ __forceinline__ int att_swizzle(int rho) { return HD == 128 ? 2 * (rho & 7) : 2 * ((rho >> 1) & 3); }
+// The K rows are read as A-operand fragments, 16 lanes fetching the same 16-byte column of 16
+// consecutive rows: there the granule index is XORed with 4 (3) bits of the row.
+template <int HD>
+__device__ __forceinline__ int att_swizzle_k(int rho) { return HD == 128 ? (rho & 15) : ((rho >> 1) & 7); }
 
 template <int HD, int D>
 __global__ __launch_bounds__(ATT_WAVES * 64) __attribute__((amdgpu_waves_per_eu(ATT_WAVES / 4, ATT_WAVES / 4))) void tree_attn_kernel(
@@ -194,25 +229,19 @@ __global__ __launch_bounds__(ATT_WAVES * 64) __attribute__((amdgpu_waves_per_eu(
     for (int nt = 0; nt < NTN; nt++) o_acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
     float m_run = -INFINITY, l_run = 0.f;
 
-    // Source row of key slot `slot` of chunk `chunk` (branch-free; padding reads the zero row)
-    auto src_row = [&](int chunk, int slot, const uint16_t *pp, const uint16_t *cp, const uint16_t *tp,
-                       const uint16_t *tp_lo, bool valid_stage) __attribute__((always_inline)) -> const uint16_t * {
-        const int kidx = chunk * ATT_CHUNK + slot;
-        const uint16_t *ctx_ptr = kidx < P ? pp + (int64_t)kidx * HD
-                                           : (kidx < n_ctx_keys ? cp + (int64_t)(kidx - P) * HD : zero);
-        const int j = (chunk - n_cc) * 16 + (slot >> 3) * 4 + (slot & 3);       // pass row
-        const bool lo = (slot & 4) != 0;                                         // partner slot
-        const uint16_t *plane = lo ? tp_lo : tp;
-        const uint16_t *tree_ptr = (j < R && plane) ? plane + (int64_t)j * HD : zero;
-        const uint16_t *p = chunk < n_cc ? ctx_ptr : tree_ptr;
-        return valid_stage ? p : zero;
-    };
-
-    u32x4 kf[D][2][KSN];
-    uint64_t anc_word[D];                                              // ancestor bits of row rq for a pass-row chunk
-    unsigned char *v_ring = smem + wave * D * C::CHUNK_BYTES;          // this wave's private ring
+    unsigned char *v_ring = smem + wave * C::CHUNK_BYTES;              // this wave's private chunk buffer
     // LDS addresses of this lane's transposed V reads inside ring slot 0: lane (g, c) addresses
     // V[slot 8g + 4half + c/4][16nt + 4(c%4) .. +4] and receives V[slots 8g + 4half .. +4][16nt + c]
+    // ... and of its K fragment reads: sub-tile tt, k-step ks = row 16tt + c, granule 4ks + g
+    uint32_t k_addr[2][KSN];
+#pragma unroll
+    for (int tt = 0; tt < 2; tt++)
+#pragma unroll
+        for (int ks = 0; ks < KSN; ks++) {
+            const int rho = 16 * tt + c;
+            k_addr[tt][ks] = (uint32_t)(size_t)((__attribute__((address_space(3))) unsigned char *)v_ring) +
+                             rho * (HD * 2) + (((4 * ks + g) ^ att_swizzle_k<HD>(rho)) * 16);
+        }
     uint32_t v_addr[NTN][2];
 #pragma unroll
     for (int nt = 0; nt < NTN; nt++)
@@ -221,87 +250,101 @@ __global__ __launch_bounds__(ATT_WAVES * 64) __attribute__((amdgpu_waves_per_eu(
             const int rho = 16 * half + 4 * g + (c >> 2);
             const int gran = (2 * nt + ((c & 3) >> 1)) ^ att_swizzle<HD>(rho);
             v_addr[nt][half] = (uint32_t)(size_t)((__attribute__((address_space(3))) unsigned char *)v_ring) +
-                               rho * (HD * 2) + gran * 16 + (c & 1) * 8;
+                               C::KV_BYTES + rho * (HD * 2) + gran * 16 + (c & 1) * 8;
         }
 
-    // Per-lane byte offsets of the fast path (a chunk that lies wholly inside the cache): K rows
-    // of S^T sub-tile tt are slots 8*(c/4) + 4*tt + c%4, so that a lane of the accumulator holds
-    // 8 consecutive slots (8g .. 8g+7) for its query; the V row a lane copies in global->LDS
-    // instruction iv is slot v_slot_base(iv) + v_slot_lane, granule (lane%GPR) ^ swizzle(row).
-    uint32_t k_off[2], v_off[2];
-#pragma unroll
-    for (int tt = 0; tt < 2; tt++) k_off[tt] = (8 * (c >> 2) + 4 * tt + (c & 3)) * (HD * 2) + g * 16;
+    // Per-lane byte offsets of the fast path (a chunk that lies wholly inside the cache).  Both
+    // operands are copied row-major, 1 KiB (RPI rows) per global->LDS instruction: instruction
+    // iv fills LDS rows iv*RPI .., LDS row rho holds key slot att_slot_of_row(rho), and the lane
+    // at granule position p of that row fetches granule p ^ swizzle(rho).  The swizzles depend
+    // on iv only through iv%4 (K) and iv%2 (V).
+    // In a chunk over the pass rows slot s is pass row 4*(s>>3) + (s&3) of the chunk's 16, plane
+    // (s>>2)&1; the instruction's first slot and the lane's slot inside the instruction occupy
+    // disjoint bits, so row and plane split the same way (the plane is uniform per instruction).
     const int v_lane_row = lane / GPR;                                  // row inside one instruction
+    const int lane_slot = att_slot_of_row(v_lane_row);
+    const int lane_tree_row = 4 * (lane_slot >> 3) + (lane_slot & 3);
+    uint32_t k_gran[4], v_gran[2];                                      // source granule (bytes) at this lane's position
 #pragma unroll
-    for (int par = 0; par < 2; par++) {
-        const int rho = par * RPI + v_lane_row;                          // swizzle depends on iv only through iv&1
-        v_off[par] = (att_slot_of_row(v_lane_row)) * (HD * 2) + (((lane % GPR) ^ att_swizzle<HD>(rho)) * 16);
+    for (int par = 0; par < 4; par++) {
+        const int rho = par * RPI + v_lane_row;
+        k_gran[par] = ((lane % GPR) ^ att_swizzle_k<HD>(rho)) * 16;
+        if (par < 2) v_gran[par] = ((lane % GPR) ^ att_swizzle<HD>(rho)) * 16;
     }
 
-    // Issue all loads of this wave's stage i into ring slot SLOT: always exactly C::LOADS
-    // vector-memory operations, in one straight-line run (stages past the end read the zero
-    // row).  Only the address computation branches: a chunk wholly inside the cache takes
-    // one uniform base per operand plus the constant lane offsets.
-    auto issue = [&](auto slot_c, int i) __attribute__((always_inline)) {
-        constexpr int SLOT = decltype(slot_c)::value;
+    // The two global->LDS loads (one K, one V instruction) number iv < NVI of this wave's stage i,
+    // the mask word riding with the last.  A chunk wholly inside the cache takes one uniform base
+    // per operand plus the constant lane offsets; the other cases select per lane.
+    typedef const __attribute__((address_space(1))) unsigned char *gptr;   // keeps the loads global, not flat
+    uint64_t anc_next = 0;                                              // ancestor bits for the stage in flight
+    auto emit = [&](int i, int iv) __attribute__((always_inline)) {
         const int chunk = chunk_begin + wave + ATT_WAVES * i;
-        const bool valid = i < n_my;
         const int base = chunk * ATT_CHUNK;
         const unsigned char *zero_b = reinterpret_cast<const unsigned char *>(zero);
-        typedef const __attribute__((address_space(1))) unsigned char *gptr;   // keeps the loads global, not flat
-        gptr k_src[2], v_src[NVI], a_src = (gptr)(zero_b + (lane & 1) * 8);
-        if (valid && base >= P && base + ATT_CHUNK <= n_ctx_keys) {
-            const unsigned char *ubk = reinterpret_cast<const unsigned char *>(ck + (int64_t)(base - P) * HD);
-            const unsigned char *ubv = reinterpret_cast<const unsigned char *>(cv + (int64_t)(base - P) * HD);
-#pragma unroll
-            for (int tt = 0; tt < 2; tt++) k_src[tt] = (gptr)(ubk + k_off[tt]);
-#pragma unroll
-            for (int iv = 0; iv < NVI; iv++) v_src[iv] = (gptr)(ubv + att_slot_of_row(iv * RPI) * (HD * 2) + v_off[iv & 1]);
+        const int slot0 = att_slot_of_row(iv * RPI);                    // slot of the instruction's first row
+        gptr k_src, v_src, a_src = (gptr)(zero_b + (lane & 1) * 8);
+        if (base >= P && base + ATT_CHUNK <= n_ctx_keys) {
+            const int64_t row_bytes = ((int64_t)(base - P + slot0) + lane_slot) * (HD * 2);
+            k_src = (gptr)(reinterpret_cast<const unsigned char *>(ck) + row_bytes + k_gran[iv & 3]);
+            v_src = (gptr)(reinterpret_cast<const unsigned char *>(cv) + row_bytes + v_gran[iv & 1]);
+        } else if (chunk >= n_cc) {
+            // over the pass rows: one plane and 4-row group per instruction, rows beyond R are zero
+            const int j_first = (chunk - n_cc) * 16;
+            if (row_ok) a_src = (gptr)(t.anc + (int64_t)rq * t.words + (j_first >> 6));   // ancestor bits of these 16 rows
+            const int j = j_first + 4 * (slot0 >> 3) + lane_tree_row;
+            const uint16_t *kp = (slot0 & 4) ? tk_lo : tk, *vp = (slot0 & 4) ? tv_lo : tv;   // uniform
+            const bool k_ok = j < R && kp, v_ok = j < R && vp;
+            k_src = (gptr)(reinterpret_cast<const unsigned char *>(k_ok ? kp + (int64_t)j * HD : zero) + k_gran[iv & 3]);
+            v_src = (gptr)(reinterpret_cast<const unsigned char *>(v_ok ? vp + (int64_t)j * HD : zero) + v_gran[iv & 1]);
         } else {
-#pragma unroll
-            for (int tt = 0; tt < 2; tt++) {
-                const int slot = 8 * (c >> 2) + 4 * tt + (c & 3);
-                const uint16_t *row = src_row(chunk, slot, pk, ck, tk, tk_lo, valid);
-                k_src[tt] = (gptr)(row + g * 8);
-            }
-            // the 64-bit word of this row's ancestor bitset that covers the chunk's 16 pass rows
-            if (valid && row_ok && chunk >= n_cc)
-                a_src = (gptr)(t.anc + (int64_t)rq * t.words + (((chunk - n_cc) * 16) >> 6));
-#pragma unroll
-            for (int iv = 0; iv < NVI; iv++) {
-                const int rho = iv * RPI + v_lane_row;                   // LDS row written by this lane
-                const uint16_t *row = src_row(chunk, att_slot_of_row(rho), pv, cv, tv, tv_lo, valid);
-                const int gran = (lane % GPR) ^ att_swizzle<HD>(rho);    // source granule for this position
-                v_src[iv] = (gptr)(row + gran * 8);
-            }
+            // a chunk with prefix rows or the ragged end of the cache
+            const int kidx = base + slot0 + lane_slot;
+            const bool in_prefix = kidx < P, in_cache = kidx >= P && kidx < n_ctx_keys;
+            const uint16_t *krow = in_prefix ? pk + (int64_t)kidx * HD : (in_cache ? ck + (int64_t)(kidx - P) * HD : zero);
+            const uint16_t *vrow = in_prefix ? pv + (int64_t)kidx * HD : (in_cache ? cv + (int64_t)(kidx - P) * HD : zero);
+            k_src = (gptr)(reinterpret_cast<const unsigned char *>(krow) + k_gran[iv & 3]);
+            v_src = (gptr)(reinterpret_cast<const unsigned char *>(vrow) + v_gran[iv & 1]);
         }
-#pragma unroll
-        for (int tt = 0; tt < 2; tt++)
-#pragma unroll
-            for (int ks = 0; ks < KSN; ks++)
-                kf[SLOT][tt][ks] = *(const __attribute__((address_space(1))) u32x4 *)(k_src[tt] + ks * 64);
-        anc_word[SLOT] = *(const __attribute__((address_space(1))) uint64_t *)a_src;
-        unsigned char *dst0 = v_ring + SLOT * C::CHUNK_BYTES;           // wave-uniform; lane l lands at +16l
-#pragma unroll
-        for (int iv = 0; iv < NVI; iv++)
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)v_src[iv],
-                                             (__attribute__((address_space(3))) void *)(dst0 + iv * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)k_src,
+                                         (__attribute__((address_space(3))) void *)(v_ring + iv * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)v_src,
+                                         (__attribute__((address_space(3))) void *)(v_ring + C::KV_BYTES + iv * 1024), 16, 0, 0);
+        if (iv == NVI - 1) anc_next = *(const __attribute__((address_space(1))) uint64_t *)a_src;
     };
 
-    auto compute = [&](auto slot_c, int i) __attribute__((always_inline)) {
-        constexpr int SLOT = decltype(slot_c)::value;
+    // One chunk.  Its K and V fragments are all pulled into registers first, which frees the
+    // wave's LDS buffer: the next chunk's loads are issued into it right away, interleaved
+    // with the QK^T matrix instructions, and have the rest of the step to land.
+    auto compute = [&](int i, bool more) __attribute__((always_inline)) {
+        constexpr int SLOT = 0;
+        const uint64_t anc_cur = anc_next;
         const int chunk = chunk_begin + wave + ATT_WAVES * i;
         const bool tree_chunk = chunk >= n_cc;
         const int base = chunk * ATT_CHUNK;
+        u32x4 kf[2][KSN];
+#pragma unroll
+        for (int tt = 0; tt < 2; tt++)
+#pragma unroll
+            for (int ks = 0; ks < KSN; ks++) kf[tt][ks] = lds_read_b128<SLOT * C::CHUNK_BYTES>(k_addr[tt][ks]);
+        s16x4 vh[NTN][2];
+#pragma unroll
+        for (int nt = 0; nt < NTN; nt++) {
+            vh[nt][0] = lds_read_tr16<SLOT * C::CHUNK_BYTES>(v_addr[nt][0]);
+            vh[nt][1] = lds_read_tr16<SLOT * C::CHUNK_BYTES>(v_addr[nt][1]);
+        }
+        lds_wait_all(kf, vh);
         f32x4 s_acc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+        static_assert(NVI == 2 * KSN, "one (k-step, sub-tile) pair per load slot");
 #pragma unroll
-        for (int ks = 0; ks < KSN; ks++)
-#pragma unroll
-            for (int tt = 0; tt < 2; tt++) {
-                const bf16x8 ka = __builtin_bit_cast(bf16x8, kf[SLOT][tt][ks]);
-                s_acc[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qf[0][ks], s_acc[tt], 0, 0, 0);
-                s_acc[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qf[1][ks], s_acc[tt], 0, 0, 0);
-            }
+        for (int iv = 0; iv < NVI; iv++) {
+            const int ks = iv >> 1, tt = iv & 1;
+            if (more) emit(i + 1, iv);
+            __builtin_amdgcn_sched_barrier(0);
+            const bf16x8 ka = __builtin_bit_cast(bf16x8, kf[tt][ks]);
+            s_acc[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qf[0][ks], s_acc[tt], 0, 0, 0);
+            s_acc[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qf[1][ks], s_acc[tt], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
         float sv[8];
 #pragma unroll
         for (int tt = 0; tt < 2; tt++)
@@ -319,7 +362,7 @@ __global__ __launch_bounds__(ATT_WAVES * 64) __attribute__((amdgpu_waves_per_eu(
             if (row_ok) {
                 if (tree_chunk) {
                     const int j0 = (chunk - n_cc) * 16 + 4 * g;          // this lane's 4 pass rows (4-aligned)
-                    const uint32_t four = (uint32_t)(anc_word[SLOT] >> (j0 & 63)) & 0xFu;
+                    const uint32_t four = (uint32_t)(anc_cur >> (j0 & 63)) & 0xFu;
 #pragma unroll
                     for (int e = 0; e < 4; e++) bits |= ((j0 + e < R) ? ((four >> e) & 1u) : 0u) << e;
                 } else {
@@ -339,8 +382,7 @@ __global__ __launch_bounds__(ATT_WAVES * 64) __attribute__((amdgpu_waves_per_eu(
         float mx = sv[0];
 #pragma unroll
         for (int e = 1; e < 8; e++) mx = fmaxf(mx, sv[e]);
-        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        mx = max_over_lane_groups(mx);
         const float m_new = fmaxf(m_run, mx);
         const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
         const float alpha = fast_exp2(m_run - m_use);
@@ -364,57 +406,40 @@ __global__ __launch_bounds__(ATT_WAVES * 64) __attribute__((amdgpu_waves_per_eu(
             pl2[3] = pl2[1];
         }
         l_run = l_run * alpha + ps;
+        // O^T[hd][q] = alpha * O^T + V^T[hd][slots 8g..8g+7] * P^T; the running maximum rarely
+        // moves after the first chunks, and then alpha is exactly 1 in every lane
+        if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+#pragma unroll
+            for (int nt = 0; nt < NTN; nt++) o_acc[nt] *= alpha;
+        }
         const bf16x8 pf = __builtin_bit_cast(bf16x8, make_uint4(pk2[0], pk2[1], pk2[2], pk2[3]));
         const bf16x8 pf_lo = __builtin_bit_cast(bf16x8, make_uint4(pl2[0], pl2[1], pl2[2], pl2[3]));
-        // O^T[hd][q] = alpha * O^T + V^T[hd][slots 8g..8g+7] * P^T
-        s16x4 vh[NTN][2];
-#pragma unroll
-        for (int nt = 0; nt < NTN; nt++) {
-            vh[nt][0] = lds_read_tr16<SLOT * C::CHUNK_BYTES>(v_addr[nt][0]);
-            vh[nt][1] = lds_read_tr16<SLOT * C::CHUNK_BYTES>(v_addr[nt][1]);
-        }
-        lds_wait_all(vh);
 #pragma unroll
         for (int nt = 0; nt < NTN; nt++) {
             const s16x8 v8 = {vh[nt][0][0], vh[nt][0][1], vh[nt][0][2], vh[nt][0][3],
                               vh[nt][1][0], vh[nt][1][1], vh[nt][1][2], vh[nt][1][3]};
             const bf16x8 vf = __builtin_bit_cast(bf16x8, v8);
-            o_acc[nt] *= alpha;
             o_acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf, o_acc[nt], 0, 0, 0);
             o_acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf_lo, o_acc[nt], 0, 0, 0);
         }
     };
 
-    // ---- per-wave ring: D-1 chunks in flight behind the one being multiplied.  Every step
-    //      issues exactly C::LOADS loads, so the wait count is a compile-time constant; the
-    //      wait also retires this wave's LDS reads of the slot about to be refilled.
-    auto step = [&](auto u_c, int i) __attribute__((always_inline)) {
-        constexpr int U = decltype(u_c)::value;
-        constexpr int PRE = (U + D - 1) % D;
-        att_wait<(D - 2) * C::LOADS>();
-        issue(std::integral_constant<int, PRE>{}, i + D - 1);
-        compute(u_c, i);
-    };
-    att_static_for<0, D - 1>([&](auto u_c) __attribute__((always_inline)) { issue(u_c, decltype(u_c)::value); });
-    int i = 0;
-    for (; i + D <= n_my; i += D)
-        att_static_for<0, D>([&](auto u_c) __attribute__((always_inline)) { step(u_c, i + decltype(u_c)::value); });
-    att_static_for<0, D - 1>([&](auto u_c) __attribute__((always_inline)) {          // remaining n_my % D chunks: nothing more to fetch
-        constexpr int U = decltype(u_c)::value;
-        if (i + U < n_my) {
-            att_wait<(D - 2 - U) * C::LOADS>();
-            compute(u_c, i + U);
-        }
-    });
-    att_wait<0>();                                      // also the loads of stages past the end
+    // ---- per-wave loop: one chunk in flight behind the one being multiplied -------------------
+    if (n_my > 0) {
+#pragma unroll
+        for (int iv = 0; iv < NVI; iv++) emit(0, iv);
+    }
+    for (int i = 0; i < n_my; i++) {
+        att_wait<0>();                                  // the chunk has landed
+        compute(i, i + 1 < n_my);
+    }
+    att_wait<0>();
 
     // ---- merge the 4 wavefronts (disjoint key subsets); wave 0 sums in wave order ----------
     __syncthreads();
     float *sm = reinterpret_cast<float *>(smem), *sl = sm + ATT_WAVES * 16;
     float4 *region = reinterpret_cast<float4 *>(smem + 2 * ATT_WAVES * 16 * 4);   // [WAVES-1][NTN][64]
-    float l = l_run;
-    l += __shfl_xor(l, 16, 64);
-    l += __shfl_xor(l, 32, 64);
+    const float l = sum_over_lane_groups(l_run);
     if (g == 0) {
         sm[wave * 16 + c] = m_run;
         sl[wave * 16 + c] = l;
