@@ -249,10 +249,11 @@ GemmPlan gemm_plan(int m_rows, int64_t n_rows, int64_t k) {
     GemmPlan p;
     const int64_t NT = n_rows / 16, KS = (k + 31) / 32;
     // Shapes measured on MI355X at 68 rows: 128-column, 4-wave workgroups for narrow matrices,
-    // 256 columns for wider ones (8 waves x 2 tiles, or 4 waves x 4 tiles in the mid range); as
+    // 256 columns for wider ones (8 waves x 2 tiles, or 4 waves x 4 tiles in the mid range), 512
+    // for the widest (8 waves x 4 tiles); as
     // many splits as give one round of equal workgroups (512 of 4 waves, 256 of 8), but no more
     // than 8 for the narrow ones, whose partial sums are re-read by a row-wise consumer.
-    p.variant = NT < 512 ? 1 : (NT < 1024 ? 3 : (NT < 1800 ? 2 : 3));
+    p.variant = NT < 512 ? 1 : (NT < 1024 ? 3 : (NT < 1800 ? 2 : (NT < 3000 ? 3 : 4)));
     if (g_force_variant >= 0 && g_force_variant < GEMM_N_VARIANTS) p.variant = g_force_variant;
     const GemmVariant &v = g_variants[p.variant];
     const int tiles_wg = v.nw * v.waves;
