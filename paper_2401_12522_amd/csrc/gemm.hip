@@ -65,33 +65,46 @@ __device__ __forceinline__ void static_for(F &&f) {
 
 // MT m-tiles of 16 rows, NW n-tiles per wave, SPLIT = two activation planes, KC k-steps (of 32)
 // per pipeline stage, D stages in the ring (D-1 in flight behind the one being multiplied),
-// WAVES wavefronts per workgroup.
-template <int MT, int NW, bool SPLIT, int KC, int D, int WAVES>
+// WAVES wavefronts per workgroup, of which KG groups of WN = WAVES/KG waves each take one
+// contiguous part of the workgroup's k range (with their own activation ring) and are summed
+// through LDS at the end: twice the waves per partial sum written.
+template <int MT, int NW, bool SPLIT, int KC, int D, int WAVES, int KG>
 struct GemmCfg {
+    static constexpr int WN = WAVES / KG;                       // waves side by side along N
     static constexpr int PL = SPLIT ? 2 : 1;
     static constexpr int NFRAG = PL * MT * KC;                  // A fragments per stage
-    static constexpr int FPW = (NFRAG + WAVES - 1) / WAVES;     // fetched per wave per stage
+    static constexpr int FPW = (NFRAG + WN - 1) / WN;           // fetched per wave per stage
     static constexpr int LOADS = NW * KC + FPW;                 // vector-memory loads per wave per stage
     // every wave issues FPW fragment loads per stage (the vmcnt bookkeeping counts on it);
     // those beyond NFRAG land in one shared dump slot after the ring
-    static constexpr int SMEM = (D * NFRAG + 1) * 1024;
+    static constexpr int RING = KG * D * NFRAG * 1024;          // one ring per k group
+    static constexpr int MERGE = KG > 1 ? WN * MT * NW * 1024 : 0;   // accumulators of one k group
+    static constexpr int SMEM = (RING > MERGE ? RING : MERGE) + 1024;
     static_assert((D - 2) * LOADS < 64, "vmcnt counter range");
 };
 
-template <int MT, int NW, bool SPLIT, int KC, int D, int WAVES>
+template <int MT, int NW, bool SPLIT, int KC, int D, int WAVES, int KG>
 __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
     const uint4 *__restrict__ A_frag, int planes_stride_f, int M, int m_tiles,
     const uint4 *__restrict__ Wp, int NT, int KS, float *__restrict__ out, int64_t ldo,
     int ksteps_per_split) {
-    using C = GemmCfg<MT, NW, SPLIT, KC, D, WAVES>;
-    extern __shared__ __attribute__((aligned(16))) uint4 a_lds[];   // [D][NFRAG][64] + dump slot
+    using C = GemmCfg<MT, NW, SPLIT, KC, D, WAVES, KG>;
+    constexpr int WN = C::WN;
+    extern __shared__ __attribute__((aligned(16))) uint4 smem_u4[];   // [KG][D][NFRAG][64] + dump slot
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int t0 = (blockIdx.x * WAVES + wave) * NW;
-    const int ks_begin = blockIdx.y * ksteps_per_split;
-    const int ks_end = min(KS, ks_begin + ksteps_per_split);
+    const int kg = wave / WN, wn = wave % WN;                  // k group, position along N
+    const int t0 = (blockIdx.x * WN + wn) * NW;
+    // the workgroup's k range, cut into KG contiguous parts of equal stage count
+    const int wg_begin = blockIdx.y * ksteps_per_split;
+    const int wg_end = min(KS, wg_begin + ksteps_per_split);
+    const int per_group = (wg_end - wg_begin + KG - 1) / KG;
+    const int ks_begin = wg_begin + kg * per_group;
+    const int ks_end = min(wg_end, ks_begin + per_group);
     const int m_base = blockIdx.z * (MT * 16);
-    const int n_stages = (ks_end - ks_begin + KC - 1) / KC;
+    const int n_stages = (per_group + KC - 1) / KC;            // same for every wave: barriers in lockstep
+    uint4 *a_lds = smem_u4 + kg * (D * C::NFRAG * 64);         // this k group's ring
+    uint4 *dump = smem_u4 + KG * D * C::NFRAG * 64;            // target of padding fetches
     (void)M;
 
     f32x4 acc[MT][NW];
@@ -119,14 +132,14 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
             }
 #pragma unroll
         for (int i = 0; i < C::FPW; i++) {
-            const int f = i * WAVES + wave;                       // fragment id inside the stage
+            const int f = i * WN + wn;                            // fragment id inside the stage
             const int plane = f / (MT * KC), mt = (f / KC) % MT, s = f % KC;
             const int mtg = blockIdx.z * MT + mt;                 // m-tile in the whole slab
             const bool ok = (f < C::NFRAG) && (mtg < m_tiles) && (ks0 + s < ks_end);
             // fragment (plane, ks, mtg) starts at ((plane * KS + ks) * m_tiles + mtg) * 64 uint4
             const uint4 *src = ok ? A_frag + ((int64_t)plane * planes_stride_f + (int64_t)(ks0 + s) * m_tiles + mtg) * 64 + lane
                                   : &g_zero16;
-            uint4 *dst = a_lds + (f < C::NFRAG ? SLOT * C::NFRAG + f : D * C::NFRAG) * 64;   // wave-uniform; lane l lands at dst[l]
+            uint4 *dst = f < C::NFRAG ? a_lds + (SLOT * C::NFRAG + f) * 64 : dump;   // wave-uniform; lane l lands at dst[l]
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
                                              (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
         }
@@ -181,6 +194,33 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
         }
     });
 
+    if constexpr (KG > 1) {
+        // sum the k groups through LDS, group by group in a fixed order; group 0 stores
+        wait_vmcnt_lds<0>();                                 // incl. this wave's fetches of stages past the end
+        float4 *mrg = reinterpret_cast<float4 *>(smem_u4) + wn * (MT * NW * 64);
+#pragma unroll
+        for (int src = 1; src < KG; src++) {
+            __syncthreads();
+            if (kg == src) {
+#pragma unroll
+                for (int i = 0; i < MT; i++)
+#pragma unroll
+                    for (int j = 0; j < NW; j++)
+                        mrg[(i * NW + j) * 64 + lane] = make_float4(acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]);
+            }
+            __syncthreads();
+            if (kg == 0) {
+#pragma unroll
+                for (int i = 0; i < MT; i++)
+#pragma unroll
+                    for (int j = 0; j < NW; j++) {
+                        const float4 v = mrg[(i * NW + j) * 64 + lane];
+                        acc[i][j][0] += v.x; acc[i][j][1] += v.y; acc[i][j][2] += v.z; acc[i][j][3] += v.w;
+                    }
+            }
+        }
+        if (kg != 0) return;
+    }
     // D layout: lane (g = lane/16, c = lane%16) holds rows 4g..4g+3, column c of each tile.
     const int g = lane >> 4, cc = lane & 15;
     float *o = out + (int64_t)blockIdx.y * M * ldo;
@@ -237,9 +277,10 @@ __global__ void to_fragments_kernel(const uint16_t *__restrict__ a_hi, const uin
 // Launch shapes.  Wide groups reuse each activation fragment for more weight tiles (the
 // L2->LDS slab traffic is what limits narrow ones) but produce wider split-K partials; deep
 // rings and more waves keep more weight bytes in flight per CU.
-struct GemmVariant { int nw, waves, depth; };
+struct GemmVariant { int nw, waves, depth, kgroups; };
 static const GemmVariant g_variants[] = {
-    {1, 4, 4}, {2, 4, 4}, {4, 4, 4}, {2, 8, 6}, {4, 8, 6},
+    {1, 4, 4, 1}, {2, 4, 4, 1}, {4, 4, 4, 1}, {2, 8, 6, 1}, {4, 8, 6, 1},
+    {2, 8, 4, 2}, {4, 8, 4, 2}, {1, 8, 4, 2}, {2, 8, 3, 2},
 };
 #define GEMM_N_VARIANTS ((int)(sizeof(g_variants) / sizeof(g_variants[0])))
 static int g_force_variant = -1, g_force_splits = -1;
@@ -248,15 +289,14 @@ void gemm_force_plan(int variant, int splits) { g_force_variant = variant; g_for
 GemmPlan gemm_plan(int m_rows, int64_t n_rows, int64_t k) {
     GemmPlan p;
     const int64_t NT = n_rows / 16, KS = (k + 31) / 32;
-    // Shapes measured on MI355X at 68 rows: 128-column, 4-wave workgroups for narrow matrices,
-    // 256 columns for wider ones (8 waves x 2 tiles, or 4 waves x 4 tiles in the mid range), 512
-    // for the widest (8 waves x 4 tiles); as
-    // many splits as give one round of equal workgroups (512 of 4 waves, 256 of 8), but no more
-    // than 8 for the narrow ones, whose partial sums are re-read by a row-wise consumer.
-    p.variant = NT < 512 ? 1 : (NT < 1024 ? 3 : (NT < 1800 ? 2 : (NT < 3000 ? 3 : 4)));
+    // Shapes measured on MI355X at 68 rows (7B- and 70B-like widths): 8 waves as 2 k groups x 4,
+    // 2 tiles per wave (128 columns per workgroup), 4 tiles for the widest matrices; as many
+    // splits as give one round of 256 equal workgroups, but no more than 8 for the narrow ones,
+    // whose partial sums are re-read by a row-wise consumer.
+    p.variant = NT < 3000 ? 8 : 6;
     if (g_force_variant >= 0 && g_force_variant < GEMM_N_VARIANTS) p.variant = g_force_variant;
     const GemmVariant &v = g_variants[p.variant];
-    const int tiles_wg = v.nw * v.waves;
+    const int tiles_wg = v.nw * v.waves / v.kgroups;
     const int64_t wgs_n = (NT + tiles_wg - 1) / tiles_wg;
     int64_t splits = (v.waves > 4 ? 256 : 512) / wgs_n;
     const int64_t max_splits = KS / 8;                          // at least 8 stages per split
@@ -272,20 +312,20 @@ GemmPlan gemm_plan(int m_rows, int64_t n_rows, int64_t k) {
     return p;
 }
 
-template <int MT, int NW, bool SPLIT, int WAVES, int D>
+template <int MT, int NW, bool SPLIT, int WAVES, int D, int KG>
 static void launch_gemm_t(const void *a_frag, int M, int64_t K, const void *w, int64_t N, float *out, int64_t ldo,
                           const GemmPlan &p, hipStream_t s) {
     constexpr int KC = 1;
-    using C = GemmCfg<MT, NW, SPLIT, KC, D, WAVES>;
+    using C = GemmCfg<MT, NW, SPLIT, KC, D, WAVES, KG>;
     static bool attr_set = false;
     if (!attr_set) {
-        (void)hipFuncSetAttribute((const void *)gemm_skinny_kernel<MT, NW, SPLIT, KC, D, WAVES>,
+        (void)hipFuncSetAttribute((const void *)gemm_skinny_kernel<MT, NW, SPLIT, KC, D, WAVES, KG>,
                                   hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM);
         attr_set = true;
     }
     const int NT = (int)(N / 16), KS = (int)((K + 31) / 32), m_tiles = (M + 15) / 16;
-    dim3 grid((NT + WAVES * NW - 1) / (WAVES * NW), p.splits, (m_tiles + MT - 1) / MT);
-    hipLaunchKernelGGL((gemm_skinny_kernel<MT, NW, SPLIT, KC, D, WAVES>), grid, dim3(WAVES * 64), C::SMEM, s,
+    dim3 grid((NT + C::WN * NW - 1) / (C::WN * NW), p.splits, (m_tiles + MT - 1) / MT);
+    hipLaunchKernelGGL((gemm_skinny_kernel<MT, NW, SPLIT, KC, D, WAVES, KG>), grid, dim3(WAVES * 64), C::SMEM, s,
                        (const uint4 *)a_frag, KS * m_tiles, M, m_tiles, (const uint4 *)w, NT, KS, out, ldo,
                        p.ksteps_per_split);
 }
@@ -293,9 +333,10 @@ static void launch_gemm_t(const void *a_frag, int M, int64_t K, const void *w, i
 template <int MT, bool SPLIT>
 static void launch_gemm_v(const void *a_frag, int M, int64_t K, const void *w, int64_t N, float *out, int64_t ldo,
                           const GemmPlan &p, hipStream_t s) {
-#define V(i, nw, waves, d) case i: launch_gemm_t<MT, nw, SPLIT, waves, d>(a_frag, M, K, w, N, out, ldo, p, s); break;
+#define V(i, nw, waves, d, kg) case i: launch_gemm_t<MT, nw, SPLIT, waves, d, kg>(a_frag, M, K, w, N, out, ldo, p, s); break;
     switch (p.variant) {
-        V(0, 1, 4, 4) V(1, 2, 4, 4) V(2, 4, 4, 4) V(3, 2, 8, 6) V(4, 4, 8, 6)
+        V(0, 1, 4, 4, 1) V(1, 2, 4, 4, 1) V(2, 4, 4, 4, 1) V(3, 2, 8, 6, 1) V(4, 4, 8, 6, 1)
+        V(5, 2, 8, 4, 2) V(6, 4, 8, 4, 2) V(7, 1, 8, 4, 2) V(8, 2, 8, 3, 2)
     }
 #undef V
 }
