@@ -26,6 +26,12 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0
 
 
+# HBM-side bytes (fetch + write) per GEMM launch, averaged over the launches of one step, from the
+# FETCH_SIZE / WRITE_SIZE counter runs scaled by a copy kernel (profiles/gemm_traffic_7b.md);
+# counters cannot be collected from inside this process, so the figure is carried as a constant
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = {"7b": 125.1e6}
+
+
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -37,6 +43,9 @@ def parse_args():
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--calibration-copy-mb", type=int, default=0,
+                    help="also run a plain device copy of this many MB a few times (a kernel of known "
+                         "traffic, to scale rocprofv3's FETCH_SIZE / WRITE_SIZE readings)")
     return ap.parse_args()
 
 
@@ -116,6 +125,14 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     bita.lib()
+    if args.calibration_copy_mb > 0:
+        n = args.calibration_copy_mb * (1 << 20) // 4
+        src_t = torch.ones(n, dtype=torch.float32, device="cuda")
+        dst_t = torch.empty_like(src_t)
+        for _ in range(4):
+            torch.add(src_t, 1.0, out=dst_t)      # reads n*4 bytes, writes n*4 bytes
+        torch.cuda.synchronize()
+        del src_t, dst_t
     cfg = synth.get_config(args.workload)
     ctx_n = args.ctx or {"tiny": 64, "7b": 1024, "13b": 2048, "70b": 2048}[args.workload]
     tin = workload_template(synth, cfg, args.workload)
@@ -298,7 +315,7 @@ def main():
     gemm_gbps = float(np.sum(g_bytes)) / (float(np.sum(g_ms)) * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": "gemm_skinny_kernel (all %d launches of a step)" % n_gemm,
                 "achieved": gemm_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": gemm_gbps / HBM_PEAK_GBPS,
-                "traffic": None, "avg_launch_us": gemm_avg_us,
+                "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH.get(args.workload), "avg_launch_us": gemm_avg_us,
                 "bytes_per_launch": float(np.mean(g_bytes)),
                 "gemm_ms_per_step": float(np.sum(g_ms)) / prof_steps}
 
