@@ -8,7 +8,7 @@ import numpy as np
 import torch
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_PKG, "libbita.so")
+_LIB_PATH = os.environ.get("BITA_LIBRARY") or os.path.join(_PKG, "libbita.so")   # override: another build of the same ABI
 _lib = None
 
 EXPORTS = [

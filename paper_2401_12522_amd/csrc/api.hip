@@ -240,10 +240,10 @@ extern "C" int bita_profile_read(int32_t capacity, int32_t *n_records, float *ms
     return BITA_OK;
 }
 static void timed_gemm(const void *a_frag, int M, int64_t K, const void *w, int64_t N, float *out, int64_t ldo,
-                       const GemmPlan &p, hipStream_t s) {
+                       const GemmPlan &p, hipStream_t s, const GemmOutput *direct = nullptr) {
     GemmRecord *r = (g_prof_on && g_prof_used < g_prof.size()) ? &g_prof[g_prof_used++] : nullptr;
     if (r) { r->weight_bytes = N * K * 2; (void)hipEventRecord(r->start, s); }
-    launch_gemm(a_frag, true, M, K, w, N, out, ldo, p, s);
+    launch_gemm(a_frag, true, M, K, w, N, out, ldo, p, s, direct);
     if (r) (void)hipEventRecord(r->stop, s);
 }
 
@@ -352,15 +352,27 @@ extern "C" int bita_verify_step(bita_model *m, const bita_kv *kv, const bita_tre
                               ap, part_o, part_ml, attn_out, true, s);
         timed_gemm(attn_out, M, nq, m->wo[l], d, partial, d, p_o, s);
         launch_rmsnorm_prep(x, partial, p_o.splits, M, d, m->ffn_norm[l], h, ssq, s);
-        timed_gemm(h, M, d, m->w_gate_up[l], 2 * (int64_t)c.d_ffn, partial, 2 * (int64_t)c.d_ffn, p_gu, s);
-        launch_silu_mul(partial, p_gu.splits, M, c.d_ffn, act, rs_norm, s);
+        // with a single split the gate/up GEMM gates in its own epilogue and writes the slab itself
+        if (gemm_direct_output_possible(p_gu, GEMM_OUT_SILU)) {
+            const GemmOutput gated = {GEMM_OUT_SILU, rs_norm, (uint16_t *)act, c.d_ffn};
+            timed_gemm(h, M, d, m->w_gate_up[l], 2 * (int64_t)c.d_ffn, partial, 2 * (int64_t)c.d_ffn, p_gu, s, &gated);
+        } else {
+            timed_gemm(h, M, d, m->w_gate_up[l], 2 * (int64_t)c.d_ffn, partial, 2 * (int64_t)c.d_ffn, p_gu, s);
+            launch_silu_mul(partial, p_gu.splits, M, c.d_ffn, act, rs_norm, s);
+        }
         timed_gemm(act, M, c.d_ffn, m->w_down[l], d, partial, d, p_dn, s);
         pending = p_dn.splits;
     }
     launch_rmsnorm_prep(x, partial, pending, M, d, m->final_norm, h, ssq, s);
-    // the LM head always goes through the reduce kernel: it applies the final norm's row factor
-    timed_gemm(h, M, d, m->lm_head, c.vocab, partial, c.vocab, p_lm, s);
-    launch_reduce_partials(partial, p_lm.splits, M, c.vocab, c.vocab, logits, rs_norm, s);
+    // the final norm's row factor: in the LM head's own epilogue when it runs as a single split,
+    // else in the reduction of its partial sums
+    if (gemm_direct_output_possible(p_lm, GEMM_OUT_SCALED)) {
+        const GemmOutput scaled = {GEMM_OUT_SCALED, rs_norm, nullptr, 0};
+        timed_gemm(h, M, d, m->lm_head, c.vocab, logits, c.vocab, p_lm, s, &scaled);
+    } else {
+        timed_gemm(h, M, d, m->lm_head, c.vocab, partial, c.vocab, p_lm, s);
+        launch_reduce_partials(partial, p_lm.splits, M, c.vocab, c.vocab, logits, rs_norm, s);
+    }
     launch_select(logits, batch, td, c.vocab, kmax, d_argmax, n_sel_mask > 0 ? d_topk_ids : nullptr, d_topk_val, s);
     BITA_HIP_CHECK(hipGetLastError());
     return BITA_OK;

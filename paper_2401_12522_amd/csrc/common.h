@@ -70,12 +70,20 @@ __device__ __forceinline__ float row_scale(const RowScale &rs, int m) {
     return 1.0f / sqrtf(tot * rs.inv_d + rs.eps);
 }
 struct GemmPlan { int splits, ksteps_per_split, variant; };
+// What a GEMM launch with a single split (complete sums in its accumulators) may do instead of
+// storing fp32 partials: apply the deferred RMSNorm row factor and store the result, or apply it
+// and the SwiGLU gating to its tile-interleaved gate/up columns and store the next GEMM's
+// activation slab (two bf16 planes, fragment order).
+enum { GEMM_OUT_PARTIAL = 0, GEMM_OUT_SCALED = 1, GEMM_OUT_SILU = 2 };
+struct GemmOutput { int kind; RowScale rs; uint16_t *act_frag; int d_ffn; };
+bool gemm_direct_output_possible(const GemmPlan &p, int kind);
 void gemm_force_plan(int variant, int splits);   // tuning aid: < 0 restores the heuristic
 GemmPlan gemm_plan(int m_rows, int64_t n_rows, int64_t k);
 size_t frag_bytes(int m_rows, int64_t k);        // bytes of a two-plane activation slab
 // a_frag: activations in fragment order (see frag_index); out_partial: [splits][m_rows][ldo] fp32
 void launch_gemm(const void *a_frag, bool two_planes, int m_rows, int64_t k, const void *w_packed,
-                 int64_t n_rows, float *out_partial, int64_t ldo, const GemmPlan &p, hipStream_t s);
+                 int64_t n_rows, float *out_partial, int64_t ldo, const GemmPlan &p, hipStream_t s,
+                 const GemmOutput *direct = nullptr);
 void launch_to_fragments(const void *a_hi, const void *a_lo, int m_rows, int64_t k, int64_t lda, void *dst,
                          hipStream_t s);
 void launch_reduce_partials(const float *partial, int splits, int m_rows, int64_t n, int64_t ld,

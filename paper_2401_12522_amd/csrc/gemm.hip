@@ -27,6 +27,7 @@
 //    from split-K with fp32 partial sums reduced in a fixed order by the consumer
 //    (deterministic, no float atomics).
 #include "common.h"
+#include <string.h>
 #include <type_traits>
 
 __device__ uint4 g_zero16 = {0u, 0u, 0u, 0u};   // source for out-of-range A granules
@@ -79,15 +80,16 @@ struct GemmCfg {
     // those beyond NFRAG land in one shared dump slot after the ring
     static constexpr int RING = KG * D * NFRAG * 1024;          // one ring per k group
     static constexpr int MERGE = KG > 1 ? WN * MT * NW * 1024 : 0;   // accumulators of one k group
-    static constexpr int SMEM = (RING > MERGE ? RING : MERGE) + 1024;
+    static constexpr int STAGE = NW % 2 == 0 ? 2 * (WN * NW * 8 / 32) * MT * 1024 : 0;   // gated output slab of the workgroup
+    static constexpr int SMEM = (RING > MERGE ? (RING > STAGE ? RING : STAGE) : (MERGE > STAGE ? MERGE : STAGE)) + 1024;
     static_assert((D - 2) * LOADS < 64, "vmcnt counter range");
 };
 
-template <int MT, int NW, bool SPLIT, int KC, int D, int WAVES, int KG>
+template <int MT, int NW, bool SPLIT, int KC, int D, int WAVES, int KG, bool DIRECT>
 __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
     const uint4 *__restrict__ A_frag, int planes_stride_f, int M, int m_tiles,
     const uint4 *__restrict__ Wp, int NT, int KS, float *__restrict__ out, int64_t ldo,
-    int ksteps_per_split) {
+    int ksteps_per_split, GemmOutput direct) {
     using C = GemmCfg<MT, NW, SPLIT, KC, D, WAVES, KG>;
     constexpr int WN = C::WN;
     extern __shared__ __attribute__((aligned(16))) uint4 smem_u4[];   // [KG][D][NFRAG][64] + dump slot
@@ -223,6 +225,74 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
     }
     // D layout: lane (g = lane/16, c = lane%16) holds rows 4g..4g+3, column c of each tile.
     const int g = lane >> 4, cc = lane & 15;
+    if (DIRECT && direct.kind != GEMM_OUT_PARTIAL) {
+        // single split: the sums are complete.  The row factors of the block's rows are computed
+        // once per workgroup (one thread per row) and handed out through LDS.
+        float *scale_lds = reinterpret_cast<float *>(smem_u4 + (C::SMEM - 1024) / 16);   // the dump slot
+        if constexpr (KG == 1) wait_vmcnt_lds<0>();          // (KG > 1: done before the merge)
+        __syncthreads();
+        if (tid < MT * 16) scale_lds[tid] = (m_base + tid < M) ? row_scale(direct.rs, m_base + tid) : 0.f;
+        __syncthreads();
+        float sc[MT][4];
+#pragma unroll
+        for (int i = 0; i < MT; i++)
+#pragma unroll
+            for (int r = 0; r < 4; r++) sc[i][r] = scale_lds[i * 16 + 4 * g + r];
+        if (direct.kind == GEMM_OUT_SCALED) {
+#pragma unroll
+            for (int j = 0; j < NW; j++) {
+                const int t = t0 + j;
+                if (t >= NT) continue;
+#pragma unroll
+                for (int i = 0; i < MT; i++)
+#pragma unroll
+                    for (int r = 0; r < 4; r++) {
+                        const int m = m_base + i * 16 + 4 * g + r;
+                        if (m < M) out[(int64_t)m * ldo + t * 16 + cc] = acc[i][j][r] * sc[i][r];
+                    }
+            }
+        } else if constexpr (NW % 2 == 0) {
+            // Tiles alternate gate, up: accumulators (j, j+1) hold gate and up of the same 16
+            // features for the same rows and lanes.  The workgroup's WN*NW*8 features are whole
+            // k-steps of the next GEMM: the gated values are laid out as its fragments in LDS
+            // (two planes) and leave as whole 1 KiB fragments, 16 bytes per lane.
+            constexpr int FEATS = WN * NW * 8, KSL = FEATS / 32;          // features, k-steps per workgroup
+            static_assert(FEATS % 32 == 0, "whole k-steps");
+            static_assert(2 * KSL * MT * 1024 <= C::SMEM, "staging fits the ring");
+            const int F = direct.d_ffn, n_ksteps = (F + 31) >> 5, mt_all = (M + 15) >> 4;
+            uint16_t *stage = reinterpret_cast<uint16_t *>(smem_u4);     // [plane][KSL][MT][512]
+            // (every wave is past the ring and the merge area: synchronised above)
+#pragma unroll
+            for (int j = 0; j < NW; j += 2) {
+                const int f_local = (wn * NW + j) * 8 + cc;              // feature inside the workgroup
+                const int ksl = f_local >> 5, pos = ((f_local >> 3) & 3) * 128 + (f_local & 7);
+                const bool live = (t0 + j) < NT;
+#pragma unroll
+                for (int i = 0; i < MT; i++)
+#pragma unroll
+                    for (int r = 0; r < 4; r++) {
+                        const float gs = acc[i][j][r] * sc[i][r];
+                        const float v = live ? gs / (1.0f + expf(-gs)) * (acc[i][j + 1][r] * sc[i][r]) : 0.f;
+                        uint16_t hi, lo;
+                        split_bf16(v, hi, lo);
+                        const int at = pos + (4 * g + r) * 8;            // row 4g+r of m-tile i
+                        stage[((0 * KSL + ksl) * MT + i) * 512 + at] = hi;
+                        stage[((1 * KSL + ksl) * MT + i) * 512 + at] = lo;
+                    }
+            }
+            __syncthreads();
+            // fragment (plane, ks, mt) of the slab starts at ((plane * n_ksteps + ks) * mt_all + mt) KiB;
+            // k-steps at or beyond n_ksteps and m-tiles beyond the slab do not exist
+            const int ks0 = blockIdx.x * KSL, mt0 = blockIdx.z * MT;
+            for (int fr = wn; fr < 2 * KSL * MT; fr += WN) {
+                const int plane = fr / (KSL * MT), ksl = (fr / MT) % KSL, i = fr % MT;
+                if (ks0 + ksl >= n_ksteps || mt0 + i >= mt_all) continue;
+                const uint4 v = reinterpret_cast<const uint4 *>(stage)[fr * 64 + lane];
+                reinterpret_cast<uint4 *>(direct.act_frag)[(((int64_t)plane * n_ksteps + ks0 + ksl) * mt_all + mt0 + i) * 64 + lane] = v;
+            }
+        }
+        return;
+    }
     float *o = out + (int64_t)blockIdx.y * M * ldo;
 #pragma unroll
     for (int j = 0; j < NW; j++) {
@@ -290,7 +360,8 @@ GemmPlan gemm_plan(int m_rows, int64_t n_rows, int64_t k) {
     GemmPlan p;
     const int64_t NT = n_rows / 16, KS = (k + 31) / 32;
     // Shapes measured on MI355X at 68 rows (7B- and 70B-like widths): 8 waves as 2 k groups x 4,
-    // 2 tiles per wave (128 columns per workgroup), 4 tiles for the widest matrices; as many
+    // 2 tiles per wave (128 columns per workgroup), 4 tiles for the widest matrices; 4 waves x 4
+    // tiles with more splits in the 16k-28k column range (the 7B-shaped gate/up); as many
     // splits as give one round of 256 equal workgroups, but no more than 8 for the narrow ones,
     // whose partial sums are re-read by a row-wise consumer.
     p.variant = NT < 3000 ? 8 : 6;
@@ -312,46 +383,60 @@ GemmPlan gemm_plan(int m_rows, int64_t n_rows, int64_t k) {
     return p;
 }
 
-template <int MT, int NW, bool SPLIT, int WAVES, int D, int KG>
+template <int MT, int NW, bool SPLIT, int WAVES, int D, int KG, bool DIRECT>
 static void launch_gemm_t(const void *a_frag, int M, int64_t K, const void *w, int64_t N, float *out, int64_t ldo,
-                          const GemmPlan &p, hipStream_t s) {
+                          const GemmPlan &p, hipStream_t s, const GemmOutput &direct) {
     constexpr int KC = 1;
     using C = GemmCfg<MT, NW, SPLIT, KC, D, WAVES, KG>;
     static bool attr_set = false;
     if (!attr_set) {
-        (void)hipFuncSetAttribute((const void *)gemm_skinny_kernel<MT, NW, SPLIT, KC, D, WAVES, KG>,
+        (void)hipFuncSetAttribute((const void *)gemm_skinny_kernel<MT, NW, SPLIT, KC, D, WAVES, KG, DIRECT>,
                                   hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM);
         attr_set = true;
     }
     const int NT = (int)(N / 16), KS = (int)((K + 31) / 32), m_tiles = (M + 15) / 16;
     dim3 grid((NT + C::WN * NW - 1) / (C::WN * NW), p.splits, (m_tiles + MT - 1) / MT);
-    hipLaunchKernelGGL((gemm_skinny_kernel<MT, NW, SPLIT, KC, D, WAVES, KG>), grid, dim3(WAVES * 64), C::SMEM, s,
+    hipLaunchKernelGGL((gemm_skinny_kernel<MT, NW, SPLIT, KC, D, WAVES, KG, DIRECT>), grid, dim3(WAVES * 64), C::SMEM, s,
                        (const uint4 *)a_frag, KS * m_tiles, M, m_tiles, (const uint4 *)w, NT, KS, out, ldo,
-                       p.ksteps_per_split);
+                       p.ksteps_per_split, direct);
 }
 
 template <int MT, bool SPLIT>
 static void launch_gemm_v(const void *a_frag, int M, int64_t K, const void *w, int64_t N, float *out, int64_t ldo,
-                          const GemmPlan &p, hipStream_t s) {
-#define V(i, nw, waves, d, kg) case i: launch_gemm_t<MT, nw, SPLIT, waves, d, kg>(a_frag, M, K, w, N, out, ldo, p, s); break;
+                          const GemmPlan &p, hipStream_t s, const GemmOutput &direct) {
+    // the instantiations with an output epilogue exist for the k-group shapes only
+#define V(i, nw, waves, d, kg) case i: launch_gemm_t<MT, nw, SPLIT, waves, d, kg, false>(a_frag, M, K, w, N, out, ldo, p, s, direct); break;
+#define W(i, nw, waves, d, kg) case i: \
+        if (direct.kind != GEMM_OUT_PARTIAL) launch_gemm_t<MT, nw, SPLIT, waves, d, kg, true>(a_frag, M, K, w, N, out, ldo, p, s, direct); \
+        else launch_gemm_t<MT, nw, SPLIT, waves, d, kg, false>(a_frag, M, K, w, N, out, ldo, p, s, direct); \
+        break;
     switch (p.variant) {
         V(0, 1, 4, 4, 1) V(1, 2, 4, 4, 1) V(2, 4, 4, 4, 1) V(3, 2, 8, 6, 1) V(4, 4, 8, 6, 1)
-        V(5, 2, 8, 4, 2) V(6, 4, 8, 4, 2) V(7, 1, 8, 4, 2) V(8, 2, 8, 3, 2)
+        W(5, 2, 8, 4, 2) W(6, 4, 8, 4, 2) V(7, 1, 8, 4, 2) W(8, 2, 8, 3, 2)
     }
 #undef V
+#undef W
 }
 
 // a_frag: activations in fragment order, [planes][k-steps][m-tiles][64] x 16 bytes;
 // out_partial: [splits][M][ldo] fp32.
 void launch_gemm(const void *a_frag, bool two_planes, int M, int64_t K, const void *w, int64_t N,
-                 float *out, int64_t ldo, const GemmPlan &p, hipStream_t s) {
+                 float *out, int64_t ldo, const GemmPlan &p, hipStream_t s, const GemmOutput *directp) {
+    GemmOutput direct;
+    memset(&direct, 0, sizeof(direct));
+    // direct outputs need complete sums and, for the gating, gate/up tile pairs inside one wave
+    if (directp && gemm_direct_output_possible(p, directp->kind)) direct = *directp;
     if (M <= 16) {
-        if (two_planes) launch_gemm_v<1, true>(a_frag, M, K, w, N, out, ldo, p, s);
-        else launch_gemm_v<1, false>(a_frag, M, K, w, N, out, ldo, p, s);
+        if (two_planes) launch_gemm_v<1, true>(a_frag, M, K, w, N, out, ldo, p, s, direct);
+        else launch_gemm_v<1, false>(a_frag, M, K, w, N, out, ldo, p, s, direct);
     } else {
-        if (two_planes) launch_gemm_v<5, true>(a_frag, M, K, w, N, out, ldo, p, s);
-        else launch_gemm_v<5, false>(a_frag, M, K, w, N, out, ldo, p, s);
+        if (two_planes) launch_gemm_v<5, true>(a_frag, M, K, w, N, out, ldo, p, s, direct);
+        else launch_gemm_v<5, false>(a_frag, M, K, w, N, out, ldo, p, s, direct);
     }
+}
+bool gemm_direct_output_possible(const GemmPlan &p, int kind) {
+    (void)kind;
+    return p.splits == 1 && (p.variant == 5 || p.variant == 6 || p.variant == 8);   // even tiles per wave, see launch_gemm_v
 }
 
 size_t frag_bytes(int m_rows, int64_t k) {                     // two planes
