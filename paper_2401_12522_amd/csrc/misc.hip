@@ -176,32 +176,40 @@ __global__ void silu_mul_kernel(const float *__restrict__ partial, int splits, i
 // Selection over the vocabulary.  Order: value descending, lower id first among equals.
 // One workgroup per selected row; pass p finds the best entry that comes strictly after
 // the previous winner in that order, so k passes give the sorted top-k and pass 0 alone
-// is the greedy argmax.  Reductions: per-lane scan, wave shuffles, then 4 waves via LDS.
+// is the greedy argmax.  Reductions: per-lane scan (16-byte loads), wave shuffles, then the
+// workgroup's 16 waves via LDS.
 struct Cand { float v; int i; };
 __device__ __forceinline__ bool better(float v, int i, float bv, int bi) {
     return v > bv || (v == bv && i < bi);
 }
-__global__ __launch_bounds__(256) void select_kernel(const float *__restrict__ logits, TemplateDev t,
-                                                     int vocab, int kmax, int32_t *__restrict__ argmax,
-                                                     int32_t *__restrict__ topk_ids,
-                                                     float *__restrict__ topk_val) {
-    __shared__ float sv[4];
-    __shared__ int si[4];
+#define SELECT_THREADS 1024
+__global__ __launch_bounds__(SELECT_THREADS) void select_kernel(const float *__restrict__ logits, TemplateDev t,
+                                                                int vocab, int kmax, int32_t *__restrict__ argmax,
+                                                                int32_t *__restrict__ topk_ids,
+                                                                float *__restrict__ topk_val) {
+    constexpr int NW = SELECT_THREADS / 64;
+    __shared__ float sv[NW];
+    __shared__ int si[NW];
     const int b = blockIdx.y;
     const int sel = blockIdx.x;                       // 0..T-1 tree rows, then G*n mask rows
     const bool is_tree = sel < t.n_tree;
     const int r = is_tree ? sel : t.mask_rows[sel - t.n_tree];
     const int k = is_tree ? 1 : kmax;
-    const float *row = logits + ((int64_t)b * t.rows + r) * vocab;
+    const float4 *row = reinterpret_cast<const float4 *>(logits + ((int64_t)b * t.rows + r) * vocab);   // vocab % 16 == 0
     float prev_v = INFINITY;
     int prev_i = -1;
     for (int p = 0; p < k; p++) {
         float bv = -INFINITY;
         int bi = 0x7FFFFFFF;
-        for (int i = threadIdx.x; i < vocab; i += 256) {
-            const float v = row[i];
-            const bool after_prev = (p == 0) || v < prev_v || (v == prev_v && i > prev_i);
-            if (after_prev && better(v, i, bv, bi)) { bv = v; bi = i; }
+        for (int i4 = threadIdx.x; i4 < (vocab >> 2); i4 += SELECT_THREADS) {
+            const float4 q = row[i4];
+            const float v[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+            for (int e = 0; e < 4; e++) {
+                const int i = 4 * i4 + e;
+                const bool after_prev = (p == 0) || v[e] < prev_v || (v[e] == prev_v && i > prev_i);
+                if (after_prev && better(v[e], i, bv, bi)) { bv = v[e]; bi = i; }
+            }
         }
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) {
@@ -213,7 +221,7 @@ __global__ __launch_bounds__(256) void select_kernel(const float *__restrict__ l
         __syncthreads();
         bv = sv[0]; bi = si[0];
 #pragma unroll
-        for (int w = 1; w < 4; w++)
+        for (int w = 1; w < NW; w++)
             if (better(sv[w], si[w], bv, bi)) { bv = sv[w]; bi = si[w]; }
         __syncthreads();
         prev_v = bv; prev_i = bi;
@@ -259,6 +267,6 @@ void launch_silu_mul(const float *partial, int splits, int M, int F, void *act_f
 void launch_select(const float *logits, int batch, const TemplateDev &t, int vocab, int kmax,
                    int32_t *argmax, int32_t *topk_ids, float *topk_val, hipStream_t s) {
     const int n_sel = t.n_tree + (topk_ids ? t.n_groups * t.n_mask : 0);
-    hipLaunchKernelGGL(select_kernel, dim3(n_sel, batch), dim3(256), 0, s, logits, t, vocab, kmax,
+    hipLaunchKernelGGL(select_kernel, dim3(n_sel, batch), dim3(SELECT_THREADS), 0, s, logits, t, vocab, kmax,
                        argmax, topk_ids, topk_val);
 }

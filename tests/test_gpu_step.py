@@ -183,3 +183,71 @@ def test_autonomous_gpu_loop_reproduces_ar_greedy(bita, mode):
     assert all(1 <= n <= d.tree_depth + 1 for n in lens)
     if mode == "planted" and not low:
         assert max(lens) >= 3
+
+
+def test_batched_steps_with_ragged_contexts_and_accepts(bita):
+    """Batch 3, independent sequences: different context lengths, planted drafts of different
+    depths per sequence and step.  Every sequence's stream equals its own autoregressive greedy
+    stream, its context counter advances by its own accepted lengths, and the committed K/V
+    equal the oracle's causal-pass cache."""
+    base = synth.get_config("tiny_gqa")
+    tin = synth.attach_mask_groups(synth.random_tree(8, 3, 3), [0], base.n_mask)
+    B = 3
+    cfg, w, om, model, tmpl, kv, d = _setup(bita, "tiny_gqa", tin, batch=B)
+    ctx_lens, ctx_seeds = [40, 64, 57], [31, 105, 56]    # seeds whose first 33 greedy tokens have decisive margins
+    steps = 8
+    n_ref = steps * (d.tree_depth + 1) + 1
+    refs, margins, ctxs, Lc0 = [], [], [], []
+    for b in range(B):
+        ctx = synth.random_context(cfg.vocab, ctx_lens[b], ctx_seeds[b])
+        ctxs.append(ctx)
+        ck, cv = oracle.decode.prefill(om, ctx)
+        ref, mar = [], []
+        last = int(ctx[-1])
+        for _ in range(n_ref):
+            lg, k, v = oracle.forward_rows(om, [last], [0], [-1], [ck[0].shape[0]], [[0]], ck, cv)
+            ck, cv = oracle.compact_kv(ck, cv, k, v, [0])
+            last = argmax_low(lg[0])
+            ref.append(last)
+            mar.append(_top2_margin(lg[0]))
+        refs.append(ref)
+        margins.append(mar)
+        st0 = round_state(BitaState(om, ctx))
+        Lc0.append(load_cache(kv, st0.cache_k, st0.cache_v, b=b))
+    buf = bita.StepBuffers(model, tmpl, B, d.kmax)
+    for b in range(B):
+        buf.bonus[b] = int(ctxs[b][-1])
+        buf.next_shift[b] = cfg.n_mask
+    emitted = [[] for _ in range(B)]
+    lens = [[] for _ in range(B)]
+    for t in range(steps):
+        hint = max(Lc0[b] + sum(lens[b]) for b in range(B))
+        cand = np.zeros((B, cfg.n_mask, d.kmax), np.int32)
+        for b in range(B):
+            rng = np.random.default_rng(900 + 10 * t + b)
+            depth_ok = int(rng.integers(0, d.tree_depth + 1))
+            col = rng.integers(0, d.kmax, cfg.n_mask)
+            cand[b] = synth.planted_candidates(refs[b][len(emitted[b]):], cfg.n_mask, d.kmax, depth_ok, col,
+                                               cfg.vocab, 77 + 10 * t + b)
+        bita.decode_step(model, kv, hint, tmpl, buf, B, buf.bonus, dev_i32(cand))
+        torch.cuda.synchronize()
+        for b in range(B):
+            na = int(buf.n_acc[b])
+            lens[b].append(na)
+            emitted[b].extend(buf.emitted[b, :na].cpu().tolist())
+    for b in range(B):
+        low = [i for i in range(len(emitted[b])) if margins[b][i] <= MARGIN]
+        upto = low[0] if low else len(emitted[b])
+        assert upto >= 6, "seed gives an early near-tie; pick another"
+        assert emitted[b][:upto] == refs[b][:upto]
+        assert int(kv.ctx_len[b]) == Lc0[b] + sum(lens[b])
+        assert all(1 <= n <= d.tree_depth + 1 for n in lens[b])
+        if not low:
+            # committed cache == the oracle's cache after feeding the same tokens causally
+            toks = np.concatenate([ctxs[b][:-1], [ctxs[b][-1]], np.array(emitted[b][:-1], dtype=ctxs[b].dtype)])[: int(kv.ctx_len[b])]
+            ck, cv = oracle.decode.prefill(om, np.concatenate([toks, [0]]))
+            gk, gv = read_cache(kv, b=b)
+            for l in range(cfg.n_layers):
+                assert np.abs(gk[l] - ck[l]).max() <= LOGIT_TOL
+                assert np.abs(gv[l] - cv[l]).max() <= LOGIT_TOL
+    assert len({tuple(x) for x in lens}) >= 2, "the sequences should not all accept alike"
