@@ -39,6 +39,9 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--workload", default="7b", choices=["tiny", "7b", "13b", "70b"])
     ap.add_argument("--ctx", type=int, default=None)
+    ap.add_argument("--tree", default=None, choices=sorted(TREES),
+                    help="draft-tree template (default: full64; tiny workload: its seeded 8-node tree); "
+                         "'-pernode' attaches a mask group to every tree node instead of the root only")
     ap.add_argument("--mode", default="planted", choices=["free", "planted"])
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -49,14 +52,37 @@ def parse_args():
     return ap.parse_args()
 
 
-def workload_template(synth, cfg, name):
+# draft-tree templates of the row-count sweep (Sec. 3.3: full trees by per-level top-k, the
+# efficient tree of n*k+1 rows; mask groups on the root only or on every node)
+TREES = {
+    "full64": ("full", [4, 3, 2, 1], 64), "full34": ("full", [3, 2, 2, 1], 34), "full16": ("full", [3, 2, 1, 1], 16),
+    "efficient": ("efficient", 5, None),
+}
+TREES.update({k + "-pernode": v for k, v in list(TREES.items())})
+
+
+def workload_template(synth, cfg, name, tree=None):
     """Draft-tree shape per workload: small case = seeded random 8-node tree; LLaMA shapes =
-    full branching by per-level top-k (4,3,2,1) truncated to 64 rows, one mask group on the root."""
-    if name == "tiny":
+    full branching by per-level top-k (4,3,2,1) truncated to 64 rows, one mask group on the
+    root, unless --tree names another template."""
+    if tree is None and name == "tiny":
         parent = synth.random_tree(8, 3, 0)
     else:
-        parent = synth.full_branching_tree([4, 3, 2, 1], 64)
-    return synth.attach_mask_groups(parent, [0], cfg.n_mask)
+        kind, a, T = TREES[tree or "full64"]
+        parent = synth.full_branching_tree(a, T) if kind == "full" else synth.efficient_tree_parents(cfg.n_mask, a)
+    per_node = tree is not None and tree.endswith("-pernode")
+    return synth.attach_mask_groups(parent, list(range(len(parent))) if per_node else [0], cfg.n_mask)
+
+
+def tree_shape(tin):
+    """children[v] in sibling order (a child's index in it is the candidate column it carries)
+    and the depth of the deepest draft row."""
+    children = [[] for _ in range(tin.n_tree)]
+    depth = [0] * tin.n_tree
+    for v in range(1, tin.n_tree):
+        children[int(tin.parent[v])].append(v)
+        depth[v] = depth[int(tin.parent[v])] + 1
+    return children, max(depth)
 
 
 def prefill(B, model, kv, cfg, ctx_tokens, chunk=64):
@@ -135,10 +161,10 @@ def main():
         del src_t, dst_t
     cfg = synth.get_config(args.workload)
     ctx_n = args.ctx or {"tiny": 64, "7b": 1024, "13b": 2048, "70b": 2048}[args.workload]
-    tin = workload_template(synth, cfg, args.workload)
+    tin = workload_template(synth, cfg, args.workload, args.tree)
     steps, warmup = args.steps, args.warmup
     R = tin.rows
-    depth_max = 4 if args.workload != "tiny" else 3
+    children, depth_max = tree_shape(tin)
     total_steps = warmup + steps
     smax = ctx_n + (total_steps + 2) * (depth_max + 1) + 64
     smax = (smax + 63) // 64 * 64
@@ -211,7 +237,7 @@ def main():
     # two summation orders), the reference is regenerated from the current state.  The kernels
     # are deterministic, so the timed run, replaying the recorded candidate tables from the
     # same initial state, follows the dry run exactly.
-    cand_all, plan_acc, resyncs, dry_emitted = None, [], 0, None
+    cand_all, plan_acc, resyncs, dry_emitted, ar_ms_per_token = None, [], 0, None, None
     if args.mode == "planted":
         t1 = synth.attach_mask_groups(np.array([-1], np.int32), [], cfg.n_mask)
         tm1 = B.TreeTemplate(t1.parent, t1.is_mask, 1, cfg.n_mask)
@@ -239,7 +265,6 @@ def main():
             torch.cuda.synchronize()
             return out_toks.cpu().tolist()
 
-        ks = [4, 3, 2, 1] if args.workload != "tiny" else [1, 1, 1, 1]
         reset_state()
         tabs, dry_emitted = [], []
         ref, pos = reference_from_current((depth_max + 1) * 8), 0
@@ -248,8 +273,13 @@ def main():
                 ref, pos = reference_from_current((depth_max + 1) * 8), 0
             rng = np.random.default_rng(1000 + t)
             depth_ok = int(rng.integers(0, depth_max + 1))
-            col = np.array([int(rng.integers(0, ks[i])) for i in range(cfg.n_mask)])
-            col[-1] = 0        # the 64-row truncation drops the last node of the deepest level
+            col, v = np.zeros(cfg.n_mask, int), 0    # a seeded root-to-node walk of the template
+            for i in range(depth_ok):
+                if not children[v]:
+                    depth_ok = i
+                    break
+                col[i] = int(rng.integers(0, len(children[v])))
+                v = children[v][col[i]]
             tab = synth.planted_candidates(ref[pos:], cfg.n_mask, kmax, depth_ok, col, cfg.vocab, 50 + t)
             tabs.append(tab)
             cand_buf.copy_(torch.tensor(tab[None], dtype=torch.int32))
@@ -265,6 +295,17 @@ def main():
                 resyncs += 1
                 ref, pos = reference_from_current((depth_max + 1) * 8), 0
         cand_all = torch.tensor(np.stack(tabs)[:, None], dtype=torch.int32, device="cuda")
+        # the one-row greedy pass (plain autoregressive decoding with the same kernels), timed
+        # beside the tree step: the paper's speedup is (this) x (tokens per step) / (step time)
+        n_ar = 32
+        reference_from_current(4)
+        e_a, e_b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e_a.record()
+        for _ in range(n_ar):
+            g1.replay()
+        e_b.record()
+        torch.cuda.synchronize()
+        ar_ms_per_token = e_a.elapsed_time(e_b) / n_ar
         del kv_ref
     reset_state()
 
@@ -325,12 +366,15 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": f"llama2-{args.workload}-shaped random-init, ctx {ctx_n}, batch 1, "
-                               f"{tin.n_tree}-node tree + {cfg.n_mask} mask rows, P={cfg.n_prompt}, mode {args.mode}",
+                               f"{tin.n_tree}-node tree ({args.tree or 'default'}) + {R - tin.n_tree} mask rows, P={cfg.n_prompt}, mode {args.mode}",
                    "rows": R, "graph": graph is not None},
         "hbm_gbps": gbps, "hbm_frac_of_peak": gbps / HBM_PEAK_GBPS, "bytes_per_step": bytes_per_step,
         "gpu_ms_per_step": gpu_ms / steps, "mean_accepted": float(np.mean(nacc[warmup:])),
         "generated_tokens_per_s": float(np.sum(nacc[warmup:])) / wall,
         "planted_resyncs": resyncs if args.mode == "planted" else None,
+        "one_row_pass_ms": ar_ms_per_token,
+        "speedup_over_one_row_passes": (ar_ms_per_token * float(np.mean(nacc[warmup:])) / ms_per_step
+                                        if ar_ms_per_token else None),
         "timed_run_equals_dry_run": replay_ok,
         "roofline": roofline, "cpu_baseline": None,
     }

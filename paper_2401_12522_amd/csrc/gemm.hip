@@ -365,6 +365,8 @@ GemmPlan gemm_plan(int m_rows, int64_t n_rows, int64_t k) {
     // splits as give one round of 256 equal workgroups, but no more than 8 for the narrow ones,
     // whose partial sums are re-read by a row-wise consumer.
     p.variant = NT < 3000 ? 8 : 6;
+    const int m_tiles = (m_rows + 15) / 16;
+    if (m_tiles == 6 || m_tiles == 7) p.variant = 8;            // one pass: 4 tiles per wave x 7 m-tiles of accumulators would spill
     if (g_force_variant >= 0 && g_force_variant < GEMM_N_VARIANTS) p.variant = g_force_variant;
     const GemmVariant &v = g_variants[p.variant];
     const int tiles_wg = v.nw * v.waves / v.kgroups;
@@ -379,7 +381,6 @@ GemmPlan gemm_plan(int m_rows, int64_t n_rows, int64_t k) {
     const int64_t per = (KS + splits - 1) / splits;
     p.ksteps_per_split = (int)per;
     p.splits = (int)((KS + per - 1) / per);
-    (void)m_rows;
     return p;
 }
 
@@ -418,6 +419,22 @@ static void launch_gemm_v(const void *a_frag, int M, int64_t K, const void *w, i
 #undef W
 }
 
+// two planes, the planner's variants (6 and 8) only; more than 5 m-tiles with variant 8 alone (registers, LDS ring)
+template <int MT>
+static void launch_gemm_k(const void *a_frag, int M, int64_t K, const void *w, int64_t N, float *out, int64_t ldo,
+                          const GemmPlan &p, hipStream_t s, const GemmOutput &direct) {
+    const bool d = direct.kind != GEMM_OUT_PARTIAL;
+    if constexpr (MT <= 5) {
+        if (p.variant == 6) {
+            if (d) launch_gemm_t<MT, 4, true, 8, 4, 2, true>(a_frag, M, K, w, N, out, ldo, p, s, direct);
+            else launch_gemm_t<MT, 4, true, 8, 4, 2, false>(a_frag, M, K, w, N, out, ldo, p, s, direct);
+            return;
+        }
+    }
+    if (d) launch_gemm_t<MT, 2, true, 8, 3, 2, true>(a_frag, M, K, w, N, out, ldo, p, s, direct);
+    else launch_gemm_t<MT, 2, true, 8, 3, 2, false>(a_frag, M, K, w, N, out, ldo, p, s, direct);
+}
+
 // a_frag: activations in fragment order, [planes][k-steps][m-tiles][64] x 16 bytes;
 // out_partial: [splits][M][ldo] fp32.
 void launch_gemm(const void *a_frag, bool two_planes, int M, int64_t K, const void *w, int64_t N,
@@ -426,13 +443,26 @@ void launch_gemm(const void *a_frag, bool two_planes, int M, int64_t K, const vo
     memset(&direct, 0, sizeof(direct));
     // direct outputs need complete sums and, for the gating, gate/up tile pairs inside one wave
     if (directp && gemm_direct_output_possible(p, directp->kind)) direct = *directp;
+    const int m_tiles = (M + 15) / 16;
     if (M <= 16) {
         if (two_planes) launch_gemm_v<1, true>(a_frag, M, K, w, N, out, ldo, p, s, direct);
         else launch_gemm_v<1, false>(a_frag, M, K, w, N, out, ldo, p, s, direct);
-    } else {
-        if (two_planes) launch_gemm_v<5, true>(a_frag, M, K, w, N, out, ldo, p, s, direct);
-        else launch_gemm_v<5, false>(a_frag, M, K, w, N, out, ldo, p, s, direct);
+        return;
     }
+    // Row counts other than the 65..80 of the 64-node tree (Sec. 3.3: 16 or 21 tree rows for
+    // the efficient tree, 105 rows with a mask group behind each of its nodes): one pass over
+    // the weights with 2, 3 or 7 m-tiles, for the planner's two variants.  Beyond 7 m-tiles
+    // the weight stream no longer bounds the kernel, and passes of 5 m-tiles (grid z)
+    // measured as fast as fewer passes of 7 or 10.
+    const bool planner_variant = p.variant == 6 || p.variant == 8;
+    if (two_planes && planner_variant && (m_tiles <= 3 || (m_tiles >= 6 && m_tiles <= 7 && p.variant == 8))) {
+        if (m_tiles == 2) launch_gemm_k<2>(a_frag, M, K, w, N, out, ldo, p, s, direct);
+        else if (m_tiles == 3) launch_gemm_k<3>(a_frag, M, K, w, N, out, ldo, p, s, direct);
+        else launch_gemm_k<7>(a_frag, M, K, w, N, out, ldo, p, s, direct);
+        return;
+    }
+    if (two_planes) launch_gemm_v<5, true>(a_frag, M, K, w, N, out, ldo, p, s, direct);
+    else launch_gemm_v<5, false>(a_frag, M, K, w, N, out, ldo, p, s, direct);
 }
 bool gemm_direct_output_possible(const GemmPlan &p, int kind) {
     (void)kind;

@@ -16,10 +16,15 @@ LOGIT_TOL = 3e-2
 MARGIN = 6e-2
 
 
-@pytest.mark.parametrize("name,n_layers,ctx_n", [("7b", 2, 150), ("70b", 1, 140), ("13b", 1, 100), ("7b", 32, 40)])
-def test_full_width_step(name, n_layers, ctx_n):
+@pytest.mark.parametrize("name,n_layers,ctx_n,topology", [
+    ("7b", 2, 150, "root"), ("70b", 1, 140, "root"), ("13b", 1, 100, "root"), ("7b", 32, 40, "root"),
+    ("7b", 2, 90, "efficient_per_node"), ("7b", 1, 70, "full_per_node")])
+def test_full_width_step(name, n_layers, ctx_n, topology):
     """Reduced depth for the wide shapes; the 7B shape also at its full depth of 32 layers
-    (one step, short context: the oracle's cost is dominated by the 0.9 TFLOP of matmuls)."""
+    (one step, short context: the oracle's cost is dominated by the 0.9 TFLOP of matmuls).
+    The per-node topologies (Sec. 3.3: a mask group behind every draft node) have 105 rows
+    (efficient tree, n=4, k=5) and 320 rows (64-node full tree): several row slices per GEMM,
+    multi-word ancestor sets."""
     import paper_2401_12522_amd as bita
     cfg = synth.get_config(name, n_layers=n_layers)
     w = synth.SynthWeights(cfg, seed=1, device="cuda")
@@ -31,7 +36,13 @@ def test_full_width_step(name, n_layers, ctx_n):
         for n in synth.weights.LAYER_TENSORS:
             wc._store[(n, l)] = w.torch(n, l).cpu()
     om = oracle.OracleModel(cfg, wc, cache_layers=(n_layers <= 2))
-    tin = synth.attach_mask_groups(synth.full_branching_tree([4, 3, 2, 1], 64), [0], cfg.n_mask)
+    if topology == "root":
+        tin = synth.attach_mask_groups(synth.full_branching_tree([4, 3, 2, 1], 64), [0], cfg.n_mask)
+    elif topology == "efficient_per_node":
+        par = synth.efficient_tree_parents(cfg.n_mask, 5)
+        tin = synth.attach_mask_groups(par, list(range(len(par))), cfg.n_mask)
+    else:
+        tin = synth.attach_mask_groups(synth.full_branching_tree([4, 3, 2, 1], 64), list(range(64)), cfg.n_mask)
     d = derive_template(tin.parent, tin.is_mask, cfg.n_mask)
     smax = 256
     model = bita.Model(cfg, w, max_pos=smax + 64)
