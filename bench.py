@@ -39,6 +39,9 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--workload", default="7b", choices=["tiny", "7b", "13b", "70b"])
     ap.add_argument("--ctx", type=int, default=None)
+    ap.add_argument("--batch", type=int, default=1,
+                    help="sequences per step (independent contexts, same template); above 1 the run is "
+                         "free-running: planted drafts need the one-sequence planning pass")
     ap.add_argument("--tree", default=None, choices=sorted(TREES),
                     help="draft-tree template (default: full64; tiny workload: its seeded 8-node tree); "
                          "'-pernode' attaches a mask group to every tree node instead of the root only")
@@ -86,22 +89,25 @@ def tree_shape(tin):
 
 
 def prefill(B, model, kv, cfg, ctx_tokens, chunk=64):
-    """Fill the cache with context[:-1] by chain-template passes (a chain is causal attention)."""
+    """Fill the cache with context[:-1] by chain-template passes (a chain is causal attention).
+    ctx_tokens: [n] or [batch][n] (equal lengths)."""
     import torch
     import synth
-    n = len(ctx_tokens) - 1
+    ctx_tokens = np.atleast_2d(np.asarray(ctx_tokens))
+    nb = ctx_tokens.shape[0]
+    n = ctx_tokens.shape[1] - 1
     done = 0
     while done < n:
         m = min(chunk, n - done)
         tin = synth.attach_mask_groups(synth.chain_tree(m), [], cfg.n_mask)
         tmpl = B.TreeTemplate(tin.parent, tin.is_mask, m, cfg.n_mask)
         kv.resize_rows(model.n_layers, cfg, m)
-        buf = B.StepBuffers(model, tmpl, 1, 1)
-        buf.token[0] = torch.tensor(ctx_tokens[done:done + m], dtype=torch.int32, device="cuda")
-        B.verify_step(model, kv, done, tmpl, buf, 1)
-        path = torch.arange(m, dtype=torch.int32, device="cuda")[None]
-        n_acc = torch.tensor([m], dtype=torch.int32, device="cuda")
-        B.compact_kv(model, kv, done, buf, 1, path=path, n_acc=n_acc)
+        buf = B.StepBuffers(model, tmpl, nb, 1)
+        buf.token.copy_(torch.tensor(ctx_tokens[:, done:done + m], dtype=torch.int32, device="cuda"))
+        B.verify_step(model, kv, done, tmpl, buf, nb)
+        path = torch.arange(m, dtype=torch.int32, device="cuda")[None].repeat(nb, 1).contiguous()
+        n_acc = torch.full((nb,), m, dtype=torch.int32, device="cuda")
+        B.compact_kv(model, kv, done, buf, nb, path=path, n_acc=n_acc)
         torch.cuda.synchronize()
         done += m
 
@@ -160,6 +166,12 @@ def main():
         torch.cuda.synchronize()
         del src_t, dst_t
     cfg = synth.get_config(args.workload)
+    NB = args.batch
+    if NB < 1:
+        sys.exit("bench.py: --batch must be at least 1")
+    if NB > 1 and args.mode == "planted":
+        print("bench.py: --batch above 1 runs free (no planted drafts)", file=sys.stderr)
+        args.mode = "free"
     ctx_n = args.ctx or {"tiny": 64, "7b": 1024, "13b": 2048, "70b": 2048}[args.workload]
     tin = workload_template(synth, cfg, args.workload, args.tree)
     steps, warmup = args.steps, args.warmup
@@ -182,25 +194,27 @@ def main():
             wsrc_np[(n, None)] = w.numpy(n)
     model = bita.Model(cfg, w, max_pos=smax + 64, free_source=True)
     tmpl = bita.TreeTemplate(tin.parent, tin.is_mask, tin.n_tree, cfg.n_mask)
-    kv = bita.KVState(cfg, cfg.n_layers, 1, smax, R)
-    ctx_tokens = synth.random_context(cfg.vocab, ctx_n, args.seed)
-    prefill(B, model, kv, cfg, ctx_tokens)
+    kv = bita.KVState(cfg, cfg.n_layers, NB, smax, R)
+    ctx_all = np.stack([synth.random_context(cfg.vocab, ctx_n, args.seed + 7919 * b) for b in range(NB)])
+    ctx_tokens = ctx_all[0]
+    prefill(B, model, kv, cfg, ctx_all)
     kv.resize_rows(cfg.n_layers, cfg, R)
     ctx0 = int(kv.ctx_len[0])
-    assert ctx0 == ctx_n - 1
+    assert ctx0 == ctx_n - 1 and bool((kv.ctx_len == ctx0).all())
     k_snap, v_snap = kv.k_cache.clone(), kv.v_cache.clone()
 
     kmax = tmpl.kmax
-    buf = bita.StepBuffers(model, tmpl, 1, kmax)
+    buf = bita.StepBuffers(model, tmpl, NB, kmax)
+    last_tokens = torch.tensor(ctx_all[:, -1].astype(np.int32), device="cuda")
     hint = ctx0 + (total_steps + 1) * (depth_max + 1)
 
     def reset_state():
         kv.k_cache.copy_(k_snap)
         kv.v_cache.copy_(v_snap)
-        kv.ctx_len[0] = ctx0
-        buf.bonus[0] = int(ctx_tokens[-1])
-        buf.next_group[0] = 0
-        buf.next_shift[0] = cfg.n_mask          # first pass: no candidates, all drafts inactive
+        kv.ctx_len.fill_(ctx0)
+        buf.bonus.copy_(last_tokens)
+        buf.next_group.zero_()
+        buf.next_shift.fill_(cfg.n_mask)        # first pass: no candidates, all drafts inactive
         buf.topk_ids.zero_()
 
     cand_buf = torch.zeros((1, cfg.n_mask, kmax), dtype=torch.int32, device="cuda")
@@ -209,7 +223,7 @@ def main():
         if args.mode == "planted":
             B.decode_step(model, kv, hint, tmpl, buf, 1, buf.bonus, cand_buf)
         else:
-            B.decode_step(model, kv, hint, tmpl, buf, 1, buf.bonus, buf.topk_ids, buf.next_group, buf.next_shift)
+            B.decode_step(model, kv, hint, tmpl, buf, NB, buf.bonus, buf.topk_ids, buf.next_group, buf.next_shift)
 
     reset_state()
     one_step()                                   # eager once (sets kernel attributes)
@@ -309,20 +323,20 @@ def main():
         del kv_ref
     reset_state()
 
-    emitted_log = torch.zeros((total_steps, depth_max + 1), dtype=torch.int32, device="cuda")
-    nacc_log = torch.zeros(total_steps, dtype=torch.int32, device="cuda")
+    emitted_log = torch.zeros((total_steps, NB, depth_max + 1), dtype=torch.int32, device="cuda")
+    nacc_log = torch.zeros((total_steps, NB), dtype=torch.int32, device="cuda")
 
     def run(t):
         if args.mode == "planted":
             cand_buf.copy_(cand_all[t])
         launch_step()
-        emitted_log[t].copy_(buf.emitted[0])
-        nacc_log[t:t + 1].copy_(buf.n_acc)
+        emitted_log[t].copy_(buf.emitted)
+        nacc_log[t].copy_(buf.n_acc)
 
     for t in range(warmup):
         run(t)
     torch.cuda.synchronize()
-    ctx_start = int(kv.ctx_len[0])
+    ctx_start = kv.ctx_len.cpu().numpy().astype(np.int64)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
     e0.record()
@@ -338,9 +352,10 @@ def main():
     em = emitted_log.cpu().numpy()
     replay_ok = None
     if args.mode == "planted":
-        replay_ok = all(em[t, : nacc[t]].tolist() == dry_emitted[t] for t in range(total_steps))
-    ctx_lens = ctx_start + np.concatenate([[0], np.cumsum(nacc[warmup:])[:-1]])
-    kv_bytes = float(np.mean([cfg.kv_bytes([int(c)]) for c in ctx_lens]))
+        replay_ok = all(em[t, 0, : nacc[t, 0]].tolist() == dry_emitted[t] for t in range(total_steps))
+    grown = np.concatenate([np.zeros((1, NB), np.int64), np.cumsum(nacc[warmup:], axis=0)[:-1]])
+    ctx_lens = ctx_start[None, :] + grown                      # [steps][batch] context length seen by each step
+    kv_bytes = float(np.mean([cfg.kv_bytes([int(c) for c in row]) for row in ctx_lens]))
     bytes_per_step = cfg.weight_bytes() + kv_bytes
     gbps = bytes_per_step / (ms_per_step * 1e-3) / 1e9
 
@@ -361,13 +376,13 @@ def main():
                 "gemm_ms_per_step": float(np.sum(g_ms)) / prof_steps}
 
     out = {
-        "metric": "tree_verify_scored_tokens_per_s", "value": R * steps / wall, "unit": "tokens/s",
+        "metric": "tree_verify_scored_tokens_per_s", "value": R * NB * steps / wall, "unit": "tokens/s",
         "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": f"llama2-{args.workload}-shaped random-init, ctx {ctx_n}, batch 1, "
+        "config": {"workload": f"llama2-{args.workload}-shaped random-init, ctx {ctx_n}, batch {NB}, "
                                f"{tin.n_tree}-node tree ({args.tree or 'default'}) + {R - tin.n_tree} mask rows, P={cfg.n_prompt}, mode {args.mode}",
-                   "rows": R, "graph": graph is not None},
+                   "rows": R, "batch": NB, "graph": graph is not None},
         "hbm_gbps": gbps, "hbm_frac_of_peak": gbps / HBM_PEAK_GBPS, "bytes_per_step": bytes_per_step,
         "gpu_ms_per_step": gpu_ms / steps, "mean_accepted": float(np.mean(nacc[warmup:])),
         "generated_tokens_per_s": float(np.sum(nacc[warmup:])) / wall,
