@@ -88,6 +88,21 @@ def tree_shape(tin):
     return children, max(depth)
 
 
+def planted_walk(children, depth_max, n_levels, rng):
+    """A seeded root-to-node walk of the template: how many levels of the reference
+    continuation to plant (0..depth_max, cut short at a node without children) and, per level,
+    the candidate column (= sibling index) of the node the walk passes through."""
+    depth_ok = int(rng.integers(0, depth_max + 1))
+    col, v = np.zeros(n_levels, int), 0
+    for i in range(depth_ok):
+        if not children[v]:
+            depth_ok = i
+            break
+        col[i] = int(rng.integers(0, len(children[v])))
+        v = children[v][col[i]]
+    return depth_ok, col
+
+
 def prefill(B, model, kv, cfg, ctx_tokens, chunk=64):
     """Fill the cache with context[:-1] by chain-template passes (a chain is causal attention).
     ctx_tokens: [n] or [batch][n] (equal lengths)."""
@@ -286,14 +301,7 @@ def main():
             if len(ref) - pos < depth_max + 2:
                 ref, pos = reference_from_current((depth_max + 1) * 8), 0
             rng = np.random.default_rng(1000 + t)
-            depth_ok = int(rng.integers(0, depth_max + 1))
-            col, v = np.zeros(cfg.n_mask, int), 0    # a seeded root-to-node walk of the template
-            for i in range(depth_ok):
-                if not children[v]:
-                    depth_ok = i
-                    break
-                col[i] = int(rng.integers(0, len(children[v])))
-                v = children[v][col[i]]
+            depth_ok, col = planted_walk(children, depth_max, cfg.n_mask, rng)
             tab = synth.planted_candidates(ref[pos:], cfg.n_mask, kmax, depth_ok, col, cfg.vocab, 50 + t)
             tabs.append(tab)
             cand_buf.copy_(torch.tensor(tab[None], dtype=torch.int32))

@@ -17,7 +17,7 @@ MARGIN = 6e-2
 
 
 @pytest.mark.parametrize("name,n_layers,ctx_n,topology", [
-    ("7b", 2, 150, "root"), ("70b", 1, 140, "root"), ("13b", 1, 100, "root"), ("7b", 32, 40, "root"),
+    ("7b", 2, 150, "root"), ("70b", 4, 140, "root"), ("13b", 1, 100, "root"), ("7b", 32, 40, "root"),
     ("7b", 2, 90, "efficient_per_node"), ("7b", 1, 70, "full_per_node")])
 def test_full_width_step(name, n_layers, ctx_n, topology):
     """Reduced depth for the wide shapes; the 7B shape also at its full depth of 32 layers
