@@ -546,10 +546,10 @@ AttnPlan attn_plan(int batch, int rows, int n_heads, int hd, int ctx_hint, int n
     const int n_mt = (rows + 15) / 16;
     const int n_chunks = (n_prompt + ctx_hint + ATT_CHUNK - 1) / ATT_CHUNK + n_mt;
     const int wgs = batch * n_heads * n_mt;
-    // No key split while one workgroup's walk stays short (64 chunks = 2048 keys); beyond that,
-    // or when the row tiles alone leave most CUs idle on a long context, split the key axis
-    // (partials + merge kernel) into shares of at least 16 chunks.
-    int splits = (n_chunks + 63) / 64;
+    // No key split while one workgroup's walk stays moderate (256 chunks = 8192 keys, 32 per
+    // wave); beyond that, or when the row tiles alone leave most CUs idle on a long context,
+    // split the key axis (partials + merge kernel) into shares of at least 16 chunks.
+    int splits = (n_chunks + 255) / 256;
     if (wgs * splits < 128) {
         int fill = 256 / wgs;
         if (fill > n_chunks / 16) fill = n_chunks / 16;

@@ -350,7 +350,7 @@ __global__ void to_fragments_kernel(const uint16_t *__restrict__ a_hi, const uin
 struct GemmVariant { int nw, waves, depth, kgroups; };
 static const GemmVariant g_variants[] = {
     {1, 4, 4, 1}, {2, 4, 4, 1}, {4, 4, 4, 1}, {2, 8, 6, 1}, {4, 8, 6, 1},
-    {2, 8, 4, 2}, {4, 8, 4, 2}, {1, 8, 4, 2}, {2, 8, 3, 2},
+    {2, 8, 4, 2}, {4, 8, 4, 2}, {1, 8, 4, 2}, {2, 8, 3, 2}, {2, 16, 3, 2},
 };
 #define GEMM_N_VARIANTS ((int)(sizeof(g_variants) / sizeof(g_variants[0])))
 static int g_force_variant = -1, g_force_splits = -1;
@@ -359,13 +359,17 @@ void gemm_force_plan(int variant, int splits) { g_force_variant = variant; g_for
 GemmPlan gemm_plan(int m_rows, int64_t n_rows, int64_t k) {
     GemmPlan p;
     const int64_t NT = n_rows / 16, KS = (k + 31) / 32;
-    // Shapes measured on MI355X at 68 rows (7B- and 70B-like widths): 8 waves as 2 k groups x 4,
-    // 2 tiles per wave (128 columns per workgroup), 4 tiles for the widest matrices; 4 waves x 4
-    // tiles with more splits in the 16k-28k column range (the 7B-shaped gate/up); as many
+    // Shapes measured on MI355X at 68 rows (7B- and 70B-like widths): 2 k groups of 4 waves
+    // with 2 tiles per wave (128 columns per workgroup) or of 8 waves (256 columns); as many
     // splits as give one round of 256 equal workgroups, but no more than 8 for the narrow ones,
     // whose partial sums are re-read by a row-wise consumer.
-    p.variant = NT < 3000 ? 8 : 6;
     const int m_tiles = (m_rows + 15) / 16;
+    p.variant = NT < 3000 ? 8 : 6;
+    // 16 waves (256 columns per workgroup, half the activation-slab traffic per weight byte)
+    // for the widest matrices, the QKV-like widths and narrow matrices with a very long k;
+    // instantiated for 1 and 5 m-tiles per pass
+    const bool wide16 = NT >= 3000 || (NT >= 512 && NT < 1024 && (NT >= 640 || KS >= 512));
+    if (wide16 && !(m_tiles == 2 || m_tiles == 3 || m_tiles == 6 || m_tiles == 7)) p.variant = 9;
     if (m_tiles == 6 || m_tiles == 7) p.variant = 8;            // one pass: 4 tiles per wave x 7 m-tiles of accumulators would spill
     if (g_force_variant >= 0 && g_force_variant < GEMM_N_VARIANTS) p.variant = g_force_variant;
     const GemmVariant &v = g_variants[p.variant];
@@ -413,7 +417,7 @@ static void launch_gemm_v(const void *a_frag, int M, int64_t K, const void *w, i
         break;
     switch (p.variant) {
         V(0, 1, 4, 4, 1) V(1, 2, 4, 4, 1) V(2, 4, 4, 4, 1) V(3, 2, 8, 6, 1) V(4, 4, 8, 6, 1)
-        W(5, 2, 8, 4, 2) W(6, 4, 8, 4, 2) V(7, 1, 8, 4, 2) W(8, 2, 8, 3, 2)
+        W(5, 2, 8, 4, 2) W(6, 4, 8, 4, 2) V(7, 1, 8, 4, 2) W(8, 2, 8, 3, 2) W(9, 2, 16, 3, 2)
     }
 #undef V
 #undef W
@@ -466,7 +470,7 @@ void launch_gemm(const void *a_frag, bool two_planes, int M, int64_t K, const vo
 }
 bool gemm_direct_output_possible(const GemmPlan &p, int kind) {
     (void)kind;
-    return p.splits == 1 && (p.variant == 5 || p.variant == 6 || p.variant == 8);   // even tiles per wave, see launch_gemm_v
+    return p.splits == 1 && (p.variant == 5 || p.variant == 6 || p.variant == 8 || p.variant == 9);   // even tiles per wave, see launch_gemm_v
 }
 
 size_t frag_bytes(int m_rows, int64_t k) {                     // two planes
