@@ -128,7 +128,7 @@ __device__ __forceinline__ void lds_wait_all(u32x4 (&k)[2][N], s16x4 (&v)[M][2])
     }
 }
 
-template <int HD, int D>
+template <int HD, int U>
 struct AttCfg {
     static constexpr int KSN = HD / 32;                       // k-steps of the QK^T contraction
     static constexpr int NTN = HD / 16;                       // 16-wide tiles of the head dimension
@@ -150,13 +150,13 @@ __device__ __forceinline__ int att_slot_of_row(int rho) { return 8 * ((rho & 15)
 // XOR swizzle of the 32-byte column pairs of an LDS row (in 16-byte granules): 8 consecutive
 // rows land on 8 different bank groups
 template <int HD>
-__device__ __forceinline__ int att_swizzle(int rho) { return HD == 128 ? 2 * (rho & 7) : 2 * ((rho >> 1) & 3); }
+__device__ __forceinline__ constexpr int att_swizzle(int rho) { return HD == 128 ? 2 * (rho & 7) : 2 * ((rho >> 1) & 3); }
 // The K rows are read as A-operand fragments, 16 lanes fetching the same 16-byte column of 16
 // consecutive rows: there the granule index is XORed with 4 (3) bits of the row.
 template <int HD>
-__device__ __forceinline__ int att_swizzle_k(int rho) { return HD == 128 ? (rho & 15) : ((rho >> 1) & 7); }
+__device__ __forceinline__ constexpr int att_swizzle_k(int rho) { return HD == 128 ? (rho & 15) : ((rho >> 1) & 7); }
 
-template <int HD, int D>
+template <int HD, int U>
 __global__ __launch_bounds__(ATT_WAVES * 64) __attribute__((amdgpu_waves_per_eu(ATT_WAVES / 4, ATT_WAVES / 4))) void tree_attn_kernel(
     TemplateDev t, const uint16_t *__restrict__ q, const uint16_t *__restrict__ q_lo,
     const uint16_t *__restrict__ k_cache, const uint16_t *__restrict__ v_cache,
@@ -166,7 +166,7 @@ __global__ __launch_bounds__(ATT_WAVES * 64) __attribute__((amdgpu_waves_per_eu(
     const int32_t *__restrict__ ctx_len, int batch, int Hq, int Hkv, int P, int smax, int n_splits, int n_mt,
     float scale_log2, float *__restrict__ part_o, float *__restrict__ part_ml, uint16_t *__restrict__ out,
     int as_fragments, int m_tiles_out) {
-    using C = AttCfg<HD, D>;
+    using C = AttCfg<HD, U>;
     constexpr int KSN = C::KSN, NTN = C::NTN, GPR = C::GPR, RPI = C::RPI, NVI = C::NVI;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
@@ -175,7 +175,7 @@ __global__ __launch_bounds__(ATT_WAVES * 64) __attribute__((amdgpu_waves_per_eu(
     // ---- workgroup id -> (kv group, query head of the group, m-tile, split), kv groups dealt
     //      round-robin to the XCDs
     const int qpk = Hq / Hkv;                                // query heads per K/V head
-    const int per_group = qpk * n_mt * n_splits;
+    const int per_group = (qpk / U) * n_mt * n_splits;       // U query heads of the group per workgroup
     const int xcd = blockIdx.x & 7, slot_in_xcd = blockIdx.x >> 3;
     const int group = xcd + 8 * (slot_in_xcd / per_group);  // (sequence, kv head)
     if (group >= batch * Hkv) return;
@@ -183,7 +183,7 @@ __global__ __launch_bounds__(ATT_WAVES * 64) __attribute__((amdgpu_waves_per_eu(
     const int split = w_in % n_splits; w_in /= n_splits;
     const int mt = n_mt - 1 - (w_in % n_mt);                 // long m-tiles first
     const int qh = w_in / n_mt;
-    const int b = group / Hkv, kvh = group % Hkv, h = kvh * qpk + qh;
+    const int b = group / Hkv, kvh = group % Hkv, h0 = kvh * qpk + qh * U;   // heads h0 .. h0+U-1
 
     const int R = t.rows, Lc = ctx_len[b];
     const int row0 = mt * 16;
@@ -211,47 +211,52 @@ __global__ __launch_bounds__(ATT_WAVES * 64) __attribute__((amdgpu_waves_per_eu(
     const int rq = row0 + c;
     const bool row_ok = rq < R;
     const bool row_mask = row_ok && t.is_mask[rq];
-    bf16x8 qf[2][KSN];
+    bf16x8 qf[U][2][KSN];
 #pragma unroll
-    for (int pl = 0; pl < 2; pl++) {
-        const uint16_t *src = pl ? q_lo : q;
+    for (int u = 0; u < U; u++)
 #pragma unroll
-        for (int ks = 0; ks < KSN; ks++) {
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (row_ok && src)
-                v = *reinterpret_cast<const uint4 *>(src + (((int64_t)b * R + rq) * Hq + h) * HD + ks * 32 + g * 8);
-            qf[pl][ks] = __builtin_bit_cast(bf16x8, v);
+        for (int pl = 0; pl < 2; pl++) {
+            const uint16_t *src = pl ? q_lo : q;
+#pragma unroll
+            for (int ks = 0; ks < KSN; ks++) {
+                uint4 v = make_uint4(0, 0, 0, 0);
+                if (row_ok && src)
+                    v = *reinterpret_cast<const uint4 *>(src + (((int64_t)b * R + rq) * Hq + h0 + u) * HD + ks * 32 + g * 8);
+                qf[u][pl][ks] = __builtin_bit_cast(bf16x8, v);
+            }
         }
-    }
 
-    f32x4 o_acc[NTN];
+    f32x4 o_acc[U][NTN];
+    float m_run[U], l_run[U];
 #pragma unroll
-    for (int nt = 0; nt < NTN; nt++) o_acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
-    float m_run = -INFINITY, l_run = 0.f;
+    for (int u = 0; u < U; u++) {
+#pragma unroll
+        for (int nt = 0; nt < NTN; nt++) o_acc[u][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        m_run[u] = -INFINITY;
+        l_run[u] = 0.f;
+    }
 
     unsigned char *v_ring = smem + wave * C::CHUNK_BYTES;              // this wave's private chunk buffer
     // LDS addresses of this lane's transposed V reads inside ring slot 0: lane (g, c) addresses
     // V[slot 8g + 4half + c/4][16nt + 4(c%4) .. +4] and receives V[slots 8g + 4half .. +4][16nt + c]
     // ... and of its K fragment reads: sub-tile tt, k-step ks = row 16tt + c, granule 4ks + g
-    uint32_t k_addr[2][KSN];
+    // (both swizzles ignore bit 4 of the row, so the second sub-tile / half is the same address
+    // plus 16 rows: an immediate offset of the read)
+    static_assert(att_swizzle_k<HD>(16) == 0 && att_swizzle<HD>(16) == 0, "row bit 4 outside the swizzles");
+    constexpr int ROWS16 = 16 * HD * 2;
+    uint32_t k_addr[KSN];
 #pragma unroll
-    for (int tt = 0; tt < 2; tt++)
+    for (int ks = 0; ks < KSN; ks++)
+        k_addr[ks] = (uint32_t)(size_t)((__attribute__((address_space(3))) unsigned char *)v_ring) +
+                     c * (HD * 2) + (((4 * ks + g) ^ att_swizzle_k<HD>(c)) * 16);
+    uint32_t v_addr[NTN];
 #pragma unroll
-        for (int ks = 0; ks < KSN; ks++) {
-            const int rho = 16 * tt + c;
-            k_addr[tt][ks] = (uint32_t)(size_t)((__attribute__((address_space(3))) unsigned char *)v_ring) +
-                             rho * (HD * 2) + (((4 * ks + g) ^ att_swizzle_k<HD>(rho)) * 16);
-        }
-    uint32_t v_addr[NTN][2];
-#pragma unroll
-    for (int nt = 0; nt < NTN; nt++)
-#pragma unroll
-        for (int half = 0; half < 2; half++) {
-            const int rho = 16 * half + 4 * g + (c >> 2);
-            const int gran = (2 * nt + ((c & 3) >> 1)) ^ att_swizzle<HD>(rho);
-            v_addr[nt][half] = (uint32_t)(size_t)((__attribute__((address_space(3))) unsigned char *)v_ring) +
-                               C::KV_BYTES + rho * (HD * 2) + gran * 16 + (c & 1) * 8;
-        }
+    for (int nt = 0; nt < NTN; nt++) {
+        const int rho = 4 * g + (c >> 2);
+        const int gran = (2 * nt + ((c & 3) >> 1)) ^ att_swizzle<HD>(rho);
+        v_addr[nt] = (uint32_t)(size_t)((__attribute__((address_space(3))) unsigned char *)v_ring) +
+                     C::KV_BYTES + rho * (HD * 2) + gran * 16 + (c & 1) * 8;
+    }
 
     // Per-lane byte offsets of the fast path (a chunk that lies wholly inside the cache).  Both
     // operands are copied row-major, 1 KiB (RPI rows) per global->LDS instruction: instruction
@@ -316,7 +321,6 @@ __global__ __launch_bounds__(ATT_WAVES * 64) __attribute__((amdgpu_waves_per_eu(
     // wave's LDS buffer: the next chunk's loads are issued into it right away, interleaved
     // with the QK^T matrix instructions, and have the rest of the step to land.
     auto compute = [&](int i, bool more) __attribute__((always_inline)) {
-        constexpr int SLOT = 0;
         const uint64_t anc_cur = anc_next;
         const int chunk = chunk_begin + wave + ATT_WAVES * i;
         const bool tree_chunk = chunk >= n_cc;
@@ -325,15 +329,18 @@ __global__ __launch_bounds__(ATT_WAVES * 64) __attribute__((amdgpu_waves_per_eu(
 #pragma unroll
         for (int tt = 0; tt < 2; tt++)
 #pragma unroll
-            for (int ks = 0; ks < KSN; ks++) kf[tt][ks] = lds_read_b128<SLOT * C::CHUNK_BYTES>(k_addr[tt][ks]);
+            for (int ks = 0; ks < KSN; ks++)
+                kf[tt][ks] = tt ? lds_read_b128<ROWS16>(k_addr[ks]) : lds_read_b128<0>(k_addr[ks]);
         s16x4 vh[NTN][2];
 #pragma unroll
         for (int nt = 0; nt < NTN; nt++) {
-            vh[nt][0] = lds_read_tr16<SLOT * C::CHUNK_BYTES>(v_addr[nt][0]);
-            vh[nt][1] = lds_read_tr16<SLOT * C::CHUNK_BYTES>(v_addr[nt][1]);
+            vh[nt][0] = lds_read_tr16<0>(v_addr[nt]);
+            vh[nt][1] = lds_read_tr16<ROWS16>(v_addr[nt]);
         }
         lds_wait_all(kf, vh);
-        f32x4 s_acc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+        f32x4 s_acc[U][2];
+#pragma unroll
+        for (int u = 0; u < U; u++) s_acc[u][0] = s_acc[u][1] = f32x4{0.f, 0.f, 0.f, 0.f};
         static_assert(NVI == 2 * KSN, "one (k-step, sub-tile) pair per load slot");
 #pragma unroll
         for (int iv = 0; iv < NVI; iv++) {
@@ -341,24 +348,20 @@ __global__ __launch_bounds__(ATT_WAVES * 64) __attribute__((amdgpu_waves_per_eu(
             if (more) emit(i + 1, iv);
             __builtin_amdgcn_sched_barrier(0);
             const bf16x8 ka = __builtin_bit_cast(bf16x8, kf[tt][ks]);
-            s_acc[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qf[0][ks], s_acc[tt], 0, 0, 0);
-            s_acc[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qf[1][ks], s_acc[tt], 0, 0, 0);
+#pragma unroll
+            for (int u = 0; u < U; u++) {
+                s_acc[u][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qf[u][0][ks], s_acc[u][tt], 0, 0, 0);
+                s_acc[u][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qf[u][1][ks], s_acc[u][tt], 0, 0, 0);
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
-        float sv[8];
-#pragma unroll
-        for (int tt = 0; tt < 2; tt++)
-#pragma unroll
-            for (int r = 0; r < 4; r++) sv[tt * 4 + r] = s_acc[tt][r] * scale_log2;
-        if (tree_chunk) {                    // score = q.k_hi + q.k_lo; partner slots leave the softmax
-#pragma unroll
-            for (int e = 0; e < 4; e++) sv[e] += sv[e + 4];
-        }
+        // the visibility of a key depends on the row and the key only: one mask word for all heads
         const bool need_mask = tree_chunk || (base < P) || (base + ATT_CHUNK > n_ctx_keys);
+        uint32_t bits = 0xFFu;
         if (need_mask) {
             // 8-bit visibility word for this lane's slots, built with integer selects only:
             // prefix -> mask rows, cache -> all rows, pass rows -> ancestor bits.
-            uint32_t bits = 0;
+            bits = 0;
             if (row_ok) {
                 if (tree_chunk) {
                     const int j0 = (chunk - n_cc) * 16 + 4 * g;          // this lane's 4 pass rows (4-aligned)
@@ -376,51 +379,68 @@ __global__ __launch_bounds__(ATT_WAVES * 64) __attribute__((amdgpu_waves_per_eu(
                     }
                 }
             }
-#pragma unroll
-            for (int e = 0; e < 8; e++) sv[e] = ((bits >> e) & 1u) ? sv[e] : -INFINITY;
         }
-        float mx = sv[0];
+        s16x8 v8[NTN];
 #pragma unroll
-        for (int e = 1; e < 8; e++) mx = fmaxf(mx, sv[e]);
-        mx = max_over_lane_groups(mx);
-        const float m_new = fmaxf(m_run, mx);
-        const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-        const float alpha = fast_exp2(m_run - m_use);
-        m_run = m_new;
-        // probabilities as two bf16 planes (value and rounding residual), like every other
-        // MFMA input of the pass
-        float ps = 0.f;
-        uint32_t pk2[4], pl2[4];
+        for (int nt = 0; nt < NTN; nt++)
+            v8[nt] = s16x8{vh[nt][0][0], vh[nt][0][1], vh[nt][0][2], vh[nt][0][3],
+                           vh[nt][1][0], vh[nt][1][1], vh[nt][1][2], vh[nt][1][3]};
 #pragma unroll
-        for (int e = 0; e < 8; e += 2) {
-            const float p0 = fast_exp2(sv[e] - m_use), p1 = fast_exp2(sv[e + 1] - m_use);
-            ps += p0 + p1;
-            const uint32_t hi = cvt_pk_bf16(p0, p1);
-            pk2[e >> 1] = hi;
-            pl2[e >> 1] = cvt_pk_bf16(p0 - __uint_as_float(hi << 16), p1 - __uint_as_float(hi & 0xFFFF0000u));
-        }
-        if (tree_chunk) {                    // the low-plane value rows take the same probabilities
-            pk2[2] = pk2[0];
-            pk2[3] = pk2[1];
-            pl2[2] = pl2[0];
-            pl2[3] = pl2[1];
-        }
-        l_run = l_run * alpha + ps;
-        // O^T[hd][q] = alpha * O^T + V^T[hd][slots 8g..8g+7] * P^T; the running maximum rarely
-        // moves after the first chunks, and then alpha is exactly 1 in every lane
-        if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+        for (int u = 0; u < U; u++) {
+            float sv[8];
 #pragma unroll
-            for (int nt = 0; nt < NTN; nt++) o_acc[nt] *= alpha;
-        }
-        const bf16x8 pf = __builtin_bit_cast(bf16x8, make_uint4(pk2[0], pk2[1], pk2[2], pk2[3]));
-        const bf16x8 pf_lo = __builtin_bit_cast(bf16x8, make_uint4(pl2[0], pl2[1], pl2[2], pl2[3]));
+            for (int tt = 0; tt < 2; tt++)
 #pragma unroll
-        for (int nt = 0; nt < NTN; nt++) {
-            const s16x8 v8 = {vh[nt][0][0], vh[nt][0][1], vh[nt][0][2], vh[nt][0][3],
-                              vh[nt][1][0], vh[nt][1][1], vh[nt][1][2], vh[nt][1][3]};
-            const bf16x8 vf = __builtin_bit_cast(bf16x8, v8);
-            o_acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf, o_acc[nt], 0, 0, 0);
-            o_acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf_lo, o_acc[nt], 0, 0, 0);
+                for (int r = 0; r < 4; r++) sv[tt * 4 + r] = s_acc[u][tt][r] * scale_log2;
+            if (tree_chunk) {                // score = q.k_hi + q.k_lo; partner slots leave the softmax
+#pragma unroll
+                for (int e = 0; e < 4; e++) sv[e] += sv[e + 4];
+            }
+            if (need_mask) {
+#pragma unroll
+                for (int e = 0; e < 8; e++) sv[e] = ((bits >> e) & 1u) ? sv[e] : -INFINITY;
+            }
+            float mx = sv[0];
+#pragma unroll
+            for (int e = 1; e < 8; e++) mx = fmaxf(mx, sv[e]);
+            mx = max_over_lane_groups(mx);
+            const float m_new = fmaxf(m_run[u], mx);
+            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+            const float alpha = fast_exp2(m_run[u] - m_use);
+            m_run[u] = m_new;
+            // probabilities as two bf16 planes (value and rounding residual), like every other
+            // MFMA input of the pass
+            float ps = 0.f;
+            uint32_t pk2[4], pl2[4];
+#pragma unroll
+            for (int e = 0; e < 8; e += 2) {
+                const float p0 = fast_exp2(sv[e] - m_use), p1 = fast_exp2(sv[e + 1] - m_use);
+                ps += p0 + p1;
+                const uint32_t hi = cvt_pk_bf16(p0, p1);
+                pk2[e >> 1] = hi;
+                pl2[e >> 1] = cvt_pk_bf16(p0 - __uint_as_float(hi << 16), p1 - __uint_as_float(hi & 0xFFFF0000u));
+            }
+            if (tree_chunk) {                // the low-plane value rows take the same probabilities
+                pk2[2] = pk2[0];
+                pk2[3] = pk2[1];
+                pl2[2] = pl2[0];
+                pl2[3] = pl2[1];
+            }
+            l_run[u] = l_run[u] * alpha + ps;
+            // O^T[hd][q] = alpha * O^T + V^T[hd][slots 8g..8g+7] * P^T; the running maximum rarely
+            // moves after the first chunks, and then alpha is exactly 1 in every lane
+            if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+#pragma unroll
+                for (int nt = 0; nt < NTN; nt++) o_acc[u][nt] *= alpha;
+            }
+            const bf16x8 pf = __builtin_bit_cast(bf16x8, make_uint4(pk2[0], pk2[1], pk2[2], pk2[3]));
+            const bf16x8 pf_lo = __builtin_bit_cast(bf16x8, make_uint4(pl2[0], pl2[1], pl2[2], pl2[3]));
+#pragma unroll
+            for (int nt = 0; nt < NTN; nt++) {
+                const bf16x8 vf = __builtin_bit_cast(bf16x8, v8[nt]);
+                o_acc[u][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf, o_acc[u][nt], 0, 0, 0);
+                o_acc[u][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf_lo, o_acc[u][nt], 0, 0, 0);
+            }
         }
     };
 
@@ -435,69 +455,74 @@ __global__ __launch_bounds__(ATT_WAVES * 64) __attribute__((amdgpu_waves_per_eu(
     }
     att_wait<0>();
 
-    // ---- merge the 4 wavefronts (disjoint key subsets); wave 0 sums in wave order ----------
-    __syncthreads();
+    // ---- merge the wavefronts (disjoint key subsets), head by head; wave 0 sums in wave order ---
     float *sm = reinterpret_cast<float *>(smem), *sl = sm + ATT_WAVES * 16;
     float4 *region = reinterpret_cast<float4 *>(smem + 2 * ATT_WAVES * 16 * 4);   // [WAVES-1][NTN][64]
-    const float l = sum_over_lane_groups(l_run);
-    if (g == 0) {
-        sm[wave * 16 + c] = m_run;
-        sl[wave * 16 + c] = l;
-    }
-    __syncthreads();
-    float m_tot = -INFINITY;
 #pragma unroll
-    for (int w = 0; w < ATT_WAVES; w++) m_tot = fmaxf(m_tot, sm[w * 16 + c]);
-    const float m_use = (m_tot == -INFINITY) ? 0.f : m_tot;
-    float l_tot = 0.f;
+    for (int u = 0; u < U; u++) {
+        const int h = h0 + u;
+        __syncthreads();                     // the chunk buffers (first head) or the previous head's sums are done with
+        const float l = sum_over_lane_groups(l_run[u]);
+        if (g == 0) {
+            sm[wave * 16 + c] = m_run[u];
+            sl[wave * 16 + c] = l;
+        }
+        __syncthreads();
+        float m_tot = -INFINITY;
 #pragma unroll
-    for (int w = 0; w < ATT_WAVES; w++) l_tot += sl[w * 16 + c] * fast_exp2(sm[w * 16 + c] - m_use);
-    const float f = fast_exp2(m_run - m_use);
+        for (int w = 0; w < ATT_WAVES; w++) m_tot = fmaxf(m_tot, sm[w * 16 + c]);
+        const float m_use = (m_tot == -INFINITY) ? 0.f : m_tot;
+        float l_tot = 0.f;
 #pragma unroll
-    for (int nt = 0; nt < NTN; nt++) o_acc[nt] *= f;
-    if (wave > 0) {
+        for (int w = 0; w < ATT_WAVES; w++) l_tot += sl[w * 16 + c] * fast_exp2(sm[w * 16 + c] - m_use);
+        const float f = fast_exp2(m_run[u] - m_use);
 #pragma unroll
-        for (int nt = 0; nt < NTN; nt++)
-            region[((wave - 1) * NTN + nt) * 64 + lane] = make_float4(o_acc[nt][0], o_acc[nt][1], o_acc[nt][2], o_acc[nt][3]);
-    }
-    __syncthreads();
-    if (wave != 0 || !row_ok) return;
+        for (int nt = 0; nt < NTN; nt++) o_acc[u][nt] *= f;
+        if (wave > 0) {
 #pragma unroll
-    for (int w = 1; w < ATT_WAVES; w++)
+            for (int nt = 0; nt < NTN; nt++)
+                region[((wave - 1) * NTN + nt) * 64 + lane] =
+                    make_float4(o_acc[u][nt][0], o_acc[u][nt][1], o_acc[u][nt][2], o_acc[u][nt][3]);
+        }
+        __syncthreads();
+        if (wave != 0 || !row_ok) continue;
+#pragma unroll
+        for (int w = 1; w < ATT_WAVES; w++)
+#pragma unroll
+            for (int nt = 0; nt < NTN; nt++) {
+                const float4 v = region[((w - 1) * NTN + nt) * 64 + lane];
+                o_acc[u][nt][0] += v.x; o_acc[u][nt][1] += v.y; o_acc[u][nt][2] += v.z; o_acc[u][nt][3] += v.w;
+            }
+        // ---- lane (g, c) holds O[row rq][hd 16nt + 4g .. +4] -----------------------------------
+        if (n_splits > 1) {                  // unnormalised partial for attn_merge_kernel
+            const int64_t prow = (((int64_t)b * Hq + h) * n_splits + split) * R + rq;
+#pragma unroll
+            for (int nt = 0; nt < NTN; nt++)
+                *reinterpret_cast<float4 *>(part_o + prow * HD + nt * 16 + 4 * g) =
+                    make_float4(o_acc[u][nt][0], o_acc[u][nt][1], o_acc[u][nt][2], o_acc[u][nt][3]);
+            if (g == 0) {
+                part_ml[prow * 2] = m_tot;
+                part_ml[prow * 2 + 1] = l_tot;
+            }
+            continue;
+        }
+        const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+        const int mrow = b * R + rq, n_ksteps = (Hq * HD) >> 5;
 #pragma unroll
         for (int nt = 0; nt < NTN; nt++) {
-            const float4 v = region[((w - 1) * NTN + nt) * 64 + lane];
-            o_acc[nt][0] += v.x; o_acc[nt][1] += v.y; o_acc[nt][2] += v.z; o_acc[nt][3] += v.w;
-        }
-    // ---- lane (g, c) holds O[row rq][hd 16nt + 4g .. +4] ---------------------------------------
-    if (n_splits > 1) {                      // unnormalised partial for attn_merge_kernel
-        const int64_t prow = (((int64_t)b * Hq + h) * n_splits + split) * R + rq;
+            uint16_t hi[4], lo[4];
 #pragma unroll
-        for (int nt = 0; nt < NTN; nt++)
-            *reinterpret_cast<float4 *>(part_o + prow * HD + nt * 16 + 4 * g) =
-                make_float4(o_acc[nt][0], o_acc[nt][1], o_acc[nt][2], o_acc[nt][3]);
-        if (g == 0) {
-            part_ml[prow * 2] = m_tot;
-            part_ml[prow * 2 + 1] = l_tot;
-        }
-        return;
-    }
-    const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
-    const int mrow = b * R + rq, n_ksteps = (Hq * HD) >> 5;
-#pragma unroll
-    for (int nt = 0; nt < NTN; nt++) {
-        uint16_t hi[4], lo[4];
-#pragma unroll
-        for (int e = 0; e < 4; e++) split_bf16(o_acc[nt][e] * inv, hi[e], lo[e]);
-        uint2 ph, pl;
-        ph.x = hi[0] | ((uint32_t)hi[1] << 16); ph.y = hi[2] | ((uint32_t)hi[3] << 16);
-        pl.x = lo[0] | ((uint32_t)lo[1] << 16); pl.y = lo[2] | ((uint32_t)lo[3] << 16);
-        const int k = h * HD + nt * 16 + 4 * g;
-        if (as_fragments) {                  // two planes, the O-projection's activation slab
-            *reinterpret_cast<uint2 *>(out + frag_index(0, mrow, k, n_ksteps, m_tiles_out)) = ph;
-            *reinterpret_cast<uint2 *>(out + frag_index(1, mrow, k, n_ksteps, m_tiles_out)) = pl;
-        } else {
-            *reinterpret_cast<uint2 *>(out + (int64_t)mrow * Hq * HD + k) = ph;
+            for (int e = 0; e < 4; e++) split_bf16(o_acc[u][nt][e] * inv, hi[e], lo[e]);
+            uint2 ph, pl;
+            ph.x = hi[0] | ((uint32_t)hi[1] << 16); ph.y = hi[2] | ((uint32_t)hi[3] << 16);
+            pl.x = lo[0] | ((uint32_t)lo[1] << 16); pl.y = lo[2] | ((uint32_t)lo[3] << 16);
+            const int k = h * HD + nt * 16 + 4 * g;
+            if (as_fragments) {              // two planes, the O-projection's activation slab
+                *reinterpret_cast<uint2 *>(out + frag_index(0, mrow, k, n_ksteps, m_tiles_out)) = ph;
+                *reinterpret_cast<uint2 *>(out + frag_index(1, mrow, k, n_ksteps, m_tiles_out)) = pl;
+            } else {
+                *reinterpret_cast<uint2 *>(out + (int64_t)mrow * Hq * HD + k) = ph;
+            }
         }
     }
 }
@@ -565,25 +590,24 @@ AttnPlan attn_plan(int batch, int rows, int n_heads, int hd, int ctx_hint, int n
     return p;
 }
 
-template <int HD>
+template <int HD, int U>
 static void launch_attn_t(const TemplateDev &t, const void *q, const void *q_lo, const void *k_cache, const void *v_cache,
                           const void *k_tree, const void *v_tree, const void *k_tree_lo, const void *v_tree_lo,
                           const void *prompt_k, const void *prompt_v, const int32_t *ctx_len, int batch, int Hq,
                           int Hkv, int P, int smax, const AttnPlan &p, float *part_o, float *part_ml, void *out,
                           bool out_as_fragments, hipStream_t s) {
-    constexpr int D = 2;
-    using C = AttCfg<HD, D>;
+    using C = AttCfg<HD, U>;
     static bool attr_set = false;
     if (!attr_set) {
-        (void)hipFuncSetAttribute((const void *)tree_attn_kernel<HD, D>,
+        (void)hipFuncSetAttribute((const void *)tree_attn_kernel<HD, U>,
                                   hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM);
         attr_set = true;
     }
     const int n_mt = (t.rows + 15) / 16;
     const float scale_log2 = 1.4426950408889634f / sqrtf((float)HD);
-    const int groups = batch * Hkv, per_group = (Hq / Hkv) * n_mt * p.splits;
+    const int groups = batch * Hkv, per_group = (Hq / Hkv / U) * n_mt * p.splits;
     const int grid = 8 * ((groups + 7) / 8) * per_group;
-    hipLaunchKernelGGL((tree_attn_kernel<HD, D>), dim3(grid), dim3(ATT_WAVES * 64), C::SMEM, s, t,
+    hipLaunchKernelGGL((tree_attn_kernel<HD, U>), dim3(grid), dim3(ATT_WAVES * 64), C::SMEM, s, t,
                        (const uint16_t *)q, (const uint16_t *)q_lo, (const uint16_t *)k_cache, (const uint16_t *)v_cache,
                        (const uint16_t *)k_tree, (const uint16_t *)v_tree, (const uint16_t *)k_tree_lo,
                        (const uint16_t *)v_tree_lo, (const uint16_t *)prompt_k, (const uint16_t *)prompt_v, ctx_len,
@@ -597,12 +621,16 @@ void launch_tree_attention(const TemplateDev &t, const void *q, const void *q_lo
                            const void *prompt_v, const int32_t *ctx_len, int batch, int Hq, int Hkv, int hd,
                            int P, int smax, const AttnPlan &p, float *part_o, float *part_ml, void *out,
                            bool out_as_fragments, hipStream_t s) {
-    if (hd == 128)
-        launch_attn_t<128>(t, q, q_lo, k_cache, v_cache, k_tree, v_tree, k_tree_lo, v_tree_lo, prompt_k, prompt_v,
-                           ctx_len, batch, Hq, Hkv, P, smax, p, part_o, part_ml, out, out_as_fragments, s);
-    else
-        launch_attn_t<64>(t, q, q_lo, k_cache, v_cache, k_tree, v_tree, k_tree_lo, v_tree_lo, prompt_k, prompt_v,
-                          ctx_len, batch, Hq, Hkv, P, smax, p, part_o, part_ml, out, out_as_fragments, s);
+    // grouped-query models: two query heads of a K/V head per workgroup share its chunk loads
+    const bool pair = (Hq / Hkv) % 2 == 0;
+#define ATT_LAUNCH(HD_, U_) launch_attn_t<HD_, U_>(t, q, q_lo, k_cache, v_cache, k_tree, v_tree, k_tree_lo, v_tree_lo, prompt_k, \
+                                                   prompt_v, ctx_len, batch, Hq, Hkv, P, smax, p, part_o, part_ml, out, out_as_fragments, s)
+    if (hd == 128) {
+        if (pair) ATT_LAUNCH(128, 2); else ATT_LAUNCH(128, 1);
+    } else {
+        if (pair) ATT_LAUNCH(64, 2); else ATT_LAUNCH(64, 1);
+    }
+#undef ATT_LAUNCH
     if (p.splits > 1) {
         const int heads_per_block = (256 / (hd / 4)) < Hq ? (256 / (hd / 4)) : Hq;
         hipLaunchKernelGGL(attn_merge_kernel, dim3(t.rows, (Hq + heads_per_block - 1) / heads_per_block, batch),
