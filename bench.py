@@ -30,6 +30,8 @@ HBM_PEAK_GBPS = 8000.0
 # FETCH_SIZE / WRITE_SIZE counter runs scaled by a copy kernel (profiles/gemm_traffic_7b.md);
 # counters cannot be collected from inside this process, so the figure is carried as a constant
 GEMM_TRAFFIC_BYTES_PER_LAUNCH = {"7b": 125.1e6}
+# layer counts of the two oracle passes timed for cpu_baseline (about 10 s of host work at 7B width)
+CPU_SAMPLE_LAYERS = (4, 8)
 
 
 def parse_args():
@@ -128,8 +130,8 @@ def prefill(B, model, kv, cfg, ctx_tokens, chunk=64):
 
 
 def cpu_baseline(cfg, wsrc_np, kv_np, tmpl_in, tokens, ctx_len):
-    """Time the oracle on a bounded sample: passes with 1 and 2 of the model's layers (+ LM
-    head) at full width, extrapolated linearly to the full depth."""
+    """Time the oracle on a bounded sample: passes with CPU_SAMPLE_LAYERS[0] and [1] of the
+    model's layers (+ LM head) at full width, extrapolated linearly to the full depth."""
     import oracle
     from oracle.tree import derive_template, ancestors_or_self
 
@@ -141,12 +143,15 @@ def cpu_baseline(cfg, wsrc_np, kv_np, tmpl_in, tokens, ctx_len):
     pos = [ctx_len + d.depth[r] for r in range(d.R)]
     vis = [ancestors_or_self(d.parent, r) for r in range(d.R)]
     ts = []
-    for nl in (1, 2):
+    na, nb = CPU_SAMPLE_LAYERS
+    if cfg.n_layers < nb:
+        na, nb = max(1, cfg.n_layers // 2), max(2, cfg.n_layers)
+    for nl in (na, nb):
         t0 = time.perf_counter()
         oracle.forward_rows(om, tokens, d.is_mask, d.mask_index, pos, vis, kv_np[0], kv_np[1], n_layers=nl)
         ts.append(time.perf_counter() - t0)
-    layer = max(ts[1] - ts[0], 1e-9)
-    head = max(ts[0] - layer, 0.0)
+    layer = max((ts[1] - ts[0]) / (nb - na), 1e-9)
+    head = max(ts[0] - na * layer, 0.0)
     full = head + cfg.n_layers * layer
     try:
         from threadpoolctl import threadpool_info
@@ -155,7 +160,7 @@ def cpu_baseline(cfg, wsrc_np, kv_np, tmpl_in, tokens, ctx_len):
         threads = os.cpu_count() or 1
     return dict(value=d.R / full, unit="tokens/s", cores=int(threads), kind="oracle",
                 ms_per_step=full * 1e3,
-                sample=f"oracle forward of 1 and 2 of {cfg.n_layers} layers + LM head at full width "
+                sample=f"oracle forward of {na} and {nb} of {cfg.n_layers} layers + LM head at full width "
                        f"({ts[0]:.1f}s + {ts[1]:.1f}s), extrapolated linearly to {cfg.n_layers} layers")
 
 
@@ -198,7 +203,7 @@ def main():
 
     # ---- model: weights drawn on the GPU, packed layer by layer ----------------------------
     w = synth.SynthWeights(cfg, seed=args.seed, device="cuda")
-    keep_layers = (0, 1)
+    keep_layers = tuple(range(min(CPU_SAMPLE_LAYERS[1], cfg.n_layers)))
     wsrc_np = {}
     if not args.no_cpu_baseline:
         for l in keep_layers:
