@@ -111,6 +111,11 @@ ATT_TOL = 2e-2
     dict(B=1, Hq=2, Hkv=2, hd=128, P=16, ctx=[1], T=1, depth=0, attach=[], n=4),
     dict(B=3, Hq=8, Hkv=1, hd=128, P=16, ctx=[1024, 96, 2047], T=64, depth=5, attach=[0], n=4),
     dict(B=1, Hq=2, Hkv=1, hd=64, P=4, ctx=[200], T=21, depth=4, attach=list(range(21)), n=4),
+    # three query heads per K/V head (no pairing), a context long enough for a key split by
+    # length (more than 256 chunks), and the largest template (512 rows, 32 row tiles)
+    dict(B=2, Hq=3, Hkv=1, hd=128, P=16, ctx=[77, 400], T=20, depth=4, attach=[0], n=4),
+    dict(B=1, Hq=2, Hkv=2, hd=128, P=16, ctx=[9000], T=8, depth=3, attach=[0], n=4),
+    dict(B=1, Hq=2, Hkv=1, hd=64, P=8, ctx=[50], T=508, depth=9, attach=[0], n=4),
 ])
 def test_tree_attention_matches_oracle(bita, case):
     parent = synth.random_tree(case["T"], max(case["depth"], 1), 11) if case["T"] > 1 else np.array([-1], np.int32)
