@@ -225,6 +225,48 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
     }
     // D layout: lane (g = lane/16, c = lane%16) holds rows 4g..4g+3, column c of each tile.
     const int g = lane >> 4, cc = lane & 15;
+    // Stores of the wave's MT x NW tiles (k group 0 after the merge).  With k groups they go
+    // through the wave's own LDS region (the one its partners wrote into, private since the
+    // merge) and leave as 16 bytes per lane: whole NW*64-byte row segments instead of 64-byte
+    // pieces.  Rows of 4-row group g sit in the half of the row given by g's parity (two-way
+    // instead of four-way bank conflicts).
+    auto store_tiles = [&](float *o, auto &&value) __attribute__((always_inline)) {
+        if constexpr (KG > 1) {
+            constexpr int CPR = NW * 4, RPI = 64 / CPR;       // 16-byte chunks per row, rows per store instruction
+            float *stage = reinterpret_cast<float *>(smem_u4) + wn * (MT * NW * 256);
+#pragma unroll
+            for (int i = 0; i < MT; i++)
+#pragma unroll
+                for (int j = 0; j < NW; j++)
+#pragma unroll
+                    for (int r = 0; r < 4; r++) {
+                        const int row = i * 16 + 4 * g + r, chunk = (j * 4 + (cc >> 2)) ^ ((CPR / 2) * (g & 1));
+                        stage[row * (NW * 16) + chunk * 4 + (cc & 3)] = value(i, j, r);
+                    }
+            // (the same wave wrote and reads: LDS keeps a wave's accesses in order)
+#pragma unroll
+            for (int k = 0; k < MT * 16 / RPI; k++) {
+                const int row = k * RPI + lane / CPR, chunk = lane % CPR;
+                const int phys = chunk ^ ((CPR / 2) * ((row >> 2) & 1));
+                const float4 v = *reinterpret_cast<const float4 *>(stage + row * (NW * 16) + phys * 4);
+                const int m = m_base + row, t = t0 + (chunk >> 2);
+                if (m < M && t < NT) *reinterpret_cast<float4 *>(o + (int64_t)m * ldo + t0 * 16 + chunk * 4) = v;
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < NW; j++) {
+                const int t = t0 + j;
+                if (t >= NT) continue;
+#pragma unroll
+                for (int i = 0; i < MT; i++)
+#pragma unroll
+                    for (int r = 0; r < 4; r++) {
+                        const int m = m_base + i * 16 + 4 * g + r;
+                        if (m < M) o[(int64_t)m * ldo + t * 16 + cc] = value(i, j, r);
+                    }
+            }
+        }
+    };
     if (DIRECT && direct.kind != GEMM_OUT_PARTIAL) {
         // single split: the sums are complete.  The row factors of the block's rows are computed
         // once per workgroup (one thread per row) and handed out through LDS.
@@ -239,18 +281,8 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
 #pragma unroll
             for (int r = 0; r < 4; r++) sc[i][r] = scale_lds[i * 16 + 4 * g + r];
         if (direct.kind == GEMM_OUT_SCALED) {
-#pragma unroll
-            for (int j = 0; j < NW; j++) {
-                const int t = t0 + j;
-                if (t >= NT) continue;
-#pragma unroll
-                for (int i = 0; i < MT; i++)
-#pragma unroll
-                    for (int r = 0; r < 4; r++) {
-                        const int m = m_base + i * 16 + 4 * g + r;
-                        if (m < M) out[(int64_t)m * ldo + t * 16 + cc] = acc[i][j][r] * sc[i][r];
-                    }
-            }
+            // (the row factors sit in the dump slot behind the ring, outside the staging regions)
+            store_tiles(out, [&](int i, int j, int r) { return acc[i][j][r] * sc[i][r]; });
         } else if constexpr (NW % 2 == 0) {
             // Tiles alternate gate, up: accumulators (j, j+1) hold gate and up of the same 16
             // features for the same rows and lanes.  The workgroup's WN*NW*8 features are whole
@@ -293,19 +325,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
         }
         return;
     }
-    float *o = out + (int64_t)blockIdx.y * M * ldo;
-#pragma unroll
-    for (int j = 0; j < NW; j++) {
-        const int t = t0 + j;
-        if (t >= NT) continue;
-#pragma unroll
-        for (int i = 0; i < MT; i++)
-#pragma unroll
-            for (int r = 0; r < 4; r++) {
-                const int m = m_base + i * 16 + 4 * g + r;
-                if (m < M) o[(int64_t)m * ldo + t * 16 + cc] = acc[i][j][r];
-            }
-    }
+    store_tiles(out + (int64_t)blockIdx.y * M * ldo, [&](int i, int j, int r) { return acc[i][j][r]; });
 }
 
 // out[m][n] = rowscale(m) * sum over splits of partial[s][m][n], in split order
