@@ -80,7 +80,7 @@ struct GemmCfg {
     // those beyond NFRAG land in one shared dump slot after the ring
     static constexpr int RING = KG * D * NFRAG * 1024;          // one ring per k group
     static constexpr int MERGE = KG > 1 ? WN * MT * NW * 1024 : 0;   // accumulators of one k group
-    static constexpr int STAGE = NW % 2 == 0 ? 2 * (WN * NW * 8 / 32) * MT * 1024 : 0;   // gated output slab of the workgroup
+    static constexpr int STAGE = NW % 2 == 0 ? 2 * (WN * NW * 8 / 16) * MT * 512 : 0;    // gated output slab of the workgroup
     static constexpr int SMEM = (RING > MERGE ? (RING > STAGE ? RING : STAGE) : (MERGE > STAGE ? MERGE : STAGE)) + 1024;
     static_assert((D - 2) * LOADS < 64, "vmcnt counter range");
 };
@@ -288,16 +288,18 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
             // features for the same rows and lanes.  The workgroup's WN*NW*8 features are whole
             // k-steps of the next GEMM: the gated values are laid out as its fragments in LDS
             // (two planes) and leave as whole 1 KiB fragments, 16 bytes per lane.
-            constexpr int FEATS = WN * NW * 8, KSL = FEATS / 32;          // features, k-steps per workgroup
-            static_assert(FEATS % 32 == 0, "whole k-steps");
-            static_assert(2 * KSL * MT * 1024 <= C::SMEM, "staging fits the ring");
+            constexpr int FEATS = WN * NW * 8, HK = FEATS / 16;           // features, half k-steps per workgroup
+            static_assert(FEATS % 16 == 0, "whole half fragments");
+            static_assert(2 * HK * MT * 512 <= C::SMEM, "staging fits the ring");
+            // a fragment (16 rows x 32 features) is two contiguous halves of 16 features
+            // (512 bytes: [feature octet][row][8 features]); the workgroup's features are whole halves
             const int F = direct.d_ffn, n_ksteps = (F + 31) >> 5, mt_all = (M + 15) >> 4;
-            uint16_t *stage = reinterpret_cast<uint16_t *>(smem_u4);     // [plane][KSL][MT][512]
+            uint16_t *stage = reinterpret_cast<uint16_t *>(smem_u4);     // [plane][HK][MT][256]
             // (every wave is past the ring and the merge area: synchronised above)
 #pragma unroll
             for (int j = 0; j < NW; j += 2) {
                 const int f_local = (wn * NW + j) * 8 + cc;              // feature inside the workgroup
-                const int ksl = f_local >> 5, pos = ((f_local >> 3) & 3) * 128 + (f_local & 7);
+                const int hk = f_local >> 4, pos = ((f_local >> 3) & 1) * 128 + (f_local & 7);
                 const bool live = (t0 + j) < NT;
 #pragma unroll
                 for (int i = 0; i < MT; i++)
@@ -308,19 +310,23 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
                         uint16_t hi, lo;
                         split_bf16(v, hi, lo);
                         const int at = pos + (4 * g + r) * 8;            // row 4g+r of m-tile i
-                        stage[((0 * KSL + ksl) * MT + i) * 512 + at] = hi;
-                        stage[((1 * KSL + ksl) * MT + i) * 512 + at] = lo;
+                        stage[((0 * HK + hk) * MT + i) * 256 + at] = hi;
+                        stage[((1 * HK + hk) * MT + i) * 256 + at] = lo;
                     }
             }
             __syncthreads();
             // fragment (plane, ks, mt) of the slab starts at ((plane * n_ksteps + ks) * mt_all + mt) KiB;
-            // k-steps at or beyond n_ksteps and m-tiles beyond the slab do not exist
-            const int ks0 = blockIdx.x * KSL, mt0 = blockIdx.z * MT;
-            for (int fr = wn; fr < 2 * KSL * MT; fr += WN) {
-                const int plane = fr / (KSL * MT), ksl = (fr / MT) % KSL, i = fr % MT;
-                if (ks0 + ksl >= n_ksteps || mt0 + i >= mt_all) continue;
-                const uint4 v = reinterpret_cast<const uint4 *>(stage)[fr * 64 + lane];
-                reinterpret_cast<uint4 *>(direct.act_frag)[(((int64_t)plane * n_ksteps + ks0 + ksl) * mt_all + mt0 + i) * 64 + lane] = v;
+            // k-steps at or beyond n_ksteps and m-tiles beyond the slab do not exist.
+            // One store instruction moves two halves (32 lanes x 16 bytes each).
+            const int hk0 = blockIdx.x * HK, mt0 = blockIdx.z * MT, half_lane = lane >> 5, l32 = lane & 31;
+            for (int pr = wn; pr < HK * MT * 2 / 2; pr += WN) {
+                const int idx = pr * 2 + half_lane;                      // (plane, hk, i) flattened, as staged
+                const int plane = idx / (HK * MT), hk = (idx / MT) % HK, i = idx % MT;
+                const int hkg = hk0 + hk;                                // half k-step in the whole slab
+                if ((hkg >> 1) >= n_ksteps || mt0 + i >= mt_all) continue;   // (a last half past F holds zeros)
+                const uint4 v = reinterpret_cast<const uint4 *>(stage)[idx * 32 + l32];
+                reinterpret_cast<uint4 *>(direct.act_frag)[(((int64_t)plane * n_ksteps + (hkg >> 1)) * mt_all + mt0 + i) * 64 +
+                                                           (hkg & 1) * 32 + l32] = v;
             }
         }
         return;
@@ -370,7 +376,7 @@ __global__ void to_fragments_kernel(const uint16_t *__restrict__ a_hi, const uin
 struct GemmVariant { int nw, waves, depth, kgroups; };
 static const GemmVariant g_variants[] = {
     {1, 4, 4, 1}, {2, 4, 4, 1}, {4, 4, 4, 1}, {2, 8, 6, 1}, {4, 8, 6, 1},
-    {2, 8, 4, 2}, {4, 8, 4, 2}, {1, 8, 4, 2}, {2, 8, 3, 2}, {2, 16, 3, 2},
+    {2, 8, 4, 2}, {4, 8, 4, 2}, {1, 8, 4, 2}, {2, 8, 3, 2}, {2, 16, 3, 2}, {2, 6, 3, 2}, {2, 14, 3, 2},
 };
 #define GEMM_N_VARIANTS ((int)(sizeof(g_variants) / sizeof(g_variants[0])))
 static int g_force_variant = -1, g_force_splits = -1;
@@ -387,9 +393,20 @@ GemmPlan gemm_plan(int m_rows, int64_t n_rows, int64_t k) {
     p.variant = NT < 3000 ? 8 : 6;
     // 16 waves (256 columns per workgroup, half the activation-slab traffic per weight byte)
     // for the widest matrices, the QKV-like widths and narrow matrices with a very long k;
-    // instantiated for 1 and 5 m-tiles per pass
+    // these and the 6- and 14-wave forms are instantiated for 1 and 5 m-tiles per pass
     const bool wide16 = NT >= 3000 || (NT >= 512 && NT < 1024 && (NT >= 640 || KS >= 512));
-    if (wide16 && !(m_tiles == 2 || m_tiles == 3 || m_tiles == 6 || m_tiles == 7)) p.variant = 9;
+    const bool mt_1_or_5 = !(m_tiles == 2 || m_tiles == 3 || m_tiles == 6 || m_tiles == 7);
+    if (wide16 && mt_1_or_5) p.variant = 9;
+    // matrices wide enough for a single k split: the workgroup width (3, 4, 7 or 8 waves of 2
+    // tiles per k group) that puts the most workgroups on the 256 CUs in one round
+    if (NT >= 1024 && mt_1_or_5) {
+        static const int wn_of[4] = {3, 4, 7, 8}, variant_of[4] = {10, 8, 11, 9};
+        int64_t best = 0;
+        for (int i = 0; i < 4; i++) {
+            const int64_t wgs = (NT + 2 * wn_of[i] - 1) / (2 * wn_of[i]);
+            if (wgs <= 256 && wgs >= best) { best = wgs; p.variant = variant_of[i]; }
+        }
+    }
     if (m_tiles == 6 || m_tiles == 7) p.variant = 8;            // one pass: 4 tiles per wave x 7 m-tiles of accumulators would spill
     if (g_force_variant >= 0 && g_force_variant < GEMM_N_VARIANTS) p.variant = g_force_variant;
     const GemmVariant &v = g_variants[p.variant];
@@ -437,7 +454,7 @@ static void launch_gemm_v(const void *a_frag, int M, int64_t K, const void *w, i
         break;
     switch (p.variant) {
         V(0, 1, 4, 4, 1) V(1, 2, 4, 4, 1) V(2, 4, 4, 4, 1) V(3, 2, 8, 6, 1) V(4, 4, 8, 6, 1)
-        W(5, 2, 8, 4, 2) W(6, 4, 8, 4, 2) V(7, 1, 8, 4, 2) W(8, 2, 8, 3, 2) W(9, 2, 16, 3, 2)
+        W(5, 2, 8, 4, 2) W(6, 4, 8, 4, 2) V(7, 1, 8, 4, 2) W(8, 2, 8, 3, 2) W(9, 2, 16, 3, 2) W(10, 2, 6, 3, 2) W(11, 2, 14, 3, 2)
     }
 #undef V
 #undef W
@@ -490,7 +507,7 @@ void launch_gemm(const void *a_frag, bool two_planes, int M, int64_t K, const vo
 }
 bool gemm_direct_output_possible(const GemmPlan &p, int kind) {
     (void)kind;
-    return p.splits == 1 && (p.variant == 5 || p.variant == 6 || p.variant == 8 || p.variant == 9);   // even tiles per wave, see launch_gemm_v
+    return p.splits == 1 && (p.variant == 5 || p.variant == 6 || p.variant >= 8);   // even tiles per wave, see launch_gemm_v
 }
 
 size_t frag_bytes(int m_rows, int64_t k) {                     // two planes
