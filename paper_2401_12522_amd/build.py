@@ -10,6 +10,9 @@ SOURCES = ["api.hip", "gemm.hip", "attention.hip", "misc.hip", "tree.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # kernel arguments arrive in SGPRs with the wave instead of through a scalar load at
+         # the head of every kernel (267 launches per step)
+         "-mllvm", "-amdgpu-kernarg-preload-count=16",
          "-Wno-unused-command-line-argument"]
 
 
