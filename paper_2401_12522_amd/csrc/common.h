@@ -65,8 +65,15 @@ struct RowScale { const float *ssq; int chunks; float inv_d, eps; };   // ssq ==
 // second half of RMSNorm: rsqrt(mean(x^2) + eps) of row m from the per-chunk sums of squares
 __device__ __forceinline__ float row_scale(const RowScale &rs, int m) {
     if (!rs.ssq) return 1.0f;
+    // all 16 slots of the row are fetched at once (independent loads, one round trip) and summed
+    // in chunk order; slots at or beyond rs.chunks are never written and are left out
+    const float4 *p = reinterpret_cast<const float4 *>(rs.ssq + (int64_t)m * RMS_MAX_CHUNKS);
+    const float4 q0 = p[0], q1 = p[1], q2 = p[2], q3 = p[3];
+    const float v[RMS_MAX_CHUNKS] = {q0.x, q0.y, q0.z, q0.w, q1.x, q1.y, q1.z, q1.w,
+                                     q2.x, q2.y, q2.z, q2.w, q3.x, q3.y, q3.z, q3.w};
     float tot = 0.f;
-    for (int ch = 0; ch < rs.chunks; ch++) tot += rs.ssq[(int64_t)m * RMS_MAX_CHUNKS + ch];
+#pragma unroll
+    for (int ch = 0; ch < RMS_MAX_CHUNKS; ch++) tot += ch < rs.chunks ? v[ch] : 0.f;
     return 1.0f / sqrtf(tot * rs.inv_d + rs.eps);
 }
 struct GemmPlan { int splits, ksteps_per_split, variant; };

@@ -45,9 +45,16 @@ __global__ __launch_bounds__(256) void rmsnorm_prep_kernel(float *__restrict__ x
     if (c < (d >> 2)) {
         float4 *xr = reinterpret_cast<float4 *>(x + (int64_t)row * d);
         float4 v = xr[c];
-        for (int s = 0; s < splits; s++) {
-            const float4 p = reinterpret_cast<const float4 *>(partial + ((int64_t)s * M + row) * d)[c];
-            v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
+        // eight splits per round trip (the loads of a group are independent; indices past the
+        // last split re-read it and are left out of the sum), summed in split order
+        for (int s0 = 0; s0 < splits; s0 += 8) {
+            float4 p[8];
+#pragma unroll
+            for (int u = 0; u < 8; u++)
+                p[u] = reinterpret_cast<const float4 *>(partial + ((int64_t)min(s0 + u, splits - 1) * M + row) * d)[c];
+#pragma unroll
+            for (int u = 0; u < 8; u++)
+                if (s0 + u < splits) { v.x += p[u].x; v.y += p[u].y; v.z += p[u].z; v.w += p[u].w; }
         }
         if (splits > 0) xr[c] = v;
         ss = v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
@@ -87,10 +94,17 @@ __global__ __launch_bounds__(64) void qkv_rope_kernel(
     const int64_t ncols = (int64_t)(Hq + 2 * Hkv) * hd;
     const int64_t col = (int64_t)head * hd + i;
     float lo = 0.f, hi = 0.f;
-    for (int s = 0; s < splits; s++) {
-        const float *p = partial + ((int64_t)s * M + row) * ncols + col;
-        lo += p[0];
-        hi += p[half];
+    for (int s0 = 0; s0 < splits; s0 += 8) {     // eight splits per round trip, summed in split order
+        float pl[8], ph[8];
+#pragma unroll
+        for (int u = 0; u < 8; u++) {
+            const float *p = partial + ((int64_t)min(s0 + u, splits - 1) * M + row) * ncols + col;
+            pl[u] = p[0];
+            ph[u] = p[half];
+        }
+#pragma unroll
+        for (int u = 0; u < 8; u++)
+            if (s0 + u < splits) { lo += pl[u]; hi += ph[u]; }
     }
     const float sc = row_scale(rs, row);          // RMSNorm's row factor, deferred past the GEMM
     lo *= sc;
