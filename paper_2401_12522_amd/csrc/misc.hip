@@ -17,8 +17,16 @@ __global__ void embed_kernel(const int32_t *__restrict__ token, TemplateDev t,
     } else if (tok >= 0 && tok < vocab) {
         src = tok_emb + (int64_t)tok * d;
     }
-    for (int i = threadIdx.x; i < d; i += blockDim.x)
-        x[(int64_t)row * d + i] = src ? bf16_to_f32(src[i]) : 0.f;
+    // d is a multiple of 32: 8 elements (16 bytes in, 32 out) per thread and iteration
+    float4 *dst = reinterpret_cast<float4 *>(x + (int64_t)row * d);
+#pragma unroll 4
+    for (int i8 = threadIdx.x; i8 < (d >> 3); i8 += blockDim.x) {
+        const uint4 q = src ? reinterpret_cast<const uint4 *>(src)[i8] : make_uint4(0, 0, 0, 0);
+        dst[2 * i8] = make_float4(__uint_as_float(q.x << 16), __uint_as_float(q.x & 0xFFFF0000u),
+                                  __uint_as_float(q.y << 16), __uint_as_float(q.y & 0xFFFF0000u));
+        dst[2 * i8 + 1] = make_float4(__uint_as_float(q.z << 16), __uint_as_float(q.z & 0xFFFF0000u),
+                                      __uint_as_float(q.w << 16), __uint_as_float(q.w & 0xFFFF0000u));
+    }
 }
 
 __device__ __forceinline__ float wave_sum(float v) {
@@ -212,11 +220,23 @@ __global__ __launch_bounds__(SELECT_THREADS) void select_kernel(const float *__r
     const float4 *row = reinterpret_cast<const float4 *>(logits + ((int64_t)b * t.rows + r) * vocab);   // vocab % 16 == 0
     float prev_v = INFINITY;
     int prev_i = -1;
+    // A row of up to 32768 logits is fetched once (8 independent 16-byte loads per thread) and
+    // stays in registers for all k passes; longer rows are re-read from L2 pass by pass.
+    constexpr int CACHE = 8;
+    const int n4 = vocab >> 2;
+    const bool cached = n4 <= CACHE * SELECT_THREADS;
+    float4 cq[CACHE];
+    if (cached) {
+#pragma unroll
+        for (int j = 0; j < CACHE; j++) {
+            const int i4 = threadIdx.x + j * SELECT_THREADS;
+            cq[j] = row[min(i4, n4 - 1)];                  // (slots past the row are skipped below)
+        }
+    }
     for (int p = 0; p < k; p++) {
         float bv = -INFINITY;
         int bi = 0x7FFFFFFF;
-        for (int i4 = threadIdx.x; i4 < (vocab >> 2); i4 += SELECT_THREADS) {
-            const float4 q = row[i4];
+        auto scan = [&](const float4 &q, int i4) __attribute__((always_inline)) {
             const float v[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
             for (int e = 0; e < 4; e++) {
@@ -224,6 +244,15 @@ __global__ __launch_bounds__(SELECT_THREADS) void select_kernel(const float *__r
                 const bool after_prev = (p == 0) || v[e] < prev_v || (v[e] == prev_v && i > prev_i);
                 if (after_prev && better(v[e], i, bv, bi)) { bv = v[e]; bi = i; }
             }
+        };
+        if (cached) {
+#pragma unroll
+            for (int j = 0; j < CACHE; j++) {
+                const int i4 = threadIdx.x + j * SELECT_THREADS;
+                if (i4 < n4) scan(cq[j], i4);
+            }
+        } else {
+            for (int i4 = threadIdx.x; i4 < n4; i4 += SELECT_THREADS) scan(row[i4], i4);
         }
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) {
