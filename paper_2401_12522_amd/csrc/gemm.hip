@@ -94,7 +94,8 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
     constexpr int WN = C::WN;
     extern __shared__ __attribute__((aligned(16))) uint4 smem_u4[];   // [KG][D][NFRAG][64] + dump slot
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, and known to be: addresses on the scalar unit
     const int kg = wave / WN, wn = wave % WN;                  // k group, position along N
     const int t0 = (blockIdx.x * WN + wn) * NW;
     // the workgroup's k range, cut into KG contiguous parts of equal stage count
@@ -120,6 +121,11 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
     // Issue all loads of pipeline stage `stage` into ring slot SLOT: NW*KC weight fragments to
     // registers and this wave's FPW activation fragments to LDS.  Every wave issues exactly
     // C::LOADS vector-memory operations, which is what the vmcnt waits below count on.
+    // Every address is valid and computed without a select (all terms are wave-uniform but the
+    // lane's 16 bytes): tiles past the matrix, k-steps past the group's range, m-tiles past the
+    // slab and the padding fetches re-read the nearest existing fragment.  What they bring is
+    // either never multiplied (k-steps: see compute) or lands in accumulators that are never
+    // stored (rows and columns beyond the output).
     auto issue = [&](auto slot_c, int stage) {
         constexpr int SLOT = decltype(slot_c)::value;
         const int ks0 = ks_begin + stage * KC;
@@ -127,20 +133,18 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
         for (int j = 0; j < NW; j++)
 #pragma unroll
             for (int s = 0; s < KC; s++) {
-                const int t = t0 + j, ks = ks0 + s;
-                const bool ok = (t < NT) && (ks < ks_end);
-                const uint4 *p = ok ? Wp + packed_block(t, ks, NT) * 64 + lane : &g_zero16;
-                w[SLOT][j][s] = *p;
+                const int t = min(t0 + j, NT - 1), ks = min(ks0 + s, KS - 1);
+                w[SLOT][j][s] = Wp[packed_block(t, ks, NT) * 64 + lane];
             }
 #pragma unroll
         for (int i = 0; i < C::FPW; i++) {
             const int f = i * WN + wn;                            // fragment id inside the stage
-            const int plane = f / (MT * KC), mt = (f / KC) % MT, s = f % KC;
-            const int mtg = blockIdx.z * MT + mt;                 // m-tile in the whole slab
-            const bool ok = (f < C::NFRAG) && (mtg < m_tiles) && (ks0 + s < ks_end);
+            const int fc = min(f, C::NFRAG - 1);
+            const int plane = fc / (MT * KC), mt = (fc / KC) % MT, s = fc % KC;
+            const int mtg = min((int)blockIdx.z * MT + mt, m_tiles - 1);   // m-tile in the whole slab
+            const int ks = min(ks0 + s, KS - 1);
             // fragment (plane, ks, mtg) starts at ((plane * KS + ks) * m_tiles + mtg) * 64 uint4
-            const uint4 *src = ok ? A_frag + ((int64_t)plane * planes_stride_f + (int64_t)(ks0 + s) * m_tiles + mtg) * 64 + lane
-                                  : &g_zero16;
+            const uint4 *src = A_frag + ((int64_t)plane * planes_stride_f + (int64_t)ks * m_tiles + mtg) * 64 + lane;
             uint4 *dst = f < C::NFRAG ? a_lds + (SLOT * C::NFRAG + f) * 64 : dump;   // wave-uniform; lane l lands at dst[l]
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
                                              (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
@@ -148,20 +152,28 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
     };
     auto compute = [&](auto slot_c, int stage) {
         constexpr int SLOT = decltype(slot_c)::value;
-        (void)stage;
 #pragma unroll
-        for (int s = 0; s < KC; s++) {          // k-steps past the end were loaded as zeros
+        for (int s = 0; s < KC; s++) {
+            // a k group whose share of the range is shorter than the others' skips the k-steps
+            // past its end (wave-uniform)
+            if (ks_begin + stage * KC + s >= ks_end) continue;
+            // all LDS reads of the k-step are issued before its first MFMA (left alone, the
+            // scheduler reads one fragment, waits, multiplies twice, reads the next)
+            bf16x8 a[C::PL * MT];
 #pragma unroll
             for (int pl = 0; pl < C::PL; pl++)
 #pragma unroll
-                for (int i = 0; i < MT; i++) {
-                    const int f = (pl * MT + i) * KC + s;
-                    const bf16x8 a = __builtin_bit_cast(bf16x8, a_lds[(SLOT * C::NFRAG + f) * 64 + lane]);
+                for (int i = 0; i < MT; i++)
+                    a[pl * MT + i] = __builtin_bit_cast(bf16x8, a_lds[(SLOT * C::NFRAG + (pl * MT + i) * KC + s) * 64 + lane]);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int pl = 0; pl < C::PL; pl++)
+#pragma unroll
+                for (int i = 0; i < MT; i++)
 #pragma unroll
                     for (int j = 0; j < NW; j++)
                         acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                            a, __builtin_bit_cast(bf16x8, w[SLOT][j][s]), acc[i][j], 0, 0, 0);
-                }
+                            a[pl * MT + i], __builtin_bit_cast(bf16x8, w[SLOT][j][s]), acc[i][j], 0, 0, 0);
         }
     };
     // One pipeline step for stage c living in slot U: wait for its data (leaving the D-2 newer
