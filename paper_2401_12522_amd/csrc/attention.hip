@@ -317,6 +317,17 @@ __global__ __launch_bounds__(ATT_WAVES * 64) __attribute__((amdgpu_waves_per_eu(
         if (iv == NVI - 1) anc_next = *(const __attribute__((address_space(1))) uint64_t *)a_src;
     };
 
+    // The same two loads for a chunk known to lie wholly inside the cache (all but a handful):
+    // one uniform base per operand, the lane's constant offset, the instruction's constant row.
+    const uint32_t lane_row_bytes = (uint32_t)lane_slot * (HD * 2);
+    auto emit_cache = [&](const unsigned char *kb, const unsigned char *vb, int iv) __attribute__((always_inline)) {
+        const uint32_t row0_bytes = (uint32_t)att_slot_of_row(iv * RPI) * (HD * 2);      // compile-time per iv
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gptr)(kb + (lane_row_bytes + k_gran[iv & 3] + row0_bytes)),
+                                         (__attribute__((address_space(3))) void *)(v_ring + iv * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gptr)(vb + (lane_row_bytes + v_gran[iv & 1] + row0_bytes)),
+                                         (__attribute__((address_space(3))) void *)(v_ring + C::KV_BYTES + iv * 1024), 16, 0, 0);
+    };
+
     // One chunk.  Its K and V fragments are all pulled into registers first, which frees the
     // wave's LDS buffer: the next chunk's loads are issued into it right away, interleaved
     // with the QK^T matrix instructions, and have the rest of the step to land.
@@ -342,18 +353,36 @@ __global__ __launch_bounds__(ATT_WAVES * 64) __attribute__((amdgpu_waves_per_eu(
 #pragma unroll
         for (int u = 0; u < U; u++) s_acc[u][0] = s_acc[u][1] = f32x4{0.f, 0.f, 0.f, 0.f};
         static_assert(NVI == 2 * KSN, "one (k-step, sub-tile) pair per load slot");
-#pragma unroll
-        for (int iv = 0; iv < NVI; iv++) {
+        auto qk = [&](int iv) __attribute__((always_inline)) {
             const int ks = iv >> 1, tt = iv & 1;
-            if (more) emit(i + 1, iv);
-            __builtin_amdgcn_sched_barrier(0);
             const bf16x8 ka = __builtin_bit_cast(bf16x8, kf[tt][ks]);
 #pragma unroll
             for (int u = 0; u < U; u++) {
                 s_acc[u][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qf[u][0][ks], s_acc[u][tt], 0, 0, 0);
                 s_acc[u][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qf[u][1][ks], s_acc[u][tt], 0, 0, 0);
             }
-            __builtin_amdgcn_sched_barrier(0);
+        };
+        const int base_n = base + ATT_WAVES * ATT_CHUNK;                 // the wave's next chunk
+        // (with two heads per workgroup the second code path costs registers the kernel does not have)
+        if (U == 1 && more && base_n >= P && base_n + ATT_CHUNK <= n_ctx_keys) {   // wave-uniform
+            const unsigned char *kb = reinterpret_cast<const unsigned char *>(ck) + (int64_t)(base_n - P) * (HD * 2);
+            const unsigned char *vb = reinterpret_cast<const unsigned char *>(cv) + (int64_t)(base_n - P) * (HD * 2);
+#pragma unroll
+            for (int iv = 0; iv < NVI; iv++) {
+                emit_cache(kb, vb, iv);
+                __builtin_amdgcn_sched_barrier(0);
+                qk(iv);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            anc_next = 0;
+        } else {
+#pragma unroll
+            for (int iv = 0; iv < NVI; iv++) {
+                if (more) emit(i + 1, iv);
+                __builtin_amdgcn_sched_barrier(0);
+                qk(iv);
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
         // the visibility of a key depends on the row and the key only: one mask word for all heads
         const bool need_mask = tree_chunk || (base < P) || (base + ATT_CHUNK > n_ctx_keys);
