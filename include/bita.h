@@ -209,6 +209,16 @@ int bita_tree_attention(const bita_tree_template *t, const void *d_q, const void
                         int32_t n_kv_heads, int32_t head_dim, int32_t n_prompt, int32_t smax,
                         int32_t ctx_hint, void *d_ws, size_t ws_bytes, void *d_out, void *stream);
 
+/* Selection alone (the last kernel of bita_verify_step; Sec. 3.3: the greedy token of every
+ * draft row and the top-kmax candidates of every mask row), for kernel-level tests.
+ * d_logits [B][R][vocab] fp32 (device, finite values; -0 counts as +0).  d_argmax [B][T]:
+ * index of the largest logit of each of the T tree rows, the lowest index among equal
+ * values.  d_topk_ids / d_topk_val [B][G*n][kmax] (device, both optional): the kmax
+ * largest logits of every mask row in the same order (value descending, lower index first
+ * among equals).  vocab must be a multiple of 16.  Returns BITA_OK or an error code. */
+int bita_select(const bita_tree_template *t, const float *d_logits, int32_t batch, int32_t vocab,
+                int32_t kmax, int32_t *d_argmax, int32_t *d_topk_ids, float *d_topk_val, void *stream);
+
 /* Skinny GEMM alone: d_out[M][N] (fp32) = A[M][K] times the packed [N][K] matrix
  * transposed.  A = d_a (bf16, row stride lda) plus, if d_a_lo is not NULL, a second bf16
  * plane of the same shape holding the rounding residual (A = hi + lo), which is how

@@ -16,7 +16,7 @@ EXPORTS = [
     "bita_workspace_bytes", "bita_tree_template_create", "bita_tree_template_destroy",
     "bita_tree_template_info", "bita_build_tree", "bita_verify_step", "bita_accept",
     "bita_compact_kv", "bita_attention_workspace_bytes", "bita_tree_attention",
-    "bita_gemm_workspace_bytes", "bita_gemm", "bita_tune_gemm", "bita_profile_enable",
+    "bita_gemm_workspace_bytes", "bita_gemm", "bita_select", "bita_tune_gemm", "bita_profile_enable",
     "bita_profile_disable", "bita_profile_read", "bita_last_error",
 ]
 
@@ -78,6 +78,7 @@ def lib():
     L.bita_tree_attention.argtypes = [vp] * 12 + [i32] * 7 + [vp, sz, vp, vp]
     L.bita_gemm_workspace_bytes.restype, L.bita_gemm_workspace_bytes.argtypes = sz, [i32, i64, i64]
     L.bita_gemm.restype, L.bita_gemm.argtypes = C.c_int, [vp, vp, i32, i64, i64, vp, i64, vp, sz, vp, vp]
+    L.bita_select.restype, L.bita_select.argtypes = C.c_int, [vp, vp, i32, i32, i32, vp, vp, vp, vp]
     L.bita_tune_gemm.restype, L.bita_tune_gemm.argtypes = None, [i32, i32]
     L.bita_profile_enable.restype, L.bita_profile_enable.argtypes = C.c_int, [i32]
     L.bita_profile_disable.restype, L.bita_profile_disable.argtypes = None, []
@@ -317,6 +318,18 @@ def gemm(a, w_packed, n_rows, k=None, a_lo=None):
     out = torch.empty((m, n_rows), dtype=torch.float32, device=a.device)
     _check(lib().bita_gemm(_ptr(a), _ptr(a_lo), m, k, lda, _ptr(w_packed), n_rows, _ptr(ws), ws.numel(), _ptr(out), _stream()))
     return out
+
+
+def select(tmpl, logits, kmax):
+    """logits fp32 cuda [B][R][vocab] -> (argmax int32 [B][T], topk_ids int32 [B][G*n][kmax], topk_val fp32)."""
+    B, R, V = logits.shape
+    assert R == tmpl.rows and logits.dtype == torch.float32 and logits.is_contiguous()
+    argmax = torch.empty((B, tmpl.n_tree), dtype=torch.int32, device=logits.device)
+    n_sel = tmpl.n_groups * tmpl.n_mask
+    ids = torch.empty((B, n_sel, kmax), dtype=torch.int32, device=logits.device)
+    val = torch.empty((B, n_sel, kmax), dtype=torch.float32, device=logits.device)
+    _check(lib().bita_select(tmpl.handle, _ptr(logits), B, V, kmax, _ptr(argmax), _ptr(ids), _ptr(val), _stream()))
+    return argmax, ids, val
 
 
 def tree_attention(tmpl, q, k_cache, v_cache, k_tree, v_tree, prompt_k, prompt_v, ctx_len, ctx_hint, q_lo=None,

@@ -432,6 +432,18 @@ extern "C" int bita_tree_attention(const bita_tree_template *t, const void *d_q,
     return BITA_OK;
 }
 
+extern "C" int bita_select(const bita_tree_template *t, const float *d_logits, int32_t batch, int32_t vocab,
+                           int32_t kmax, int32_t *d_argmax, int32_t *d_topk_ids, float *d_topk_val, void *stream) {
+    if (!t || !d_logits || !d_argmax || batch <= 0 || vocab <= 0)
+        return bita_set_error(BITA_ERR_INVALID_ARG, "bita_select: bad argument");
+    if (vocab % 16) return bita_set_error(BITA_ERR_UNSUPPORTED, "bita_select: vocab must be a multiple of 16");
+    if (d_topk_ids && (kmax <= 0 || kmax > BITA_MAX_TOPK || kmax > vocab))
+        return bita_set_error(BITA_ERR_INVALID_ARG, "bita_select: kmax must be in 1..%d", BITA_MAX_TOPK);
+    launch_select(d_logits, batch, t->dev, vocab, kmax, d_argmax, d_topk_ids, d_topk_val, (hipStream_t)stream);
+    BITA_HIP_CHECK(hipGetLastError());
+    return BITA_OK;
+}
+
 extern "C" void bita_tune_gemm(int32_t variant, int32_t splits) { gemm_force_plan(variant, splits); }
 
 extern "C" size_t bita_gemm_workspace_bytes(int32_t m_rows, int64_t n_rows, int64_t k) {

@@ -200,9 +200,18 @@ __global__ void silu_mul_kernel(const float *__restrict__ partial, int splits, i
 // the previous winner in that order, so k passes give the sorted top-k and pass 0 alone
 // is the greedy argmax.  Reductions: per-lane scan (16-byte loads), wave shuffles, then the
 // workgroup's 16 waves via LDS.
-struct Cand { float v; int i; };
-__device__ __forceinline__ bool better(float v, int i, float bv, int bi) {
-    return v > bv || (v == bv && i < bi);
+// (value, index) as one unsigned 64-bit key whose order is "larger value first, lower index on
+// equal values": the float's bits made monotone (sign flip for positives, complement for
+// negatives; -0 is first turned into +0) above the complemented index.  Logits are finite.
+__device__ __forceinline__ unsigned long long select_key(float v, int i) {
+    uint32_t u = __float_as_uint(v + 0.0f);
+    u ^= (u & 0x80000000u) ? 0xFFFFFFFFu : 0x80000000u;
+    return ((unsigned long long)u << 32) | (uint32_t)(0x7FFFFFFF - i);
+}
+__device__ __forceinline__ float select_key_value(unsigned long long k) {
+    uint32_t u = (uint32_t)(k >> 32);
+    u ^= (u & 0x80000000u) ? 0x80000000u : 0xFFFFFFFFu;
+    return __uint_as_float(u);
 }
 #define SELECT_THREADS 1024
 __global__ __launch_bounds__(SELECT_THREADS) void select_kernel(const float *__restrict__ logits, TemplateDev t,
@@ -210,16 +219,13 @@ __global__ __launch_bounds__(SELECT_THREADS) void select_kernel(const float *__r
                                                                 int32_t *__restrict__ topk_ids,
                                                                 float *__restrict__ topk_val) {
     constexpr int NW = SELECT_THREADS / 64;
-    __shared__ float sv[NW];
-    __shared__ int si[NW];
+    __shared__ unsigned long long sk[NW];
     const int b = blockIdx.y;
     const int sel = blockIdx.x;                       // 0..T-1 tree rows, then G*n mask rows
     const bool is_tree = sel < t.n_tree;
     const int r = is_tree ? sel : t.mask_rows[sel - t.n_tree];
     const int k = is_tree ? 1 : kmax;
     const float4 *row = reinterpret_cast<const float4 *>(logits + ((int64_t)b * t.rows + r) * vocab);   // vocab % 16 == 0
-    float prev_v = INFINITY;
-    int prev_i = -1;
     // A row of up to 32768 logits is fetched once (8 independent 16-byte loads per thread) and
     // stays in registers for all k passes; longer rows are re-read from L2 pass by pass.
     constexpr int CACHE = 8;
@@ -233,16 +239,15 @@ __global__ __launch_bounds__(SELECT_THREADS) void select_kernel(const float *__r
             cq[j] = row[min(i4, n4 - 1)];                  // (slots past the row are skipped below)
         }
     }
+    unsigned long long prev = ~0ull;                      // pass p selects the largest key below pass p-1's
     for (int p = 0; p < k; p++) {
-        float bv = -INFINITY;
-        int bi = 0x7FFFFFFF;
+        unsigned long long best = 0;                      // below every real key (indices are < 2^31 - 1)
         auto scan = [&](const float4 &q, int i4) __attribute__((always_inline)) {
             const float v[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
             for (int e = 0; e < 4; e++) {
-                const int i = 4 * i4 + e;
-                const bool after_prev = (p == 0) || v[e] < prev_v || (v[e] == prev_v && i > prev_i);
-                if (after_prev && better(v[e], i, bv, bi)) { bv = v[e]; bi = i; }
+                const unsigned long long key = select_key(v[e], 4 * i4 + e);
+                best = (key < prev && key > best) ? key : best;
             }
         };
         if (cached) {
@@ -256,25 +261,24 @@ __global__ __launch_bounds__(SELECT_THREADS) void select_kernel(const float *__r
         }
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) {
-            const float ov = __shfl_xor(bv, o, 64);
-            const int oi = __shfl_xor(bi, o, 64);
-            if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+            const unsigned long long other = __shfl_xor(best, o, 64);
+            best = other > best ? other : best;
         }
-        if ((threadIdx.x & 63) == 0) { sv[threadIdx.x >> 6] = bv; si[threadIdx.x >> 6] = bi; }
+        if ((threadIdx.x & 63) == 0) sk[threadIdx.x >> 6] = best;
         __syncthreads();
-        bv = sv[0]; bi = si[0];
+        best = sk[0];
 #pragma unroll
-        for (int w = 1; w < NW; w++)
-            if (better(sv[w], si[w], bv, bi)) { bv = sv[w]; bi = si[w]; }
+        for (int w = 1; w < NW; w++) best = sk[w] > best ? sk[w] : best;
         __syncthreads();
-        prev_v = bv; prev_i = bi;
+        prev = best;
         if (threadIdx.x == 0) {
+            const int bi = 0x7FFFFFFF - (int)(uint32_t)(best & 0xFFFFFFFFu);
             if (is_tree) {
                 argmax[b * t.n_tree + sel] = bi;
             } else {
                 const int64_t o = ((int64_t)b * (t.n_groups * t.n_mask) + (sel - t.n_tree)) * kmax + p;
                 topk_ids[o] = bi;
-                if (topk_val) topk_val[o] = bv;
+                if (topk_val) topk_val[o] = select_key_value(best);
             }
         }
     }

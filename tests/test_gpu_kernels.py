@@ -132,6 +132,44 @@ def test_tree_attention_chain_equals_causal(bita):
     assert err < ATT_TOL, err
 
 
+def test_select_orders_equal_values_by_index(bita):
+    """Selection alone on crafted logits: runs of equal maxima, equal values across the 16-byte
+    and thread strides, +0 / -0, negative-only rows, very large and very small magnitudes.
+    Greedy index and sorted top-k must equal the oracle's (value descending, lower id first)."""
+    from oracle.model import argmax_low, topk_desc
+    n_mask, kmax, V = 4, 6, 32000
+    par = synth.full_branching_tree([2, 2], 7)
+    tin = synth.attach_mask_groups(par, [0], n_mask)
+    tmpl = bita.TreeTemplate(tin.parent, tin.is_mask, tin.n_tree, n_mask)
+    R = tin.rows
+    rng = np.random.default_rng(12)
+    lg = rng.normal(size=(2, R, V)).astype(np.float32)
+    lg[0, 0, [5, 4099, 31999]] = 9.0                      # three equal maxima, far apart
+    lg[0, 1, :] = -3.5                                    # a constant row
+    lg[0, 2, :] = -np.abs(lg[0, 2, :]) - 1.0              # all negative ...
+    lg[0, 2, [17, 16]] = -0.25                            # ... with an equal pair as maximum
+    lg[0, 3, :] = -1.0
+    lg[0, 3, 777] = -0.0                                  # -0 and +0 are one value: the lower id wins
+    lg[0, 3, 20000] = 0.0
+    lg[0, 4, :] = 1e-30 * rng.normal(size=V)              # tiny magnitudes of both signs
+    lg[0, 5, [1, 2, 3]] = [3e38, -3e38, 3e38]             # near the float range
+    for r in range(tin.n_tree, R):                        # mask rows: ties inside and across the top-k
+        lg[1, r, :] = np.round(lg[1, r, :] * 2) / 2       # many equal values
+        lg[1, r, [31990 - r, 8, 4104]] = 40.0
+    dev = torch.tensor(lg, device="cuda")
+    am, ids, val = bita.select(tmpl, dev, kmax)
+    torch.cuda.synchronize()
+    am, ids, val = am.cpu().numpy(), ids.cpu().numpy(), val.cpu().numpy()
+    d = derive_template(tin.parent, tin.is_mask, n_mask)
+    for b in range(2):
+        for r in range(d.T):
+            assert am[b, r] == argmax_low(lg[b, r].astype(np.float64)), (b, r)
+        for j, r in enumerate(range(d.T, R)):
+            ref_ids, ref_val = topk_desc(lg[b, r].astype(np.float64), kmax)
+            assert ids[b, j].tolist() == list(ref_ids), (b, r)
+            assert np.array_equal(val[b, j].astype(np.float64) + 0.0, np.asarray(ref_val) + 0.0), (b, r)
+
+
 def test_integer_kernels_match_oracle(bita):
     rng = np.random.default_rng(0)
     for trial in range(40):
