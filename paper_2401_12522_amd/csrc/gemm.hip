@@ -134,7 +134,9 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
 #pragma unroll
             for (int s = 0; s < KC; s++) {
                 const int t = min(t0 + j, NT - 1), ks = min(ks0 + s, KS - 1);
-                w[SLOT][j][s] = Wp[packed_block(t, ks, NT) * 64 + lane];
+                typedef uint32_t __attribute__((ext_vector_type(4))) u32x4_t;
+                const u32x4_t q = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(Wp + packed_block(t, ks, NT) * 64 + lane));
+                w[SLOT][j][s] = make_uint4(q.x, q.y, q.z, q.w);
             }
 #pragma unroll
         for (int i = 0; i < C::FPW; i++) {
