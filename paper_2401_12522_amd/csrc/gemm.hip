@@ -56,6 +56,23 @@ __device__ __forceinline__ void wg_barrier() {
     asm volatile("" ::: "memory");
 }
 
+// LDS reads of activation fragments as bare instructions with their own staged waits: the
+// k-step's reads are all issued up front and each MFMA group waits only for the fragment it
+// uses (the compiler's own placement was one wait for all of them).  lgkmcnt counts this
+// wave's outstanding LDS reads, which return in order.
+template <int OFFSET>
+__device__ __forceinline__ bf16x8 lds_read_frag(uint32_t lds_addr) {
+    static_assert(OFFSET >= 0 && OFFSET < 65536, "ds offset field");
+    bf16x8 v;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(lds_addr), "n"(OFFSET));
+    return v;
+}
+template <int OUTSTANDING>
+__device__ __forceinline__ void lds_wait_frag(bf16x8 &a) {
+    static_assert(OUTSTANDING >= 0 && OUTSTANDING < 16, "lgkmcnt range");
+    asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(a) : "n"(OUTSTANDING));
+}
+
 template <int I, int N, typename F>
 __device__ __forceinline__ void static_for(F &&f) {
     if constexpr (I < N) {
@@ -117,6 +134,8 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
         for (int j = 0; j < NW; j++) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     uint4 w[D][NW][KC];
+    // byte address in LDS of this lane's 16 bytes of the k group's fragment 0
+    const uint32_t lds_lane_base = (uint32_t)(size_t)((__attribute__((address_space(3))) uint4 *)a_lds) + lane * 16;
 
     // Issue all loads of pipeline stage `stage` into ring slot SLOT: NW*KC weight fragments to
     // registers and this wave's FPW activation fragments to LDS.  Every wave issues exactly
@@ -159,23 +178,24 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
             // a k group whose share of the range is shorter than the others' skips the k-steps
             // past its end (wave-uniform)
             if (ks_begin + stage * KC + s >= ks_end) continue;
-            // all LDS reads of the k-step are issued before its first MFMA (left alone, the
-            // scheduler reads one fragment, waits, multiplies twice, reads the next)
-            bf16x8 a[C::PL * MT];
+            // all LDS reads of the k-step are issued before its first MFMA; fragment f is
+            // waited for with the NF-1-f later reads still in flight
+            constexpr int NF = C::PL * MT;
+            static_assert(NF <= 16, "lgkmcnt range");
+            bf16x8 a[NF];
+            static_for<0, NF>([&](auto f_c) {
+                constexpr int F = decltype(f_c)::value;
+                a[F] = lds_read_frag<((SLOT * C::NFRAG + F * KC) * 64) * 16>(lds_lane_base + s * 1024);
+            });
+            static_for<0, NF>([&](auto f_c) {
+                constexpr int F = decltype(f_c)::value, i = F % MT;
+                lds_wait_frag<NF - 1 - F>(a[F]);
 #pragma unroll
-            for (int pl = 0; pl < C::PL; pl++)
-#pragma unroll
-                for (int i = 0; i < MT; i++)
-                    a[pl * MT + i] = __builtin_bit_cast(bf16x8, a_lds[(SLOT * C::NFRAG + (pl * MT + i) * KC + s) * 64 + lane]);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int pl = 0; pl < C::PL; pl++)
-#pragma unroll
-                for (int i = 0; i < MT; i++)
-#pragma unroll
-                    for (int j = 0; j < NW; j++)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                            a[pl * MT + i], __builtin_bit_cast(bf16x8, w[SLOT][j][s]), acc[i][j], 0, 0, 0);
+                for (int j = 0; j < NW; j++)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                        a[F], __builtin_bit_cast(bf16x8, w[SLOT][j][s]), acc[i][j], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);          // keeps the next fragment's wait behind these MFMAs
+            });
         }
     };
     // One pipeline step for stage c living in slot U: wait for its data (leaving the D-2 newer
