@@ -204,19 +204,35 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
     // (those read the zero granule), so the wait count is a compile-time constant and the
     // compiler's own wait-count analysis sees every register dependency satisfied by it; with
     // data-dependent counts it drains the whole ring at the loop head instead.
-    auto step = [&](auto u_c, int c) {
-        constexpr int U = decltype(u_c)::value;
-        constexpr int PRE = (U + D - 1) % D;
-        wait_vmcnt_lds<(D - 2) * C::LOADS>();
-        wg_barrier();
-        issue(std::integral_constant<int, PRE>{}, c + D - 1);
-        compute(u_c, c);
+    // The k groups take the two halves of a step in opposite order: behind the barrier one
+    // group queues its loads on the vector-memory path while the other is on LDS and the
+    // matrix cores (waves of different groups share a SIMD), then they swap.  Two copies of the
+    // loop, chosen once per wave: with both orders inside one body the compiler's wait-count
+    // analysis loses track at the join and drains the ring (vmcnt(0)) before every multiply.
+    auto main_loop = [&](auto multiply_first_c) __attribute__((always_inline)) {
+        constexpr bool MULTIPLY_FIRST = decltype(multiply_first_c)::value;
+        int c = 0;
+        for (; c + D <= n_stages; c += D)        // branch-free body: D steps, slots 0..D-1
+            static_for<0, D>([&](auto u_c) {
+                constexpr int U = decltype(u_c)::value;
+                constexpr int PRE = (U + D - 1) % D;
+                wait_vmcnt_lds<(D - 2) * C::LOADS>();
+                wg_barrier();
+                if constexpr (MULTIPLY_FIRST) {
+                    compute(u_c, c + U);
+                    issue(std::integral_constant<int, PRE>{}, c + U + D - 1);
+                } else {
+                    issue(std::integral_constant<int, PRE>{}, c + U + D - 1);
+                    compute(u_c, c + U);
+                }
+            });
+        return c;
     };
 
     static_for<0, D - 1>([&](auto u_c) { issue(u_c, decltype(u_c)::value); });
-    int c = 0;
-    for (; c + D <= n_stages; c += D)            // branch-free body: D steps, slots 0..D-1
-        static_for<0, D>([&](auto u_c) { step(u_c, c + decltype(u_c)::value); });
+    int c;
+    if (KG > 1 && (kg & 1)) c = main_loop(std::true_type{});
+    else c = main_loop(std::false_type{});
     // Remaining n_stages % D steps: nothing more to fetch.  Stages c .. c+D-2 were issued by the
     // loop above (or the prologue) with C::LOADS loads each, so step U leaves D-2-U stages in
     // flight.  (Issuing dummy loads here instead would not keep the count: the compiler drops
