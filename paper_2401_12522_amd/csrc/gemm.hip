@@ -114,14 +114,36 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, and known to be: addresses on the scalar unit
     const int kg = wave / WN, wn = wave % WN;                  // k group, position along N
-    const int t0 = (blockIdx.x * WN + wn) * NW;
+    // (column group, k split, row pass) of this workgroup.  With several row passes (more rows
+    // than one pass holds) the passes over the same weights are made neighbours on one XCD:
+    // dispatch index L goes to XCD L % 8, so the passes of a (column group, split) pair take
+    // indices 8 apart and run side by side on that XCD, the later ones finding the weight
+    // blocks in its L2 instead of fetching them again.
+    int bx = blockIdx.x, by = blockIdx.y, bz = blockIdx.z;
+    if (gridDim.z > 1) {
+        const int X = gridDim.x, Z = gridDim.z, T = X * (int)gridDim.y, Tb = T & ~7;
+        const int L = bx + X * (by + (int)gridDim.y * bz);
+        int pair;
+        if (L < Tb * Z) {
+            const int q = L >> 3;
+            bz = q % Z;
+            pair = (q / Z) * 8 + (L & 7);
+        } else {                                               // the last T % 8 pairs, pass-major
+            const int r = L - Tb * Z;
+            bz = r % Z;
+            pair = Tb + r / Z;
+        }
+        bx = pair % X;
+        by = pair / X;
+    }
+    const int t0 = (bx * WN + wn) * NW;
     // the workgroup's k range, cut into KG contiguous parts of equal stage count
-    const int wg_begin = blockIdx.y * ksteps_per_split;
+    const int wg_begin = by * ksteps_per_split;
     const int wg_end = min(KS, wg_begin + ksteps_per_split);
     const int per_group = (wg_end - wg_begin + KG - 1) / KG;
     const int ks_begin = wg_begin + kg * per_group;
     const int ks_end = min(wg_end, ks_begin + per_group);
-    const int m_base = blockIdx.z * (MT * 16);
+    const int m_base = bz * (MT * 16);
     const int n_stages = (per_group + KC - 1) / KC;            // same for every wave: barriers in lockstep
     uint4 *a_lds = smem_u4 + kg * (D * C::NFRAG * 64);         // this k group's ring
     uint4 *dump = smem_u4 + KG * D * C::NFRAG * 64;            // target of padding fetches
@@ -162,7 +184,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
             const int f = i * WN + wn;                            // fragment id inside the stage
             const int fc = min(f, C::NFRAG - 1);
             const int plane = fc / (MT * KC), mt = (fc / KC) % MT, s = fc % KC;
-            const int mtg = min((int)blockIdx.z * MT + mt, m_tiles - 1);   // m-tile in the whole slab
+            const int mtg = min(bz * MT + mt, m_tiles - 1);   // m-tile in the whole slab
             const int ks = min(ks0 + s, KS - 1);
             // fragment (plane, ks, mtg) starts at ((plane * KS + ks) * m_tiles + mtg) * 64 uint4
             const uint4 *src = A_frag + ((int64_t)plane * planes_stride_f + (int64_t)ks * m_tiles + mtg) * 64 + lane;
@@ -368,7 +390,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
             // fragment (plane, ks, mt) of the slab starts at ((plane * n_ksteps + ks) * mt_all + mt) KiB;
             // k-steps at or beyond n_ksteps and m-tiles beyond the slab do not exist.
             // One store instruction moves two halves (32 lanes x 16 bytes each).
-            const int hk0 = blockIdx.x * HK, mt0 = blockIdx.z * MT, half_lane = lane >> 5, l32 = lane & 31;
+            const int hk0 = bx * HK, mt0 = bz * MT, half_lane = lane >> 5, l32 = lane & 31;
             for (int pr = wn; pr < HK * MT * 2 / 2; pr += WN) {
                 const int idx = pr * 2 + half_lane;                      // (plane, hk, i) flattened, as staged
                 const int plane = idx / (HK * MT), hk = (idx / MT) % HK, i = idx % MT;
@@ -381,7 +403,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
         }
         return;
     }
-    store_tiles(out + (int64_t)blockIdx.y * M * ldo, [&](int i, int j, int r) { return acc[i][j][r]; });
+    store_tiles(out + (int64_t)by * M * ldo, [&](int i, int j, int r) { return acc[i][j][r]; });
 }
 
 // out[m][n] = rowscale(m) * sum over splits of partial[s][m][n], in split order
