@@ -136,6 +136,23 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
         bx = pair % X;
         by = pair / X;
     }
+    else if (gridDim.y > 1) {
+        // Split-K launch: workgroups of one k split read the same k range of the activation
+        // slab.  With a power-of-two number of splits each split is given to its own XCD(s), so
+        // that every k range is fetched into one L2 (or few) instead of all eight.
+        const int X = gridDim.x, Y = gridDim.y, L = bx + X * by;
+        if ((Y & (Y - 1)) == 0 && ((X * Y) & 7) == 0) {
+            if (Y >= 8) {
+                const int per = Y >> 3;                        // splits per XCD
+                by = (L & 7) + 8 * ((L >> 3) % per);
+                bx = (L >> 3) / per;
+            } else {
+                const int per = 8 / Y;                         // XCDs per split
+                by = (L & 7) / per;
+                bx = (L >> 3) * per + (L & 7) % per;
+            }
+        }
+    }
     const int t0 = (bx * WN + wn) * NW;
     // the workgroup's k range, cut into KG contiguous parts of equal stage count
     const int wg_begin = by * ksteps_per_split;
