@@ -29,7 +29,7 @@ HBM_PEAK_GBPS = 8000.0
 # HBM-side bytes (fetch + write) per GEMM launch, averaged over the launches of one step, from the
 # FETCH_SIZE / WRITE_SIZE counter runs scaled by a copy kernel (profiles/gemm_traffic_7b.md);
 # counters cannot be collected from inside this process, so the figure is carried as a constant
-GEMM_TRAFFIC_BYTES_PER_LAUNCH = {"7b": 125.1e6}
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = {"7b": 120.9e6}
 # layer counts of the two oracle passes timed for cpu_baseline (about 10 s of host work at 7B width)
 CPU_SAMPLE_LAYERS = (4, 8)
 
