@@ -106,27 +106,15 @@ def planted_walk(children, depth_max, n_levels, rng):
 
 
 def prefill(B, model, kv, cfg, ctx_tokens, chunk=64):
-    """Fill the cache with context[:-1] by chain-template passes (a chain is causal attention).
-    ctx_tokens: [n] or [batch][n] (equal lengths)."""
+    """Fill the cache with context[:-1] through the library's prefill entry point (chunked
+    causal passes).  ctx_tokens: [n] or [batch][n] (equal lengths)."""
     import torch
-    import synth
     ctx_tokens = np.atleast_2d(np.asarray(ctx_tokens))
-    nb = ctx_tokens.shape[0]
-    n = ctx_tokens.shape[1] - 1
-    done = 0
-    while done < n:
-        m = min(chunk, n - done)
-        tin = synth.attach_mask_groups(synth.chain_tree(m), [], cfg.n_mask)
-        tmpl = B.TreeTemplate(tin.parent, tin.is_mask, m, cfg.n_mask)
-        kv.resize_rows(model.n_layers, cfg, m)
-        buf = B.StepBuffers(model, tmpl, nb, 1)
-        buf.token.copy_(torch.tensor(ctx_tokens[:, done:done + m], dtype=torch.int32, device="cuda"))
-        B.verify_step(model, kv, done, tmpl, buf, nb)
-        path = torch.arange(m, dtype=torch.int32, device="cuda")[None].repeat(nb, 1).contiguous()
-        n_acc = torch.full((nb,), m, dtype=torch.int32, device="cuda")
-        B.compact_kv(model, kv, done, buf, nb, path=path, n_acc=n_acc)
-        torch.cuda.synchronize()
-        done += m
+    if kv.rows < chunk:
+        kv.resize_rows(model.n_layers, cfg, chunk)
+    toks = torch.tensor(ctx_tokens[:, :-1], dtype=torch.int32, device="cuda").contiguous()
+    B.prefill(model, kv, 0, toks, chunk)
+    torch.cuda.synchronize()
 
 
 def cpu_baseline(cfg, wsrc_np, kv_np, tmpl_in, tokens, ctx_len):

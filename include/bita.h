@@ -10,6 +10,7 @@
  *                     token tree plus mask tokens, under tree-based attention
  *   bita_accept       greedy verification walk (Algorithm 1, inner loops)
  *   bita_compact_kv   commit the accepted rows' K/V to the cache
+ *   bita_prefill      the context's K/V by chunked causal passes
  *
  * Conventions
  *   - Every call returns an int status: BITA_OK or a negative BITA_ERR_* code;
@@ -190,6 +191,33 @@ int bita_accept(const bita_tree_template *t, const int32_t *d_token, const int32
 int bita_compact_kv(const bita_model *m, const bita_kv *kv, const int32_t *d_path,
                     int32_t path_stride, const int32_t *d_n_acc, int32_t *d_ctx_len,
                     int32_t batch, void *stream);
+
+/* Context prefill (Algorithm 1: the pass over the input that precedes the first
+ * draft; Sec. 3.2: ordinary tokens attend causally).  Runs the decoder over the
+ * context in chunks of at most chunk_rows rows; a chunk is a verify pass whose
+ * tree is a chain (row i hangs off row i-1), which is causal attention over
+ * [cache, chunk], followed by committing every row of the chunk to the cache.
+ * Same kernels and arithmetic as bita_verify_step / bita_compact_kv.
+ *   d_tokens     [B][n_tokens]  context tokens, row b valid up to its length
+ *   d_seq_len    [B] or NULL    per-sequence lengths (clamped to 0..n_tokens);
+ *                               NULL = every sequence has n_tokens tokens
+ *   d_ctx_len    [B] in/out     advanced by each sequence's length
+ *   kv           cache as for bita_verify_step; kv->rows is the CAPACITY of the
+ *                tree scratch in rows (>= chunk_rows; each chunk lays it out for
+ *                its own row count), kv->ctx_hint an upper bound of ctx_len on
+ *                entry
+ *   chunk_rows   1..BITA_MAX_ROWS
+ *   d_workspace  bita_prefill_workspace_bytes(m, batch, chunk_rows) bytes
+ *   d_next_token [B] or NULL    greedy token that follows each sequence's last
+ *                               context token (untouched for empty sequences)
+ * Host-synchronous: builds its chain templates, enqueues all chunks on `stream`,
+ * waits for the stream and frees the templates; not for graph capture.
+ * Errors: CAPACITY if ctx_hint + n_tokens exceeds smax or max_pos or the
+ * workspace is too small (checked before anything is enqueued). */
+size_t bita_prefill_workspace_bytes(const bita_model *m, int32_t batch, int32_t chunk_rows);
+int bita_prefill(bita_model *m, const bita_kv *kv, const int32_t *d_tokens, int32_t n_tokens,
+                 const int32_t *d_seq_len, int32_t *d_ctx_len, int32_t batch, int32_t chunk_rows,
+                 void *d_workspace, size_t ws_bytes, int32_t *d_next_token, void *stream);
 
 /* Tree-masked attention alone (the kernel bita_verify_step runs per layer), for
  * kernel-level tests and measurement.  d_q [B][R][n_heads][hd] (already rotated; d_q_lo

@@ -2,4 +2,4 @@
 over libbita.so.  Importing the package does not load the library; the first use does,
 and fails loudly if it has not been built (there is no CPU fallback)."""
 from .binding import (lib, BitaError, Model, TreeTemplate, KVState, StepBuffers,   # noqa: F401
-                      pack_weight, packed_bytes, gemm, tree_attention, select, decode_step)
+                      pack_weight, packed_bytes, gemm, tree_attention, select, decode_step, prefill)

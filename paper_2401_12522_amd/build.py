@@ -6,7 +6,7 @@ import sys
 PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libbita.so")
-SOURCES = ["api.hip", "gemm.hip", "attention.hip", "misc.hip", "tree.hip"]
+SOURCES = ["api.hip", "gemm.hip", "attention.hip", "misc.hip", "tree.hip", "prefill.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -20,12 +20,6 @@ extern "C" const char *bita_last_error(void) { return g_err; }
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // ------------------------------------------------------------------------------------------
-struct bita_model {
-    bita_config cfg;
-    const void *tok_emb, *mask_emb, *final_norm, *lm_head;
-    std::vector<const void *> attn_norm, ffn_norm, wqkv, wo, w_gate_up, w_down, prompt_k, prompt_v;
-    float *rope_cos = nullptr, *rope_sin = nullptr;     // [max_pos][hd/2]
-};
 
 extern "C" size_t bita_packed_bytes(int64_t n_rows, int64_t k) {
     if (n_rows <= 0 || k <= 0) return 0;

@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stddef.h>
+#include <vector>
 #include "../../include/bita.h"
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -57,6 +58,14 @@ struct TemplateDev {
 struct bita_tree_template {
     TemplateDev dev;
     void *blob;                   // one device allocation backing all arrays
+};
+
+// ---- the model handle: borrowed weight pointers plus the rotary table it owns --------
+struct bita_model {
+    bita_config cfg;
+    const void *tok_emb, *mask_emb, *final_norm, *lm_head;
+    std::vector<const void *> attn_norm, ffn_norm, wqkv, wo, w_gate_up, w_down, prompt_k, prompt_v;
+    float *rope_cos = nullptr, *rope_sin = nullptr;     // [max_pos][hd/2]
 };
 
 // ---- kernel launchers (each only enqueues) --------------------------------------

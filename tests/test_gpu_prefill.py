@@ -1,0 +1,121 @@
+"""Context prefill through the C ABI (chunked chain passes) against the oracle's single
+causal pass: committed K/V, context counters and the first greedy token."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth
+from oracle.model import argmax_low
+from gpu_util import dev_i32, read_cache
+
+pytestmark = pytest.mark.gpu
+
+KV_TOL = 3e-2         # same bar as the step tests put on a pass' K/V rows
+MARGIN = 6e-2
+
+
+@pytest.fixture(scope="module")
+def bita():
+    import paper_2401_12522_amd as b
+    b.lib()
+    return b
+
+
+def _oracle_causal(om, toks):
+    """K/V and last-row logits of one causal pass over toks from an empty cache."""
+    cfg = om.cfg
+    n = len(toks)
+    ck = [np.zeros((0, cfg.n_kv_heads, cfg.head_dim)) for _ in range(cfg.n_layers)]
+    cv = [np.zeros((0, cfg.n_kv_heads, cfg.head_dim)) for _ in range(cfg.n_layers)]
+    vis = [list(range(r + 1)) for r in range(n)]
+    logits, k, v = oracle.forward_rows(om, list(toks), [0] * n, [-1] * n, list(range(n)), vis, ck, cv)
+    return k, v, logits[n - 1]
+
+
+def _margin(row):
+    s = np.sort(row)
+    return s[-1] - s[-2]
+
+
+@pytest.mark.parametrize("cfg_name,n_ctx,chunk", [("tiny", 150, 64), ("tiny_gqa", 150, 256), ("tiny_gqa", 97, 17)])
+def test_prefill_chunks_match_one_causal_pass(bita, cfg_name, n_ctx, chunk):
+    cfg = synth.get_config(cfg_name)
+    w = synth.SynthWeights(cfg, seed=3)
+    om = oracle.OracleModel(cfg, w)
+    smax = 256
+    model = bita.Model(cfg, w, max_pos=smax + 64)
+    kv = bita.KVState(cfg, cfg.n_layers, 1, smax, chunk)
+    ctx = synth.random_context(cfg.vocab, n_ctx, 11)
+    nxt = bita.prefill(model, kv, 0, dev_i32(ctx[None]), chunk)
+    torch.cuda.synchronize()
+    assert int(kv.ctx_len[0]) == n_ctx
+    k, v, last = _oracle_causal(om, ctx)
+    gk, gv = read_cache(kv)
+    for l in range(cfg.n_layers):
+        assert gk[l].shape == k[l].shape
+        assert np.abs(gk[l] - k[l]).max() <= KV_TOL
+        assert np.abs(gv[l] - v[l]).max() <= KV_TOL
+    # slots past the context stay untouched (the cache starts zeroed)
+    assert not kv.k_cache[:, 0, :, n_ctx:].any() and not kv.v_cache[:, 0, :, n_ctx:].any()
+    if _margin(last) > MARGIN:
+        assert int(nxt[0]) == argmax_low(last)
+    else:
+        assert 0 <= int(nxt[0]) < cfg.vocab
+
+
+def test_prefill_ragged_batch_in_two_calls(bita):
+    """Three sequences of different lengths (one empty), filled by two calls: the second call
+    appends to what the first committed.  Each sequence equals its own causal pass."""
+    cfg = synth.get_config("tiny_gqa")
+    w = synth.SynthWeights(cfg, seed=5)
+    om = oracle.OracleModel(cfg, w)
+    smax, chunk, B = 256, 48, 3
+    model = bita.Model(cfg, w, max_pos=smax + 64)
+    kv = bita.KVState(cfg, cfg.n_layers, B, smax, chunk)
+    lens = [131, 37, 0]
+    first = [60, 37, 0]                                  # tokens handed over by the first call
+    ctxs = [synth.random_context(cfg.vocab, max(n, 1), 40 + b)[:n] for b, n in enumerate(lens)]
+
+    def padded(parts):
+        width = max(max(len(p) for p in parts), 1)
+        out = np.full((B, width), -7, np.int32)           # padding is never read as a token
+        for b, p in enumerate(parts):
+            out[b, :len(p)] = p
+        return dev_i32(out)
+    n1 = bita.prefill(model, kv, 0, padded([c[:f] for c, f in zip(ctxs, first)]), chunk, seq_len=dev_i32(first))
+    torch.cuda.synchronize()
+    assert kv.ctx_len.cpu().tolist() == first
+    rest = [len(c) - f for c, f in zip(ctxs, first)]
+    n2 = bita.prefill(model, kv, max(first), padded([c[f:] for c, f in zip(ctxs, first)]), chunk, seq_len=dev_i32(rest))
+    torch.cuda.synchronize()
+    assert kv.ctx_len.cpu().tolist() == lens
+    assert int(n1[2]) == -1 and int(n2[2]) == -1          # an empty sequence has no next token
+    assert int(n2[1]) == -1                               # nothing of sequence 1 in the second call
+    for b in range(B):
+        if lens[b] == 0:
+            continue
+        k, v, last = _oracle_causal(om, ctxs[b])
+        gk, gv = read_cache(kv, b=b)
+        for l in range(cfg.n_layers):
+            assert np.abs(gk[l] - k[l]).max() <= KV_TOL
+            assert np.abs(gv[l] - v[l]).max() <= KV_TOL
+        got = int(n2[b]) if rest[b] > 0 else int(n1[b])
+        if _margin(last) > MARGIN:
+            assert got == argmax_low(last)
+
+
+def test_prefill_rejects_what_does_not_fit(bita):
+    cfg = synth.get_config("tiny")
+    w = synth.SynthWeights(cfg, seed=1)
+    model = bita.Model(cfg, w, max_pos=96)
+    kv = bita.KVState(cfg, cfg.n_layers, 1, 64, 32)
+    toks = dev_i32(synth.random_context(cfg.vocab, 80, 2)[None])
+    with pytest.raises(bita.BitaError) as e:
+        bita.prefill(model, kv, 0, toks, 32)              # 80 tokens into 64 slots
+    assert e.value.code == -3
+    with pytest.raises(bita.BitaError) as e:
+        bita.prefill(model, kv, 0, toks[:, :40].contiguous(), 33)   # scratch holds 32 rows
+    assert e.value.code == -1
+    torch.cuda.synchronize()
+    assert int(kv.ctx_len[0]) == 0 and not kv.k_cache.any()
