@@ -119,3 +119,52 @@ def test_prefill_rejects_what_does_not_fit(bita):
     assert e.value.code == -1
     torch.cuda.synchronize()
     assert int(kv.ctx_len[0]) == 0 and not kv.k_cache.any()
+
+
+def test_prompt_to_tokens_on_the_device_alone(bita):
+    """The whole decoder with no oracle data on the device: prefill of the full prompt gives the
+    first token, then the first step runs with no candidates (Algorithm 1, t = 1: only the root
+    and its mask rows are live) and later steps draft for themselves.  The emitted stream is the
+    oracle's autoregressive greedy stream wherever its top-2 margin is decisive."""
+    cfg = synth.get_config("tiny")
+    tin = synth.attach_mask_groups(synth.random_tree(8, 3, 0), [0], cfg.n_mask)
+    w = synth.SynthWeights(cfg, seed=0)
+    om = oracle.OracleModel(cfg, w)
+    d = oracle.tree.derive_template(tin.parent, tin.is_mask, tin.n_mask)
+    smax, steps = 256, 12
+    model = bita.Model(cfg, w, max_pos=smax + 64)
+    tmpl = bita.TreeTemplate(tin.parent, tin.is_mask, tin.n_tree, tin.n_mask)
+    kv = bita.KVState(cfg, cfg.n_layers, 1, smax, max(tmpl.rows, 32))
+    ctx = synth.random_context(cfg.vocab, 64, 0)
+    # oracle: greedy stream and margins, one token per pass
+    ck, cv = oracle.decode.prefill(om, ctx)
+    ref, margins = [], []
+    last = int(ctx[-1])
+    for _ in range(steps * (d.tree_depth + 1) + 2):
+        lg, k, v = oracle.forward_rows(om, [last], [0], [-1], [ck[0].shape[0]], [[0]], ck, cv)
+        ck, cv = oracle.compact_kv(ck, cv, k, v, [0])
+        last = argmax_low(lg[0])
+        ref.append(last)
+        margins.append(_margin(lg[0]))
+    # device: prompt -> first token -> steps
+    first = bita.prefill(model, kv, 0, dev_i32(ctx[None]), 32)
+    emitted = [int(first[0])]
+    kv.resize_rows(cfg.n_layers, cfg, tmpl.rows)
+    buf = bita.StepBuffers(model, tmpl, 1, d.kmax)
+    buf.bonus.copy_(first)
+    buf.next_shift[0] = cfg.n_mask                       # t = 1: no candidates yet
+    lens = []
+    for t in range(steps):
+        hint = len(ctx) + t * (d.tree_depth + 1)
+        bita.decode_step(model, kv, hint, tmpl, buf, 1, buf.bonus, buf.topk_ids, buf.next_group, buf.next_shift)
+        torch.cuda.synchronize()
+        na = int(buf.n_acc[0])
+        if t == 0:
+            assert na == 1 and buf.token[0, 1:tmpl.n_tree].cpu().tolist() == [-1] * (tmpl.n_tree - 1)
+        lens.append(na)
+        emitted.extend(buf.emitted[0, :na].cpu().tolist())
+    low = [i for i in range(len(emitted)) if margins[i] <= MARGIN]
+    upto = low[0] if low else len(emitted)
+    assert upto >= 8, "seed gives an early near-tie; pick another"
+    assert emitted[:upto] == ref[:upto]
+    assert int(kv.ctx_len[0]) == len(ctx) + sum(lens)
