@@ -48,6 +48,8 @@ def parse_args():
                     help="draft-tree template (default: full64; tiny workload: its seeded 8-node tree); "
                          "'-pernode' attaches a mask group to every tree node instead of the root only")
     ap.add_argument("--mode", default="planted", choices=["free", "planted"])
+    ap.add_argument("--page-size", type=int, default=0,
+                    help="keep the KV cache in shuffled pages of this many slots (power of two >= 16; runs free)")
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
@@ -180,6 +182,9 @@ def main():
     if NB > 1 and args.mode == "planted":
         print("bench.py: --batch above 1 runs free (no planted drafts)", file=sys.stderr)
         args.mode = "free"
+    if args.page_size and args.mode == "planted":
+        print("bench.py: a paged cache runs free (no planted drafts)", file=sys.stderr)
+        args.mode = "free"
     ctx_n = args.ctx or {"tiny": 64, "7b": 1024, "13b": 2048, "70b": 2048}[args.workload]
     tin = workload_template(synth, cfg, args.workload, args.tree)
     steps, warmup = args.steps, args.warmup
@@ -202,7 +207,10 @@ def main():
             wsrc_np[(n, None)] = w.numpy(n)
     model = bita.Model(cfg, w, max_pos=smax + 64, free_source=True)
     tmpl = bita.TreeTemplate(tin.parent, tin.is_mask, tin.n_tree, cfg.n_mask)
-    kv = bita.KVState(cfg, cfg.n_layers, NB, smax, R)
+    if args.page_size:
+        kv = bita.PagedKVState(cfg, cfg.n_layers, NB, smax, R, args.page_size, seed=args.seed)
+    else:
+        kv = bita.KVState(cfg, cfg.n_layers, NB, smax, R)
     ctx_all = np.stack([synth.random_context(cfg.vocab, ctx_n, args.seed + 7919 * b) for b in range(NB)])
     ctx_tokens = ctx_all[0]
     prefill(B, model, kv, cfg, ctx_all)
@@ -383,7 +391,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"llama2-{args.workload}-shaped random-init, ctx {ctx_n}, batch {NB}, "
                                f"{tin.n_tree}-node tree ({args.tree or 'default'}) + {R - tin.n_tree} mask rows, P={cfg.n_prompt}, mode {args.mode}",
-                   "rows": R, "batch": NB, "graph": graph is not None},
+                   "rows": R, "batch": NB, "graph": graph is not None, "page_size": args.page_size or None},
         "hbm_gbps": gbps, "hbm_frac_of_peak": gbps / HBM_PEAK_GBPS, "bytes_per_step": bytes_per_step,
         "gpu_ms_per_step": gpu_ms / steps, "mean_accepted": float(np.mean(nacc[warmup:])),
         "generated_tokens_per_s": float(np.sum(nacc[warmup:])) / wall,

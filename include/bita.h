@@ -93,11 +93,25 @@ typedef struct bita_weights {
  *   k_tree, v_tree   [n_layers][batch][n_kv_heads][rows][head_dim]: K/V of the R
  *       rows of the current pass (scratch; only accepted rows are ever committed).
  *   ctx_hint: HOST upper bound on every sequence's ctx_len for this call, used
- *       only to size launches and to check capacity without reading device memory. */
+ *       only to size launches and to check capacity without reading device memory.
+ * Paged cache (block_table != NULL; the paper runs batch 1 with one contiguous
+ * cache, Sec. 4.1; pages serve batches whose sequences grow unevenly): the caches
+ * are page pools
+ *   k_cache, v_cache [n_layers][n_pages][n_kv_heads][page_size][head_dim]
+ * and key slot s of sequence b lives in page block_table[b][s / page_size], row
+ * s % page_size.  block_table is device memory, [batch][max_pages] int32;
+ * page_size a power of two >= 16; smax (the capacity of one sequence in slots)
+ * <= max_pages * page_size and <= 4096 pages.  The entries that cover slots
+ * 0 .. ctx_len + rows committed by the call must name distinct pages in
+ * [0, n_pages) across all sequences: the library does not check that (ids are
+ * clamped to the pool: a bad table gives wrong data, never a fault).
+ * block_table == NULL: contiguous layout above; the three sizes are ignored. */
 typedef struct bita_kv {
     void *k_cache, *v_cache;
     void *k_tree, *v_tree;
     int32_t smax, rows, batch, ctx_hint;
+    const int32_t *block_table;
+    int32_t page_size, n_pages, max_pages;
 } bita_kv;
 
 typedef struct bita_model bita_model;                 /* opaque */

@@ -41,7 +41,8 @@ class _Weights(C.Structure):
 
 class _KV(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("k_cache", "v_cache", "k_tree", "v_tree")] + \
-               [(n, C.c_int32) for n in ("smax", "rows", "batch", "ctx_hint")]
+               [(n, C.c_int32) for n in ("smax", "rows", "batch", "ctx_hint")] + \
+               [("block_table", C.c_void_p)] + [(n, C.c_int32) for n in ("page_size", "n_pages", "max_pages")]
 
 
 def lib():
@@ -237,7 +238,52 @@ class KVState:
 
     def desc(self, ctx_hint):
         return _KV(self.k_cache.data_ptr(), self.v_cache.data_ptr(), self.k_tree.data_ptr(),
-                   self.v_tree.data_ptr(), self.smax, self.rows, self.batch, int(ctx_hint))
+                   self.v_tree.data_ptr(), self.smax, self.rows, self.batch, int(ctx_hint), None, 0, 0, 0)
+
+
+class PagedKVState(KVState):
+    """KV state whose caches are page pools [n_layers][n_pages][n_kv_heads][page_size][head_dim];
+    block_table [batch][max_pages] names the pages of every sequence (here: a seeded shuffle of
+    the pool, so that neighbouring slots of a sequence are not neighbours in memory)."""
+
+    def __init__(self, cfg, n_layers, batch, smax, rows, page_size, n_pages=None, seed=0):
+        dev = torch.device("cuda")
+        self.page_size = int(page_size)
+        self.max_pages = (smax + page_size - 1) // page_size
+        self.n_pages = int(n_pages or batch * self.max_pages)
+        assert self.n_pages >= batch * self.max_pages
+        shape_c = (n_layers, self.n_pages, cfg.n_kv_heads, page_size, cfg.head_dim)
+        shape_t = (n_layers, batch, cfg.n_kv_heads, rows, cfg.head_dim)
+        self.k_cache = torch.zeros(shape_c, dtype=torch.bfloat16, device=dev)
+        self.v_cache = torch.zeros(shape_c, dtype=torch.bfloat16, device=dev)
+        self.k_tree = torch.zeros(shape_t, dtype=torch.bfloat16, device=dev)
+        self.v_tree = torch.zeros(shape_t, dtype=torch.bfloat16, device=dev)
+        self.ctx_len = torch.zeros(batch, dtype=torch.int32, device=dev)
+        self.smax, self.rows, self.batch = smax, rows, batch
+        perm = np.random.default_rng(seed).permutation(self.n_pages)[: batch * self.max_pages]
+        self.block_table = torch.tensor(perm.reshape(batch, self.max_pages), dtype=torch.int32, device=dev)
+
+    def desc(self, ctx_hint):
+        return _KV(self.k_cache.data_ptr(), self.v_cache.data_ptr(), self.k_tree.data_ptr(),
+                   self.v_tree.data_ptr(), self.smax, self.rows, self.batch, int(ctx_hint),
+                   self.block_table.data_ptr(), self.page_size, self.n_pages, self.max_pages)
+
+    def contiguous(self, b):
+        """(k, v) of sequence b as [n_layers][n_kv_heads][max_pages * page_size][head_dim] copies."""
+        pages = self.block_table[b].long()
+        def one(pool):
+            x = pool[:, pages]                                      # [L][max_pages][Hkv][page][hd]
+            return x.permute(0, 2, 1, 3, 4).reshape(x.shape[0], x.shape[2], -1, x.shape[4])
+        return one(self.k_cache), one(self.v_cache)
+
+    def load_contiguous(self, b, k, v, n):
+        """Write slots 0..n-1 of sequence b from k, v [n_layers][n_kv_heads][>= n][head_dim]; sets ctx_len[b] = n."""
+        for i in range((n + self.page_size - 1) // self.page_size):
+            lo, hi = i * self.page_size, min((i + 1) * self.page_size, n)
+            page = int(self.block_table[b, i])
+            self.k_cache[:, page, :, : hi - lo] = k[:, :, lo:hi]
+            self.v_cache[:, page, :, : hi - lo] = v[:, :, lo:hi]
+        self.ctx_len[b] = n
 
 
 class StepBuffers:

@@ -279,6 +279,25 @@ static WsLayout ws_layout(const bita_config &c, int batch, int rows) {
     return L;
 }
 
+// Paging fields of a KV descriptor -> PageMap (table == nullptr when the cache is contiguous).
+// ctx_upper: the number of leading slots per sequence the call may read.
+int page_map_of(const bita_kv *kv, int ctx_upper, PageMap *pm, const char *who) {
+    *pm = PageMap{nullptr, 0, 0, 0, 0};
+    if (!kv->block_table) return BITA_OK;
+    const int ps = kv->page_size;
+    if (ps < 16 || (ps & (ps - 1)) || kv->n_pages <= 0 || kv->max_pages <= 0)
+        return bita_set_error(BITA_ERR_INVALID_ARG, "%s: paged cache needs page_size a power of two >= 16 (got %d), n_pages and max_pages positive",
+                              who, ps);
+    if ((int64_t)kv->smax > (int64_t)kv->max_pages * ps)
+        return bita_set_error(BITA_ERR_CAPACITY, "%s: smax %d exceeds the block table (%d pages of %d)", who, kv->smax, kv->max_pages, ps);
+    int cap = (ctx_upper + ps - 1) / ps;
+    if (cap > kv->max_pages) cap = kv->max_pages;
+    if (cap > ATT_PAGE_TABLE_MAX)
+        return bita_set_error(BITA_ERR_UNSUPPORTED, "%s: %d pages per sequence, at most %d", who, cap, ATT_PAGE_TABLE_MAX);
+    *pm = PageMap{kv->block_table, __builtin_ctz((unsigned)ps), kv->n_pages, kv->max_pages, cap};
+    return BITA_OK;
+}
+
 extern "C" size_t bita_workspace_bytes(const bita_model *m, int32_t batch, int32_t rows) {
     if (!m || batch <= 0 || rows <= 0) return 0;
     return ws_layout(m->cfg, batch, rows).total;
@@ -310,6 +329,8 @@ extern "C" int bita_verify_step(bita_model *m, const bita_kv *kv, const bita_tre
     const WsLayout L = ws_layout(c, batch, td.rows);
     if (ws_bytes < L.total)
         return bita_set_error(BITA_ERR_CAPACITY, "bita_verify_step: workspace %zu < %zu bytes", ws_bytes, L.total);
+    PageMap pm;
+    if (int rc = page_map_of(kv, kv->ctx_hint, &pm, "bita_verify_step")) return rc;
 
     hipStream_t s = (hipStream_t)stream;
     unsigned char *ws = (unsigned char *)d_workspace;
@@ -329,7 +350,8 @@ extern "C" int bita_verify_step(bita_model *m, const bita_kv *kv, const bita_tre
                    p_lm = gemm_plan(M, c.vocab, d);
     AttnPlan ap = attn_plan(batch, td.rows, c.n_heads, hd, kv->ctx_hint, c.n_prompt);
     if (ap.splits > ATTN_MAX_SPLITS) ap.splits = ATTN_MAX_SPLITS;
-    const size_t kv_layer_cache = (size_t)batch * c.n_kv_heads * kv->smax * hd * 2;
+    const size_t kv_layer_cache = pm.table ? (size_t)kv->n_pages * c.n_kv_heads * kv->page_size * hd * 2
+                                           : (size_t)batch * c.n_kv_heads * kv->smax * hd * 2;
     const size_t kv_layer_tree = (size_t)batch * c.n_kv_heads * td.rows * hd * 2;
 
     launch_embed(d_token, td, batch, m->tok_emb, m->mask_emb, d, c.vocab, x, s);
@@ -343,7 +365,7 @@ extern "C" int bita_verify_step(bita_model *m, const bita_kv *kv, const bita_tre
         launch_tree_attention(td, q, q_lo, (unsigned char *)kv->k_cache + l * kv_layer_cache,
                               (unsigned char *)kv->v_cache + l * kv_layer_cache, kt, vt, k_lo, v_lo, m->prompt_k[l],
                               m->prompt_v[l], d_ctx_len, batch, c.n_heads, c.n_kv_heads, hd, c.n_prompt, kv->smax,
-                              ap, part_o, part_ml, attn_out, true, s);
+                              ap, part_o, part_ml, attn_out, true, pm, s);
         timed_gemm(attn_out, M, nq, m->wo[l], d, partial, d, p_o, s);
         launch_rmsnorm_prep(x, partial, p_o.splits, M, d, m->ffn_norm[l], h, ssq, s);
         // with a single split the gate/up GEMM gates in its own epilogue and writes the slab itself
@@ -372,8 +394,8 @@ extern "C" int bita_verify_step(bita_model *m, const bita_kv *kv, const bita_tre
     return BITA_OK;
 }
 
-int compact_kv_launch(const bita_config &cfg, const bita_kv *kv, const int32_t *d_path, int path_stride,
-                      const int32_t *d_n_acc, int32_t *d_ctx_len, int batch, hipStream_t s);
+int compact_kv_launch(const bita_config &cfg, const bita_kv *kv, const PageMap &pm, const int32_t *d_path,
+                      int path_stride, const int32_t *d_n_acc, int32_t *d_ctx_len, int batch, hipStream_t s);
 
 extern "C" int bita_compact_kv(const bita_model *m, const bita_kv *kv, const int32_t *d_path,
                                int32_t path_stride, const int32_t *d_n_acc, int32_t *d_ctx_len,
@@ -387,7 +409,9 @@ extern "C" int bita_compact_kv(const bita_model *m, const bita_kv *kv, const int
     if (kv->ctx_hint + path_stride > kv->smax)
         return bita_set_error(BITA_ERR_CAPACITY, "bita_compact_kv: ctx_hint %d + %d accepted rows exceed cache capacity %d",
                               kv->ctx_hint, path_stride, kv->smax);
-    compact_kv_launch(m->cfg, kv, d_path, path_stride, d_n_acc, d_ctx_len, batch, (hipStream_t)stream);
+    PageMap pm;
+    if (int rc = page_map_of(kv, kv->ctx_hint + path_stride, &pm, "bita_compact_kv")) return rc;
+    compact_kv_launch(m->cfg, kv, pm, d_path, path_stride, d_n_acc, d_ctx_len, batch, (hipStream_t)stream);
     BITA_HIP_CHECK(hipGetLastError());
     return BITA_OK;
 }
@@ -421,7 +445,7 @@ extern "C" int bita_tree_attention(const bita_tree_template *t, const void *d_q,
     float *part_o = (float *)d_ws, *part_ml = (float *)((unsigned char *)d_ws + align_up(p.part_o_bytes, 256));
     launch_tree_attention(t->dev, d_q, d_q_lo, d_k_cache, d_v_cache, d_k_tree, d_v_tree, d_k_tree_lo, d_v_tree_lo, d_prompt_k, d_prompt_v, d_ctx_len,
                           batch, n_heads, n_kv_heads, head_dim, n_prompt, smax, p, part_o, part_ml, d_out,
-                          false, (hipStream_t)stream);
+                          false, PageMap{nullptr, 0, 0, 0, 0}, (hipStream_t)stream);
     BITA_HIP_CHECK(hipGetLastError());
     return BITA_OK;
 }

@@ -156,7 +156,10 @@ __device__ __forceinline__ constexpr int att_swizzle(int rho) { return HD == 128
 template <int HD>
 __device__ __forceinline__ constexpr int att_swizzle_k(int rho) { return HD == 128 ? (rho & 15) : ((rho >> 1) & 7); }
 
-template <int HD, int U>
+// PAGED: the cache operands are page pools [n_pages][Hkv][page][HD] and key slot s of sequence b
+// lives in page table[b][s >> page_lg] at row s & (page - 1); the sequence's table entries are
+// copied to LDS (behind the chunk buffers) once per workgroup.
+template <int HD, int U, bool PAGED>
 __global__ __launch_bounds__(ATT_WAVES * 64) __attribute__((amdgpu_waves_per_eu(ATT_WAVES / 4, ATT_WAVES / 4))) void tree_attn_kernel(
     TemplateDev t, const uint16_t *__restrict__ q, const uint16_t *__restrict__ q_lo,
     const uint16_t *__restrict__ k_cache, const uint16_t *__restrict__ v_cache,
@@ -165,7 +168,7 @@ __global__ __launch_bounds__(ATT_WAVES * 64) __attribute__((amdgpu_waves_per_eu(
     const uint16_t *__restrict__ prompt_k, const uint16_t *__restrict__ prompt_v,
     const int32_t *__restrict__ ctx_len, int batch, int Hq, int Hkv, int P, int smax, int n_splits, int n_mt,
     float scale_log2, float *__restrict__ part_o, float *__restrict__ part_ml, uint16_t *__restrict__ out,
-    int as_fragments, int m_tiles_out) {
+    int as_fragments, int m_tiles_out, PageMap pm) {
     using C = AttCfg<HD, U>;
     constexpr int KSN = C::KSN, NTN = C::NTN, GPR = C::GPR, RPI = C::RPI, NVI = C::NVI;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -185,7 +188,20 @@ __global__ __launch_bounds__(ATT_WAVES * 64) __attribute__((amdgpu_waves_per_eu(
     const int qh = w_in / n_mt;
     const int b = group / Hkv, kvh = group % Hkv, h0 = kvh * qpk + qh * U;   // heads h0 .. h0+U-1
 
-    const int R = t.rows, Lc = ctx_len[b];
+    const int R = t.rows;
+    int Lc = ctx_len[b];
+    const int32_t *tbl = reinterpret_cast<const int32_t *>(smem + C::SMEM);
+    const int page_lg = pm.page_lg, page_mask = (1 << pm.page_lg) - 1;
+    if (PAGED) {
+        // never walk past the table entries the launch made room for; page ids are clamped to
+        // the pool, so a bad table gives wrong data, not a fault
+        Lc = min(Lc, pm.tbl_cap << page_lg);
+        int32_t *dst = reinterpret_cast<int32_t *>(smem + C::SMEM);
+        const int n_used = (Lc + page_mask) >> page_lg;
+        for (int i = tid; i < n_used; i += ATT_WAVES * 64)
+            dst[i] = min(max(pm.table[(int64_t)b * pm.max_pages + i], 0), pm.n_pages - 1);
+        __syncthreads();
+    }
     const int row0 = mt * 16;
     const int n_ctx_keys = P + Lc;
     const int n_cc = (n_ctx_keys + ATT_CHUNK - 1) / ATT_CHUNK;           // chunks over [prefix | cache]
@@ -198,8 +214,18 @@ __global__ __launch_bounds__(ATT_WAVES * 64) __attribute__((amdgpu_waves_per_eu(
     const int n_my = max(0, (chunk_end - chunk_begin - wave + ATT_WAVES - 1) / ATT_WAVES);
 
     const uint16_t *pk = prompt_k + (int64_t)kvh * P * HD, *pv = prompt_v + (int64_t)kvh * P * HD;
-    const uint16_t *ck = k_cache + ((int64_t)b * Hkv + kvh) * smax * HD;
-    const uint16_t *cv = v_cache + ((int64_t)b * Hkv + kvh) * smax * HD;
+    const int64_t page_stride = (int64_t)Hkv * HD << page_lg;           // elements per page (all kv heads)
+    const uint16_t *ck = k_cache + (PAGED ? ((int64_t)kvh * HD << page_lg) : ((int64_t)b * Hkv + kvh) * smax * HD);
+    const uint16_t *cv = v_cache + (PAGED ? ((int64_t)kvh * HD << page_lg) : ((int64_t)b * Hkv + kvh) * smax * HD);
+    // element offset of cache slot j of this (sequence, kv head) from ck / cv
+    auto slot_off = [&](int j) __attribute__((always_inline)) -> int64_t {
+        if (!PAGED) return (int64_t)j * HD;
+        return (int64_t)tbl[j >> page_lg] * page_stride + (int64_t)(j & page_mask) * HD;
+    };
+    // a chunk of cache slots j0 .. j0+ATT_CHUNK-1 has one base address (always, when contiguous)
+    auto one_page = [&](int j0) __attribute__((always_inline)) -> bool {
+        return !PAGED || (j0 >> page_lg) == ((j0 + ATT_CHUNK - 1) >> page_lg);
+    };
     const int64_t tree_off = ((int64_t)b * Hkv + kvh) * R * HD;
     const uint16_t *tk = k_tree + tree_off, *tv = v_tree + tree_off;
     const uint16_t *tk_lo = k_tree_lo ? k_tree_lo + tree_off : nullptr;
@@ -288,8 +314,8 @@ __global__ __launch_bounds__(ATT_WAVES * 64) __attribute__((amdgpu_waves_per_eu(
         const unsigned char *zero_b = reinterpret_cast<const unsigned char *>(zero);
         const int slot0 = att_slot_of_row(iv * RPI);                    // slot of the instruction's first row
         gptr k_src, v_src, a_src = (gptr)(zero_b + (lane & 1) * 8);
-        if (base >= P && base + ATT_CHUNK <= n_ctx_keys) {
-            const int64_t row_bytes = ((int64_t)(base - P + slot0) + lane_slot) * (HD * 2);
+        if (base >= P && base + ATT_CHUNK <= n_ctx_keys && one_page(base - P)) {
+            const int64_t row_bytes = (slot_off(base - P) + (int64_t)(slot0 + lane_slot) * HD) * 2;
             k_src = (gptr)(reinterpret_cast<const unsigned char *>(ck) + row_bytes + k_gran[iv & 3]);
             v_src = (gptr)(reinterpret_cast<const unsigned char *>(cv) + row_bytes + v_gran[iv & 1]);
         } else if (chunk >= n_cc) {
@@ -305,8 +331,9 @@ __global__ __launch_bounds__(ATT_WAVES * 64) __attribute__((amdgpu_waves_per_eu(
             // a chunk with prefix rows or the ragged end of the cache
             const int kidx = base + slot0 + lane_slot;
             const bool in_prefix = kidx < P, in_cache = kidx >= P && kidx < n_ctx_keys;
-            const uint16_t *krow = in_prefix ? pk + (int64_t)kidx * HD : (in_cache ? ck + (int64_t)(kidx - P) * HD : zero);
-            const uint16_t *vrow = in_prefix ? pv + (int64_t)kidx * HD : (in_cache ? cv + (int64_t)(kidx - P) * HD : zero);
+            const int64_t off = in_cache ? slot_off(kidx - P) : 0;
+            const uint16_t *krow = in_prefix ? pk + (int64_t)kidx * HD : (in_cache ? ck + off : zero);
+            const uint16_t *vrow = in_prefix ? pv + (int64_t)kidx * HD : (in_cache ? cv + off : zero);
             k_src = (gptr)(reinterpret_cast<const unsigned char *>(krow) + k_gran[iv & 3]);
             v_src = (gptr)(reinterpret_cast<const unsigned char *>(vrow) + v_gran[iv & 1]);
         }
@@ -364,9 +391,10 @@ __global__ __launch_bounds__(ATT_WAVES * 64) __attribute__((amdgpu_waves_per_eu(
         };
         const int base_n = base + ATT_WAVES * ATT_CHUNK;                 // the wave's next chunk
         // (with two heads per workgroup the second code path costs registers the kernel does not have)
-        if (U == 1 && more && base_n >= P && base_n + ATT_CHUNK <= n_ctx_keys) {   // wave-uniform
-            const unsigned char *kb = reinterpret_cast<const unsigned char *>(ck) + (int64_t)(base_n - P) * (HD * 2);
-            const unsigned char *vb = reinterpret_cast<const unsigned char *>(cv) + (int64_t)(base_n - P) * (HD * 2);
+        if (U == 1 && more && base_n >= P && base_n + ATT_CHUNK <= n_ctx_keys && one_page(base_n - P)) {   // wave-uniform
+            const int64_t off_n = slot_off(base_n - P) * 2;
+            const unsigned char *kb = reinterpret_cast<const unsigned char *>(ck) + off_n;
+            const unsigned char *vb = reinterpret_cast<const unsigned char *>(cv) + off_n;
 #pragma unroll
             for (int iv = 0; iv < NVI; iv++) {
                 emit_cache(kb, vb, iv);
@@ -619,29 +647,31 @@ AttnPlan attn_plan(int batch, int rows, int n_heads, int hd, int ctx_hint, int n
     return p;
 }
 
-template <int HD, int U>
+template <int HD, int U, bool PAGED>
 static void launch_attn_t(const TemplateDev &t, const void *q, const void *q_lo, const void *k_cache, const void *v_cache,
                           const void *k_tree, const void *v_tree, const void *k_tree_lo, const void *v_tree_lo,
                           const void *prompt_k, const void *prompt_v, const int32_t *ctx_len, int batch, int Hq,
                           int Hkv, int P, int smax, const AttnPlan &p, float *part_o, float *part_ml, void *out,
-                          bool out_as_fragments, hipStream_t s) {
+                          bool out_as_fragments, const PageMap &pm, hipStream_t s) {
     using C = AttCfg<HD, U>;
     static bool attr_set = false;
     if (!attr_set) {
-        (void)hipFuncSetAttribute((const void *)tree_attn_kernel<HD, U>,
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM);
+        (void)hipFuncSetAttribute((const void *)tree_attn_kernel<HD, U, PAGED>,
+                                  hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  C::SMEM + (PAGED ? ATT_PAGE_TABLE_MAX * 4 : 0));
         attr_set = true;
     }
+    const size_t smem_bytes = C::SMEM + (PAGED ? (size_t)((pm.tbl_cap + 3) / 4) * 16 : 0);
     const int n_mt = (t.rows + 15) / 16;
     const float scale_log2 = 1.4426950408889634f / sqrtf((float)HD);
     const int groups = batch * Hkv, per_group = (Hq / Hkv / U) * n_mt * p.splits;
     const int grid = 8 * ((groups + 7) / 8) * per_group;
-    hipLaunchKernelGGL((tree_attn_kernel<HD, U>), dim3(grid), dim3(ATT_WAVES * 64), C::SMEM, s, t,
+    hipLaunchKernelGGL((tree_attn_kernel<HD, U, PAGED>), dim3(grid), dim3(ATT_WAVES * 64), smem_bytes, s, t,
                        (const uint16_t *)q, (const uint16_t *)q_lo, (const uint16_t *)k_cache, (const uint16_t *)v_cache,
                        (const uint16_t *)k_tree, (const uint16_t *)v_tree, (const uint16_t *)k_tree_lo,
                        (const uint16_t *)v_tree_lo, (const uint16_t *)prompt_k, (const uint16_t *)prompt_v, ctx_len,
                        batch, Hq, Hkv, P, smax, p.splits, n_mt, scale_log2, part_o, part_ml, (uint16_t *)out,
-                       out_as_fragments ? 1 : 0, (batch * t.rows + 15) / 16);
+                       out_as_fragments ? 1 : 0, (batch * t.rows + 15) / 16, pm);
 }
 
 void launch_tree_attention(const TemplateDev &t, const void *q, const void *q_lo, const void *k_cache, const void *v_cache,
@@ -649,16 +679,18 @@ void launch_tree_attention(const TemplateDev &t, const void *q, const void *q_lo
                            const void *prompt_k,
                            const void *prompt_v, const int32_t *ctx_len, int batch, int Hq, int Hkv, int hd,
                            int P, int smax, const AttnPlan &p, float *part_o, float *part_ml, void *out,
-                           bool out_as_fragments, hipStream_t s) {
+                           bool out_as_fragments, const PageMap &pm, hipStream_t s) {
     // grouped-query models: two query heads of a K/V head per workgroup share its chunk loads
     const bool pair = (Hq / Hkv) % 2 == 0;
-#define ATT_LAUNCH(HD_, U_) launch_attn_t<HD_, U_>(t, q, q_lo, k_cache, v_cache, k_tree, v_tree, k_tree_lo, v_tree_lo, prompt_k, \
-                                                   prompt_v, ctx_len, batch, Hq, Hkv, P, smax, p, part_o, part_ml, out, out_as_fragments, s)
+#define ATT_LAUNCH_P(HD_, U_, PG_) launch_attn_t<HD_, U_, PG_>(t, q, q_lo, k_cache, v_cache, k_tree, v_tree, k_tree_lo, v_tree_lo, prompt_k, \
+                                                   prompt_v, ctx_len, batch, Hq, Hkv, P, smax, p, part_o, part_ml, out, out_as_fragments, pm, s)
+#define ATT_LAUNCH(HD_, U_) do { if (pm.table) ATT_LAUNCH_P(HD_, U_, true); else ATT_LAUNCH_P(HD_, U_, false); } while (0)
     if (hd == 128) {
         if (pair) ATT_LAUNCH(128, 2); else ATT_LAUNCH(128, 1);
     } else {
         if (pair) ATT_LAUNCH(64, 2); else ATT_LAUNCH(64, 1);
     }
+#undef ATT_LAUNCH_P
 #undef ATT_LAUNCH
     if (p.splits > 1) {
         const int heads_per_block = (256 / (hd / 4)) < Hq ? (256 / (hd / 4)) : Hq;

@@ -125,6 +125,11 @@ void launch_silu_mul(const float *partial, int splits, int m_rows, int d_ffn, vo
 void launch_select(const float *logits, int batch, const TemplateDev &t, int vocab, int kmax,
                    int32_t *argmax, int32_t *topk_ids, float *topk_val, hipStream_t s);
 
+// Where the cache rows live: contiguous per sequence (table == nullptr) or in pages of
+// 1 << page_lg key slots, page ids per sequence in table[b][0 .. max_pages).  tbl_cap: table
+// entries per sequence a launch makes room for (covers the call's ctx_hint).
+#define ATT_PAGE_TABLE_MAX 4096
+struct PageMap { const int32_t *table; int page_lg, n_pages, max_pages, tbl_cap; };
 struct AttnPlan { int splits; size_t part_o_bytes, part_ml_bytes; };
 AttnPlan attn_plan(int batch, int rows, int n_heads, int hd, int ctx_hint, int n_prompt);
 // k_tree_lo / v_tree_lo: low bf16 plane of the pass rows' K/V (nullable)
@@ -134,4 +139,4 @@ void launch_tree_attention(const TemplateDev &t, const void *q, const void *q_lo
                            const void *prompt_k, const void *prompt_v, const int32_t *ctx_len,
                            int batch, int n_heads, int n_kv_heads, int hd, int n_prompt, int smax,
                            const AttnPlan &p, float *part_o, float *part_ml, void *out,
-                           bool out_as_fragments, hipStream_t s);
+                           bool out_as_fragments, const PageMap &pm, hipStream_t s);

@@ -77,7 +77,7 @@ __global__ void compact_kv_kernel(uint4 *__restrict__ k_cache, uint4 *__restrict
                                   const uint4 *__restrict__ k_tree, const uint4 *__restrict__ v_tree,
                                   const int32_t *__restrict__ path, int path_stride,
                                   const int32_t *__restrict__ n_acc, const int32_t *__restrict__ ctx_len,
-                                  int batch, int Hkv, int smax, int rows, int row_u4) {
+                                  int batch, int Hkv, int smax, int rows, int row_u4, PageMap pm) {
     const int lh = blockIdx.x, i = blockIdx.y, b = blockIdx.z;
     const int n = n_acc[b];
     if (i >= n) return;
@@ -87,7 +87,12 @@ __global__ void compact_kv_kernel(uint4 *__restrict__ k_cache, uint4 *__restrict
     if (src_row < 0 || src_row >= rows) return;
     const int l = lh / Hkv, h = lh % Hkv;
     const int64_t src = ((((int64_t)l * batch + b) * Hkv + h) * rows + src_row) * row_u4;
-    const int64_t dst = ((((int64_t)l * batch + b) * Hkv + h) * smax + lc + i) * row_u4;
+    int64_t dst = ((((int64_t)l * batch + b) * Hkv + h) * smax + lc + i) * row_u4;
+    if (pm.table) {                                     // page pools [L][n_pages][Hkv][page][hd]
+        const int slot = lc + i;
+        const int page = min(max(pm.table[(int64_t)b * pm.max_pages + (slot >> pm.page_lg)], 0), pm.n_pages - 1);
+        dst = (((((int64_t)l * pm.n_pages + page) * Hkv + h) << pm.page_lg) + (slot & ((1 << pm.page_lg) - 1))) * row_u4;
+    }
     for (int j = threadIdx.x; j < row_u4; j += blockDim.x) {
         k_cache[dst + j] = k_tree[src + j];
         v_cache[dst + j] = v_tree[src + j];
@@ -127,13 +132,13 @@ extern "C" int bita_accept(const bita_tree_template *t, const int32_t *d_token, 
     return BITA_OK;
 }
 
-int compact_kv_launch(const bita_config &cfg, const bita_kv *kv, const int32_t *d_path, int path_stride,
-                      const int32_t *d_n_acc, int32_t *d_ctx_len, int batch, hipStream_t s) {
+int compact_kv_launch(const bita_config &cfg, const bita_kv *kv, const PageMap &pm, const int32_t *d_path,
+                      int path_stride, const int32_t *d_n_acc, int32_t *d_ctx_len, int batch, hipStream_t s) {
     const int row_u4 = cfg.head_dim * 2 / 16;
     dim3 grid(cfg.n_layers * cfg.n_kv_heads, path_stride, batch);
     hipLaunchKernelGGL(compact_kv_kernel, grid, dim3(16), 0, s, (uint4 *)kv->k_cache, (uint4 *)kv->v_cache,
                        (const uint4 *)kv->k_tree, (const uint4 *)kv->v_tree, d_path, path_stride, d_n_acc,
-                       d_ctx_len, batch, cfg.n_kv_heads, kv->smax, kv->rows, row_u4);
+                       d_ctx_len, batch, cfg.n_kv_heads, kv->smax, kv->rows, row_u4, pm);
     hipLaunchKernelGGL(advance_ctx_kernel, dim3((batch + 63) / 64), dim3(64), 0, s, d_n_acc, d_ctx_len,
                        batch, kv->smax);
     return BITA_OK;
