@@ -497,11 +497,18 @@ GemmPlan gemm_plan(int m_rows, int64_t n_rows, int64_t k) {
         }
     }
     if (m_tiles == 6 || m_tiles == 7) p.variant = 8;            // one pass: 4 tiles per wave x 7 m-tiles of accumulators would spill
+    // Many rows (prefill chunks, batches, per-node mask groups on large trees): the launch
+    // makes `passes` row passes of 5 m-tiles over the weights, every pass its own set of
+    // workgroups.  The passes fill the CUs, so fewer k splits are needed, and the widest
+    // workgroups (16 waves, or 14 on the gate/up-like widths) share each activation fragment
+    // among the most weight tiles.
+    const int passes = m_tiles > 7 ? (m_tiles + 4) / 5 : 1;
+    if (passes >= 2) p.variant = (NT >= 1024 && NT < 3000) ? 11 : 9;
     if (g_force_variant >= 0 && g_force_variant < GEMM_N_VARIANTS) p.variant = g_force_variant;
     const GemmVariant &v = g_variants[p.variant];
     const int tiles_wg = v.nw * v.waves / v.kgroups;
     const int64_t wgs_n = (NT + tiles_wg - 1) / tiles_wg;
-    int64_t splits = (v.waves > 4 ? 256 : 512) / wgs_n;
+    int64_t splits = (v.waves > 4 ? 256 : 512) / (wgs_n * passes);
     const int64_t max_splits = KS / 8;                          // at least 8 stages per split
     if (splits > max_splits) splits = max_splits;
     if (NT < 512 && splits > 8) splits = 8;
