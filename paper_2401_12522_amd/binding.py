@@ -230,10 +230,18 @@ class KVState:
         self.smax, self.rows, self.batch = smax, rows, batch
 
     def resize_rows(self, n_layers, cfg, rows):
-        dev = self.k_cache.device
+        """Lay the per-pass scratch out for a template of `rows` rows (the template may change from
+        step to step).  The memory is kept when it is large enough; the contents are undefined."""
         shape_t = (n_layers, self.batch, cfg.n_kv_heads, rows, cfg.head_dim)
-        self.k_tree = torch.zeros(shape_t, dtype=torch.bfloat16, device=dev)
-        self.v_tree = torch.zeros(shape_t, dtype=torch.bfloat16, device=dev)
+        n = n_layers * self.batch * cfg.n_kv_heads * rows * cfg.head_dim
+        for name in ("k_tree", "v_tree"):
+            flat = getattr(self, "_" + name + "_flat", None)
+            if flat is None:
+                flat = getattr(self, name).reshape(-1)
+            if flat.numel() < n:
+                flat = torch.zeros(n, dtype=torch.bfloat16, device=self.k_cache.device)
+            setattr(self, "_" + name + "_flat", flat)
+            setattr(self, name, flat[:n].view(shape_t))
         self.rows = rows
 
     def desc(self, ctx_hint):

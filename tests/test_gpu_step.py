@@ -251,3 +251,71 @@ def test_batched_steps_with_ragged_contexts_and_accepts(bita):
                 assert np.abs(gk[l] - ck[l]).max() <= LOGIT_TOL
                 assert np.abs(gv[l] - cv[l]).max() <= LOGIT_TOL
     assert len({tuple(x) for x in lens}) >= 2, "the sequences should not all accept alike"
+
+
+def test_topology_may_change_every_step(bita):
+    """The template is an argument of the step, not state: an efficient tree, a full tree, a
+    per-node-group tree and a chain take turns on one KV state (Sec. 3.3 compares these
+    topologies).  The candidates, group and shift a step hands over come from the previous
+    step's template; every step is compared with the oracle run through the same sequence."""
+    cfg = synth.get_config("tiny")
+    n = cfg.n_mask
+    eff = synth.efficient_tree_parents(n, 3)
+    tins = [synth.attach_mask_groups(eff, [0], n),
+            synth.attach_mask_groups(synth.full_branching_tree([3, 2, 2, 1]), [0], n),
+            synth.attach_mask_groups(eff, range(len(eff)), n),
+            synth.attach_mask_groups(synth.chain_tree(n + 1), [0], n)]
+    w = synth.SynthWeights(cfg, seed=0)
+    om = oracle.OracleModel(cfg, w)
+    smax = 256
+    model = bita.Model(cfg, w, max_pos=smax + 64)
+    ds = [derive_template(t.parent, t.is_mask, t.n_mask) for t in tins]
+    tmpls = [bita.TreeTemplate(t.parent, t.is_mask, t.n_tree, t.n_mask) for t in tins]
+    KMAX = max(d.kmax for d in ds)
+    bufs = [bita.StepBuffers(model, t, 1, KMAX, want_logits=True) for t in tmpls]
+    kv = bita.KVState(cfg, cfg.n_layers, 1, smax, max(t.rows for t in tmpls))
+    ctx = synth.random_context(cfg.vocab, 64, 0)
+    ref_stream = ar_greedy(om, ctx, 12 * (n + 1) + 1)
+    st = round_state(BitaState(om, ctx))
+    out, seen = [], set()
+    for t in range(12):
+        i = (t * 3 + t // 4) % 4                          # 0 3 2 1 1 0 3 2 2 1 0 3: each follows several others
+        d, tmpl, buf = ds[i], tmpls[i], bufs[i]
+        kv.resize_rows(cfg.n_layers, cfg, tmpl.rows)
+        Lc = load_cache(kv, st.cache_k, st.cache_v)
+        root = st.root_token
+        if t % 2 == 1:                                    # a planted draft, so that some steps accept deep
+            rng = np.random.default_rng(300 + t)
+            cand = synth.planted_candidates(ref_stream[len(out):], n, KMAX, int(rng.integers(1, d.tree_depth + 1)),
+                                            np.zeros(n, int), cfg.vocab, 40 + t)
+            group, shift = 0, 0
+            ref = bita_step(om, d, st, cand, kmax=KMAX)
+        else:                                             # what the previous step (another template) left
+            if st.cand is None:
+                cand, group, shift = np.full((n, KMAX), -1, np.int32), 0, n
+            else:
+                cand, group, shift = st.cand, st.group, st.shift
+            ref = bita_step(om, d, st, kmax=KMAX)
+        bita.decode_step(model, kv, Lc, tmpl, buf, 1, dev_i32([root]), dev_i32(np.asarray(cand)[None]),
+                         dev_i32([group]), dev_i32([shift]))
+        torch.cuda.synchronize()
+        assert buf.token[0].cpu().tolist() == ref["tokens"], t
+        lg = buf.logits[0].cpu().numpy()
+        assert np.abs(lg - ref["logits"]).max() <= LOGIT_TOL, t
+        _check_selection_bit_exact(buf, d, lg)
+        gpu_greedy = buf.argmax[0].cpu().tolist()
+        path, bonus = accept_walk(d, ref["tokens"], gpu_greedy)
+        na = len(path)
+        assert int(buf.n_acc[0]) == na and buf.path[0, :na].cpu().tolist() == path and int(buf.bonus[0]) == bonus
+        assert (int(buf.next_group[0]), int(buf.next_shift[0])) == next_group_and_shift(d, path)
+        assert int(kv.ctx_len[0]) == Lc + na
+        for l in range(cfg.n_layers):
+            assert torch.equal(kv.k_cache[l, 0][:, Lc:Lc + na], kv.k_tree[l, 0][:, path])
+        decisive = all(_top2_margin(ref["logits"][r]) > MARGIN for r in range(d.T))
+        if decisive:
+            assert gpu_greedy == ref["greedy"] and path == ref["path"]
+        seen.add((i, na))
+        out.extend(ref["emitted"])
+        round_state(st)
+    assert out == ref_stream[: len(out)]                  # lossless whatever the topology
+    assert len({i for i, _ in seen}) == 4 and max(na for _, na in seen) >= 2
