@@ -60,7 +60,7 @@ extern "C" size_t bita_prefill_workspace_bytes(const bita_model *m, int32_t batc
 extern "C" int bita_prefill(bita_model *m, const bita_kv *kv, const int32_t *d_tokens, int32_t n_tokens,
                             const int32_t *d_seq_len, int32_t *d_ctx_len, int32_t batch, int32_t chunk_rows,
                             void *d_workspace, size_t ws_bytes, int32_t *d_next_token, void *stream) {
-    if (!m || !kv || !d_tokens || !d_ctx_len || !d_workspace || batch <= 0 || n_tokens < 0)
+    if (!m || !kv || (!d_tokens && n_tokens != 0) || !d_ctx_len || !d_workspace || batch <= 0 || n_tokens < 0)
         return bita_set_error(BITA_ERR_INVALID_ARG, "bita_prefill: null argument, batch <= 0 or n_tokens < 0");
     if (chunk_rows <= 0 || chunk_rows > BITA_MAX_ROWS)
         return bita_set_error(BITA_ERR_INVALID_ARG, "bita_prefill: chunk_rows must be in 1..%d", BITA_MAX_ROWS);

@@ -117,7 +117,10 @@ def test_prefill_rejects_what_does_not_fit(bita):
     with pytest.raises(bita.BitaError) as e:
         bita.prefill(model, kv, 0, toks[:, :40].contiguous(), 33)   # scratch holds 32 rows
     assert e.value.code == -1
+    # an empty context is a no-op, not an error
+    nxt = bita.prefill(model, kv, 0, torch.zeros((1, 0), dtype=torch.int32, device="cuda"), 32)
     torch.cuda.synchronize()
+    assert int(nxt[0]) == -1
     assert int(kv.ctx_len[0]) == 0 and not kv.k_cache.any()
 
 
