@@ -10,7 +10,10 @@
  *                     token tree plus mask tokens, under tree-based attention
  *   bita_accept       greedy verification walk (Algorithm 1, inner loops)
  *   bita_compact_kv   commit the accepted rows' K/V to the cache
- *   bita_prefill      the context's K/V by chunked causal passes
+ *
+ * and the context is brought into the cache beforehand by
+ *
+ *   bita_prefill      chunked causal passes over the context (the same kernels)
  *
  * Conventions
  *   - Every call returns an int status: BITA_OK or a negative BITA_ERR_* code;
@@ -20,7 +23,7 @@
  *     DEVICE pointers BORROWED from the caller; the library never frees them.
  *     Pointers without the prefix are HOST pointers, read during the call only.
  *   - `stream` is a hipStream_t passed as void*.  The four step calls only
- *     enqueue work: no allocation, no host synchronisation, no host read of
+ *     enqueue work (bita_prefill also waits for the stream, see there): no allocation, no host synchronisation, no host read of
  *     device memory.  Results are valid once the caller has synchronised the
  *     stream.  They may be captured into a HIP graph by the caller.
  *   - Row layout of a pass ("template"): R rows per sequence.  Row 0 is the root
