@@ -71,3 +71,53 @@ def test_full_width_step(name, n_layers, ctx_n, topology):
     for l in range(n_layers):
         got_k = kv.k_tree[l, 0].permute(1, 0, 2).to(torch.float64).cpu().numpy()
         assert np.abs(got_k - ref["new_k"][l]).max() < 3e-2
+
+
+def test_13b_width_batch_of_four():
+    """LLaMA-2-13B-shaped layer, batch 4 with independent contexts of different lengths and an
+    independent candidate table per sequence: every sequence against its own oracle step."""
+    import paper_2401_12522_amd as bita
+    n_layers, B = 1, 4
+    cfg = synth.get_config("13b", n_layers=n_layers)
+    w = synth.SynthWeights(cfg, seed=3, device="cuda")
+    wc = synth.SynthWeights(cfg, seed=3, device="cpu")
+    for n in synth.weights.GLOBAL_TENSORS:
+        wc._store[(n, None)] = w.torch(n).cpu()
+    for n in synth.weights.LAYER_TENSORS:
+        wc._store[(n, 0)] = w.torch(n, 0).cpu()
+    om = oracle.OracleModel(cfg, wc, cache_layers=True)
+    tin = synth.attach_mask_groups(synth.full_branching_tree([4, 3, 2, 1], 64), [0], cfg.n_mask)
+    d = derive_template(tin.parent, tin.is_mask, cfg.n_mask)
+    smax = 256
+    model = bita.Model(cfg, w, max_pos=smax + 64)
+    tmpl = bita.TreeTemplate(tin.parent, tin.is_mask, tin.n_tree, cfg.n_mask)
+    kv = bita.KVState(cfg, n_layers, B, smax, tmpl.rows)
+    lens = [90, 33, 140, 64]
+    states, cands, roots = [], [], []
+    for b in range(B):
+        ctx = synth.random_context(cfg.vocab, lens[b], 20 + b)
+        st = round_state(BitaState(om, ctx))
+        load_cache(kv, st.cache_k, st.cache_v, b=b)
+        states.append(st)
+        roots.append(int(ctx[-1]))
+        cands.append(np.random.default_rng(60 + b).integers(0, cfg.vocab, size=(cfg.n_mask, d.kmax)).astype(np.int32))
+    buf = bita.StepBuffers(model, tmpl, B, d.kmax, want_logits=True)
+    bita.decode_step(model, kv, max(lens) - 1, tmpl, buf, B, dev_i32(roots), dev_i32(np.stack(cands)))
+    torch.cuda.synchronize()
+    for b in range(B):
+        ref = bita_step(om, d, states[b], cands[b])
+        assert buf.token[b].cpu().tolist() == ref["tokens"]
+        lg = buf.logits[b].cpu().numpy()
+        err = np.abs(lg - ref["logits"]).max()
+        print(f"13b batch 4, sequence {b} (ctx {lens[b] - 1}): logits max-abs err {err:.4f}", flush=True)
+        assert err <= LOGIT_TOL, (b, err)
+        gpu_greedy = buf.argmax[b].cpu().tolist()
+        for r in range(d.T):
+            s = np.sort(ref["logits"][r])
+            if s[-1] - s[-2] > MARGIN:
+                assert gpu_greedy[r] == ref["greedy"][r]
+        path, bonus = accept_walk(d, ref["tokens"], gpu_greedy)
+        assert buf.path[b, : len(path)].cpu().tolist() == path and int(buf.bonus[b]) == bonus
+        assert int(kv.ctx_len[b]) == lens[b] - 1 + len(path)
+        got_k = kv.k_tree[0, b].permute(1, 0, 2).to(torch.float64).cpu().numpy()
+        assert np.abs(got_k - ref["new_k"][0]).max() < 3e-2
