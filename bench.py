@@ -27,9 +27,10 @@ HBM_PEAK_GBPS = 8000.0
 
 
 # HBM-side bytes (fetch + write) per GEMM launch, averaged over the launches of one step, from the
-# FETCH_SIZE / WRITE_SIZE counter runs scaled by a copy kernel (profiles/gemm_traffic_7b.md);
-# counters cannot be collected from inside this process, so the figure is carried as a constant
-GEMM_TRAFFIC_BYTES_PER_LAUNCH = {"7b": 120.9e6}
+# FETCH_SIZE / WRITE_SIZE counter runs scaled by a copy kernel (profiles/gemm_traffic_7b.md,
+# gemm_traffic_70b.md), 68 rows, batch 1; counters cannot be collected from inside this process,
+# so the figure is carried as a constant
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = {"7b": 120.9e6, "70b": 459.3e6}
 # layer counts of the two oracle passes timed for cpu_baseline (about 10 s of host work at 7B width)
 CPU_SAMPLE_LAYERS = (4, 8)
 
@@ -380,7 +381,8 @@ def main():
     gemm_gbps = float(np.sum(g_bytes)) / (float(np.sum(g_ms)) * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": "gemm_skinny_kernel (all %d launches of a step)" % n_gemm,
                 "achieved": gemm_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": gemm_gbps / HBM_PEAK_GBPS,
-                "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH.get(args.workload), "avg_launch_us": gemm_avg_us,
+                "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH.get(args.workload) if (R == 68 and NB == 1) else None,
+                "avg_launch_us": gemm_avg_us,
                 "bytes_per_launch": float(np.mean(g_bytes)),
                 "gemm_ms_per_step": float(np.sum(g_ms)) / prof_steps}
 
