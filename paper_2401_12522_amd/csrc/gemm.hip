@@ -164,7 +164,9 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
     const int n_stages = (per_group + KC - 1) / KC;            // same for every wave: barriers in lockstep
     uint4 *a_lds = smem_u4 + kg * (D * C::NFRAG * 64);         // this k group's ring
     uint4 *dump = smem_u4 + KG * D * C::NFRAG * 64;            // target of padding fetches
-    (void)M;
+
+    // lane -> lane holding the same k granule of the last existing row of the slab's last m-tile
+    const int lane_last = (lane & ~15) | min(lane & 15, M - 1 - (m_tiles - 1) * 16);
 
     f32x4 acc[MT][NW];
 #pragma unroll
@@ -204,7 +206,12 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
             const int mtg = min(bz * MT + mt, m_tiles - 1);   // m-tile in the whole slab
             const int ks = min(ks0 + s, KS - 1);
             // fragment (plane, ks, mtg) starts at ((plane * KS + ks) * m_tiles + mtg) * 64 uint4
-            const uint4 *src = A_frag + ((int64_t)plane * planes_stride_f + (int64_t)ks * m_tiles + mtg) * 64 + lane;
+            // The slab's last m-tile may hold fewer than 16 rows (4 of the 68 of a 64-node tree):
+            // the lanes of its missing rows re-read the last row that exists, so the fragment
+            // costs the L1 the cache lines of its real rows only (same-address lanes coalesce).
+            // The copies land in accumulator rows that are never stored.
+            const int src_lane = mtg == m_tiles - 1 ? lane_last : lane;   // wave-uniform choice
+            const uint4 *src = A_frag + ((int64_t)plane * planes_stride_f + (int64_t)ks * m_tiles + mtg) * 64 + src_lane;
             uint4 *dst = f < C::NFRAG ? a_lds + (SLOT * C::NFRAG + f) * 64 : dump;   // wave-uniform; lane l lands at dst[l]
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
                                              (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
