@@ -38,12 +38,13 @@ def _margin(row):
     return s[-1] - s[-2]
 
 
-@pytest.mark.parametrize("cfg_name,n_ctx,chunk", [("tiny", 150, 64), ("tiny_gqa", 150, 256), ("tiny_gqa", 97, 17)])
+@pytest.mark.parametrize("cfg_name,n_ctx,chunk", [("tiny", 150, 64), ("tiny_gqa", 150, 256), ("tiny_gqa", 97, 17),
+                                                  ("tiny", 600, 512)])      # 512 rows: the largest template
 def test_prefill_chunks_match_one_causal_pass(bita, cfg_name, n_ctx, chunk):
     cfg = synth.get_config(cfg_name)
     w = synth.SynthWeights(cfg, seed=3)
     om = oracle.OracleModel(cfg, w)
-    smax = 256
+    smax = 256 if n_ctx <= 256 else 640
     model = bita.Model(cfg, w, max_pos=smax + 64)
     kv = bita.KVState(cfg, cfg.n_layers, 1, smax, chunk)
     ctx = synth.random_context(cfg.vocab, n_ctx, 11)
