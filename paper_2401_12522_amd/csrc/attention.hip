@@ -575,8 +575,9 @@ __global__ __launch_bounds__(ATT_WAVES * 64) __attribute__((amdgpu_waves_per_eu(
             pl.x = lo[0] | ((uint32_t)lo[1] << 16); pl.y = lo[2] | ((uint32_t)lo[3] << 16);
             const int k = h * HD + nt * 16 + 4 * g;
             if (as_fragments) {              // two planes, the O-projection's activation slab
-                *reinterpret_cast<uint2 *>(out + frag_index(0, mrow, k, n_ksteps, m_tiles_out)) = ph;
-                *reinterpret_cast<uint2 *>(out + frag_index(1, mrow, k, n_ksteps, m_tiles_out)) = pl;
+                const int pack_off = frag_pack_offset(batch * R);
+                *reinterpret_cast<uint2 *>(out + frag_index(0, mrow, k, n_ksteps, m_tiles_out, pack_off)) = ph;
+                *reinterpret_cast<uint2 *>(out + frag_index(1, mrow, k, n_ksteps, m_tiles_out, pack_off)) = pl;
             } else {
                 *reinterpret_cast<uint2 *>(out + (int64_t)mrow * Hq * HD + k) = ph;
             }
@@ -616,8 +617,9 @@ __global__ void attn_merge_kernel(const float *__restrict__ part_o, const float 
     pl.x = lo[0] | ((uint32_t)lo[1] << 16); pl.y = lo[2] | ((uint32_t)lo[3] << 16);
     if (as_fragments) {                     // two planes, the O-projection's activation slab
         const int mrow = b * R + r, k = h * HD + i4 * 4, n_ksteps = (Hq * HD) >> 5;
-        *reinterpret_cast<uint2 *>(out + frag_index(0, mrow, k, n_ksteps, m_tiles)) = ph;
-        *reinterpret_cast<uint2 *>(out + frag_index(1, mrow, k, n_ksteps, m_tiles)) = pl;
+        const int pack_off = frag_pack_offset((int)gridDim.z * R);
+        *reinterpret_cast<uint2 *>(out + frag_index(0, mrow, k, n_ksteps, m_tiles, pack_off)) = ph;
+        *reinterpret_cast<uint2 *>(out + frag_index(1, mrow, k, n_ksteps, m_tiles, pack_off)) = pl;
     } else {
         *reinterpret_cast<uint2 *>(out + (((int64_t)b * R + r) * Hq + h) * HD + i4 * 4) = ph;
     }

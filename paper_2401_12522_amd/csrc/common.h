@@ -26,7 +26,24 @@ __device__ __forceinline__ void split_bf16(float x, uint16_t &hi, uint16_t &lo) 
 // Position (in bf16 elements) of A[m][k] of plane p inside an activation slab kept in MFMA
 // A-operand fragment order: 1 KiB per (plane, k-step of 32, m-tile of 16), lane l of a
 // fragment holding A[16mt + l%16][32ks + 8(l/16) .. +8].
-__device__ __forceinline__ int64_t frag_index(int plane, int m, int k, int n_ksteps, int m_tiles) {
+// A last m-tile that is at most half full keeps BOTH planes of its rows in the high plane's
+// fragment: the low plane of row r sits at row r + off (off = 4 for up to 4 rows, 8 for up to 8).
+// One fragment and one matrix instruction per weight tile then serve both planes of those rows;
+// the two partial products come out as different accumulator rows and are added once, after the
+// k loop.  frag_pack_offset gives off (0 = not packed) from the slab's row count alone, so
+// producers and the GEMM agree; it applies to the slabs whose GEMM always takes every m-tile in
+// one pass with as many accumulator tiles: one m-tile (M <= 8: the one-row pass) or five
+// (65..72 rows: the 64-node tree with its mask rows).
+__host__ __device__ __forceinline__ int frag_pack_offset(int M) {
+    const int m_tiles = (M + 15) >> 4, v = M - 16 * (m_tiles - 1);
+    if ((m_tiles != 1 && m_tiles != 5) || v > 8) return 0;
+    return v <= 4 ? 4 : 8;
+}
+__device__ __forceinline__ int64_t frag_index(int plane, int m, int k, int n_ksteps, int m_tiles, int pack_off) {
+    if (pack_off && plane == 1 && (m >> 4) == m_tiles - 1) {
+        plane = 0;
+        m += pack_off;
+    }
     const int ks = k >> 5, kq = (k >> 3) & 3, e = k & 7;
     return ((((int64_t)plane * n_ksteps + ks) * m_tiles + (m >> 4)) * 64 + kq * 16 + (m & 15)) * 8 + e;
 }

@@ -86,11 +86,14 @@ __device__ __forceinline__ void static_for(F &&f) {
 // WAVES wavefronts per workgroup, of which KG groups of WN = WAVES/KG waves each take one
 // contiguous part of the workgroup's k range (with their own activation ring) and are summed
 // through LDS at the end: twice the waves per partial sum written.
-template <int MT, int NW, bool SPLIT, int KC, int D, int WAVES, int KG>
+// PACK: the slab's last m-tile (the pass' tile MT-1) keeps both planes of its rows in its high
+// plane's fragment (frag_pack_offset): the stage has one fragment less, the last of the list.
+template <int MT, int NW, bool SPLIT, int KC, int D, int WAVES, int KG, bool PACK = false>
 struct GemmCfg {
+    static_assert(!PACK || (SPLIT && KC == 1), "packing folds the low plane into the high one");
     static constexpr int WN = WAVES / KG;                       // waves side by side along N
     static constexpr int PL = SPLIT ? 2 : 1;
-    static constexpr int NFRAG = PL * MT * KC;                  // A fragments per stage
+    static constexpr int NFRAG = PL * MT * KC - (PACK ? 1 : 0); // A fragments per stage
     static constexpr int FPW = (NFRAG + WN - 1) / WN;           // fetched per wave per stage
     static constexpr int LOADS = NW * KC + FPW;                 // vector-memory loads per wave per stage
     // every wave issues FPW fragment loads per stage (the vmcnt bookkeeping counts on it);
@@ -102,12 +105,12 @@ struct GemmCfg {
     static_assert((D - 2) * LOADS < 64, "vmcnt counter range");
 };
 
-template <int MT, int NW, bool SPLIT, int KC, int D, int WAVES, int KG, bool DIRECT>
+template <int MT, int NW, bool SPLIT, int KC, int D, int WAVES, int KG, bool DIRECT, bool PACK>
 __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
     const uint4 *__restrict__ A_frag, int planes_stride_f, int M, int m_tiles,
     const uint4 *__restrict__ Wp, int NT, int KS, float *__restrict__ out, int64_t ldo,
     int ksteps_per_split, GemmOutput direct) {
-    using C = GemmCfg<MT, NW, SPLIT, KC, D, WAVES, KG>;
+    using C = GemmCfg<MT, NW, SPLIT, KC, D, WAVES, KG, PACK>;
     constexpr int WN = C::WN;
     extern __shared__ __attribute__((aligned(16))) uint4 smem_u4[];   // [KG][D][NFRAG][64] + dump slot
 
@@ -166,7 +169,11 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
     uint4 *dump = smem_u4 + KG * D * C::NFRAG * 64;            // target of padding fetches
 
     // lane -> lane holding the same k granule of the last existing row of the slab's last m-tile
-    const int lane_last = (lane & ~15) | min(lane & 15, M - 1 - (m_tiles - 1) * 16);
+    // (packed tile: of the last existing row of the lane's plane)
+    const int rows_last = M - (m_tiles - 1) * 16, pack_off = PACK ? frag_pack_offset(M) : 16;
+    const int lane_row = lane & 15;
+    const int lane_last = (lane & ~15) | (lane_row < pack_off ? min(lane_row, rows_last - 1)
+                                                              : pack_off + min(lane_row - pack_off, rows_last - 1));
 
     f32x4 acc[MT][NW];
 #pragma unroll
@@ -226,7 +233,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
             if (ks_begin + stage * KC + s >= ks_end) continue;
             // all LDS reads of the k-step are issued before its first MFMA; fragment f is
             // waited for with the NF-1-f later reads still in flight
-            constexpr int NF = C::PL * MT;
+            constexpr int NF = C::PL * MT - (PACK ? 1 : 0);
             static_assert(NF <= 16, "lgkmcnt range");
             bf16x8 a[NF];
             static_for<0, NF>([&](auto f_c) {
@@ -319,6 +326,14 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
         }
         if (kg != 0) return;
     }
+    if constexpr (PACK) {
+        // the packed tile's low-plane products sit pack_off rows (pack_off / 4 lane groups)
+        // further down: add them to the rows they belong to
+#pragma unroll
+        for (int j = 0; j < NW; j++)
+#pragma unroll
+            for (int r = 0; r < 4; r++) acc[MT - 1][j][r] += __shfl_down(acc[MT - 1][j][r], 4 * pack_off, 64);
+    }
     // D layout: lane (g = lane/16, c = lane%16) holds rows 4g..4g+3, column c of each tile.
     const int g = lane >> 4, cc = lane & 15;
     // Stores of the wave's MT x NW tiles (k group 0 after the merge).  With k groups they go
@@ -406,8 +421,13 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
                         uint16_t hi, lo;
                         split_bf16(v, hi, lo);
                         const int at = pos + (4 * g + r) * 8;            // row 4g+r of m-tile i
-                        stage[((0 * HK + hk) * MT + i) * 256 + at] = hi;
-                        stage[((1 * HK + hk) * MT + i) * 256 + at] = lo;
+                        if (PACK && i == MT - 1) {                       // the output slab packs its last tile the same way
+                            if (4 * g + r < pack_off) stage[((0 * HK + hk) * MT + i) * 256 + at] = hi;
+                            if (4 * g + r < rows_last) stage[((0 * HK + hk) * MT + i) * 256 + at + pack_off * 8] = lo;
+                        } else {
+                            stage[((0 * HK + hk) * MT + i) * 256 + at] = hi;
+                            stage[((1 * HK + hk) * MT + i) * 256 + at] = lo;
+                        }
                     }
             }
             __syncthreads();
@@ -420,6 +440,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
                 const int plane = idx / (HK * MT), hk = (idx / MT) % HK, i = idx % MT;
                 const int hkg = hk0 + hk;                                // half k-step in the whole slab
                 if ((hkg >> 1) >= n_ksteps || mt0 + i >= mt_all) continue;   // (a last half past F holds zeros)
+                if (PACK && plane == 1 && i == MT - 1) continue;             // lives in the high plane's fragment
                 const uint4 v = reinterpret_cast<const uint4 *>(stage)[idx * 32 + l32];
                 reinterpret_cast<uint4 *>(direct.act_frag)[(((int64_t)plane * n_ksteps + (hkg >> 1)) * mt_all + mt0 + i) * 64 +
                                                            (hkg & 1) * 32 + l32] = v;
@@ -463,6 +484,14 @@ __global__ void to_fragments_kernel(const uint16_t *__restrict__ a_hi, const uin
     const int m = mt * 16 + (lane & 15), k = ks * 32 + (lane >> 4) * 8;
     uint4 v = make_uint4(0, 0, 0, 0);
     if (src && m < M && k < K) v = *reinterpret_cast<const uint4 *>(src + (int64_t)m * lda + k);
+    const int pack_off = a_lo ? frag_pack_offset(M) : 0;
+    if (pack_off && mt == m_tiles - 1) {
+        // both planes of a packed last tile share the high plane's fragment (disjoint rows)
+        const int row = lane & 15;
+        if (plane == 0 && row < pack_off) dst[((int64_t)ks * m_tiles + mt) * 64 + lane] = v;
+        if (plane == 1 && m < M) dst[((int64_t)ks * m_tiles + mt) * 64 + lane + pack_off] = v;
+        return;
+    }
     dst[(((int64_t)plane * KS + ks) * m_tiles + mt) * 64 + lane] = v;
 }
 
@@ -528,20 +557,20 @@ GemmPlan gemm_plan(int m_rows, int64_t n_rows, int64_t k) {
     return p;
 }
 
-template <int MT, int NW, bool SPLIT, int WAVES, int D, int KG, bool DIRECT>
+template <int MT, int NW, bool SPLIT, int WAVES, int D, int KG, bool DIRECT, bool PACK = false>
 static void launch_gemm_t(const void *a_frag, int M, int64_t K, const void *w, int64_t N, float *out, int64_t ldo,
                           const GemmPlan &p, hipStream_t s, const GemmOutput &direct) {
     constexpr int KC = 1;
-    using C = GemmCfg<MT, NW, SPLIT, KC, D, WAVES, KG>;
+    using C = GemmCfg<MT, NW, SPLIT, KC, D, WAVES, KG, PACK>;
     static bool attr_set = false;
     if (!attr_set) {
-        (void)hipFuncSetAttribute((const void *)gemm_skinny_kernel<MT, NW, SPLIT, KC, D, WAVES, KG, DIRECT>,
+        (void)hipFuncSetAttribute((const void *)gemm_skinny_kernel<MT, NW, SPLIT, KC, D, WAVES, KG, DIRECT, PACK>,
                                   hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM);
         attr_set = true;
     }
     const int NT = (int)(N / 16), KS = (int)((K + 31) / 32), m_tiles = (M + 15) / 16;
     dim3 grid((NT + C::WN * NW - 1) / (C::WN * NW), p.splits, (m_tiles + MT - 1) / MT);
-    hipLaunchKernelGGL((gemm_skinny_kernel<MT, NW, SPLIT, KC, D, WAVES, KG, DIRECT>), grid, dim3(WAVES * 64), C::SMEM, s,
+    hipLaunchKernelGGL((gemm_skinny_kernel<MT, NW, SPLIT, KC, D, WAVES, KG, DIRECT, PACK>), grid, dim3(WAVES * 64), C::SMEM, s,
                        (const uint4 *)a_frag, KS * m_tiles, M, m_tiles, (const uint4 *)w, NT, KS, out, ldo,
                        p.ksteps_per_split, direct);
 }
@@ -550,10 +579,20 @@ template <int MT, bool SPLIT>
 static void launch_gemm_v(const void *a_frag, int M, int64_t K, const void *w, int64_t N, float *out, int64_t ldo,
                           const GemmPlan &p, hipStream_t s, const GemmOutput &direct) {
     // the instantiations with an output epilogue exist for the k-group shapes only
-#define V(i, nw, waves, d, kg) case i: launch_gemm_t<MT, nw, SPLIT, waves, d, kg, false>(a_frag, M, K, w, N, out, ldo, p, s, direct); break;
+    // a two-plane slab whose last m-tile is packed (frag_pack_offset) takes the instantiation
+    // that reads it so; both exist for one and five m-tiles, the only slabs that pack
+    constexpr bool CAN_PACK = SPLIT && (MT == 1 || MT == 5);
+    const bool pack = CAN_PACK && frag_pack_offset(M) != 0;
+#define T(nw, waves, d, kg, dir) do { \
+        if constexpr (CAN_PACK) { \
+            if (pack) { launch_gemm_t<MT, nw, SPLIT, waves, d, kg, dir, true>(a_frag, M, K, w, N, out, ldo, p, s, direct); break; } \
+        } \
+        launch_gemm_t<MT, nw, SPLIT, waves, d, kg, dir, false>(a_frag, M, K, w, N, out, ldo, p, s, direct); \
+    } while (0)
+#define V(i, nw, waves, d, kg) case i: T(nw, waves, d, kg, false); break;
 #define W(i, nw, waves, d, kg) case i: \
-        if (direct.kind != GEMM_OUT_PARTIAL) launch_gemm_t<MT, nw, SPLIT, waves, d, kg, true>(a_frag, M, K, w, N, out, ldo, p, s, direct); \
-        else launch_gemm_t<MT, nw, SPLIT, waves, d, kg, false>(a_frag, M, K, w, N, out, ldo, p, s, direct); \
+        if (direct.kind != GEMM_OUT_PARTIAL) T(nw, waves, d, kg, true); \
+        else T(nw, waves, d, kg, false); \
         break;
     switch (p.variant) {
         V(0, 1, 4, 4, 1) V(1, 2, 4, 4, 1) V(2, 4, 4, 4, 1) V(3, 2, 8, 6, 1) V(4, 4, 8, 6, 1)
@@ -561,6 +600,7 @@ static void launch_gemm_v(const void *a_frag, int M, int64_t K, const void *w, i
     }
 #undef V
 #undef W
+#undef T
 }
 
 // two planes, the planner's variants (6 and 8) only; more than 5 m-tiles with variant 8 alone (registers, LDS ring)

@@ -75,8 +75,9 @@ __global__ __launch_bounds__(256) void rmsnorm_prep_kernel(float *__restrict__ x
         uint2 ph, pl;
         ph.x = hi[0] | ((uint32_t)hi[1] << 16); ph.y = hi[2] | ((uint32_t)hi[3] << 16);
         pl.x = lo[0] | ((uint32_t)lo[1] << 16); pl.y = lo[2] | ((uint32_t)lo[3] << 16);
-        *reinterpret_cast<uint2 *>(h_frag + frag_index(0, row, 4 * c, n_ksteps, m_tiles)) = ph;
-        *reinterpret_cast<uint2 *>(h_frag + frag_index(1, row, 4 * c, n_ksteps, m_tiles)) = pl;
+        const int pack_off = frag_pack_offset(M);
+        *reinterpret_cast<uint2 *>(h_frag + frag_index(0, row, 4 * c, n_ksteps, m_tiles, pack_off)) = ph;
+        *reinterpret_cast<uint2 *>(h_frag + frag_index(1, row, 4 * c, n_ksteps, m_tiles, pack_off)) = pl;
     }
     ss = wave_sum(ss);
     if ((tid & 63) == 0) red[tid >> 6] = ss;
@@ -190,8 +191,9 @@ __global__ void silu_mul_kernel(const float *__restrict__ partial, int splits, i
     ph.z = hi[4] | ((uint32_t)hi[5] << 16); ph.w = hi[6] | ((uint32_t)hi[7] << 16);
     pl.x = lo[0] | ((uint32_t)lo[1] << 16); pl.y = lo[2] | ((uint32_t)lo[3] << 16);
     pl.z = lo[4] | ((uint32_t)lo[5] << 16); pl.w = lo[6] | ((uint32_t)lo[7] << 16);
-    *reinterpret_cast<uint4 *>(act_frag + frag_index(0, row, f, n_ksteps, m_tiles)) = ph;
-    *reinterpret_cast<uint4 *>(act_frag + frag_index(1, row, f, n_ksteps, m_tiles)) = pl;
+    const int pack_off = frag_pack_offset(M);
+    *reinterpret_cast<uint4 *>(act_frag + frag_index(0, row, f, n_ksteps, m_tiles, pack_off)) = ph;
+    *reinterpret_cast<uint4 *>(act_frag + frag_index(1, row, f, n_ksteps, m_tiles, pack_off)) = pl;
 }
 
 // ---------------------------------------------------------------------------------------

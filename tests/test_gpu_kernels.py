@@ -37,7 +37,11 @@ def test_gemm_matches_float64_matmul(bita, M, N, K):
 @pytest.mark.parametrize("M,N,K", [(68, 4096, 4096), (68, 22016, 4096), (12, 256, 688), (1, 1024, 256),
                                    # other row counts: 2, 3, 7 and 10 m-tiles per pass, two passes, the wide variant
                                    (25, 4096, 1024), (40, 2048, 4096), (105, 4096, 2048), (170, 1024, 4096),
-                                   (320, 2048, 1024), (25, 57344, 512), (105, 57344, 512), (333, 512, 688)])
+                                   (320, 2048, 1024), (25, 57344, 512), (105, 57344, 512), (333, 512, 688),
+                                   # a last m-tile at most half full keeps both planes in one fragment
+                                   # (rows 1..8 and 65..72); 9, 64 and 73 rows sit just outside
+                                   (3, 2048, 1024), (4, 22016, 512), (5, 1024, 4096), (8, 4096, 688), (9, 1024, 1024),
+                                   (64, 2048, 1024), (65, 4096, 1024), (69, 22016, 512), (72, 1024, 4096), (73, 2048, 688)])
 def test_gemm_two_plane_activation(bita, M, N, K):
     """A = hi + lo (two bf16 planes): the product must match float64 on the summed operand
     to fp32-accumulation accuracy, i.e. the activation rounding is gone."""
