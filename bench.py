@@ -60,7 +60,7 @@ def parse_args():
     return ap.parse_args()
 
 
-# draft-tree templates of the row-count sweep (Sec. 3.3: full trees by per-level top-k, the
+# draft-tree templates of the row-count sweep (Sec. 3.2, compared in Sec. 4.3.4 / Table 4: full trees by per-level top-k, the
 # efficient tree of n*k+1 rows; mask groups on the root only or on every node)
 TREES = {
     "full64": ("full", [4, 3, 2, 1], 64), "full34": ("full", [3, 2, 2, 1], 34), "full16": ("full", [3, 2, 1, 1], 16),

@@ -242,7 +242,10 @@ int bita_prefill(bita_model *m, const bita_kv *kv, const int32_t *d_tokens, int3
  * K/V arguments are one layer's slices laid out as in bita_kv; d_k_tree_lo / d_v_tree_lo
  * are optional second planes of d_k_tree / d_v_tree (the pass rows' K/V before they are
  * rounded to the cache format: value = hi + lo; NULL = zero); d_out
- * [B][R][n_heads*hd] bf16.  d_ws needs bita_attention_workspace_bytes(). */
+ * [B][R][n_heads*hd] bf16; d_out_lo (optional, same shape) receives the rounding residual
+ * of d_out, so that d_out + d_out_lo carries the kernel's fp32 result to about 16 bits, which
+ * is the form bita_verify_step hands to the output projection.  d_ws needs
+ * bita_attention_workspace_bytes(). */
 size_t bita_attention_workspace_bytes(int32_t batch, int32_t rows, int32_t n_heads,
                                       int32_t head_dim, int32_t ctx_hint, int32_t n_prompt);
 int bita_tree_attention(const bita_tree_template *t, const void *d_q, const void *d_q_lo,
@@ -252,9 +255,10 @@ int bita_tree_attention(const bita_tree_template *t, const void *d_q, const void
                         const void *d_prompt_k, const void *d_prompt_v,
                         const int32_t *d_ctx_len, int32_t batch, int32_t n_heads,
                         int32_t n_kv_heads, int32_t head_dim, int32_t n_prompt, int32_t smax,
-                        int32_t ctx_hint, void *d_ws, size_t ws_bytes, void *d_out, void *stream);
+                        int32_t ctx_hint, void *d_ws, size_t ws_bytes, void *d_out, void *d_out_lo,
+                        void *stream);
 
-/* Selection alone (the last kernel of bita_verify_step; Sec. 3.3: the greedy token of every
+/* Selection alone (the last kernel of bita_verify_step; Sec. 3.2: the greedy token of every
  * draft row and the top-kmax candidates of every mask row), for kernel-level tests.
  * d_logits [B][R][vocab] fp32 (device, finite values; -0 counts as +0).  d_argmax [B][T]:
  * index of the largest logit of each of the T tree rows, the lowest index among equal

@@ -79,7 +79,7 @@ def lib():
     L.bita_attention_workspace_bytes.restype = sz
     L.bita_attention_workspace_bytes.argtypes = [i32] * 6
     L.bita_tree_attention.restype = C.c_int
-    L.bita_tree_attention.argtypes = [vp] * 12 + [i32] * 7 + [vp, sz, vp, vp]
+    L.bita_tree_attention.argtypes = [vp] * 12 + [i32] * 7 + [vp, sz, vp, vp, vp]
     L.bita_gemm_workspace_bytes.restype, L.bita_gemm_workspace_bytes.argtypes = sz, [i32, i64, i64]
     L.bita_gemm.restype, L.bita_gemm.argtypes = C.c_int, [vp, vp, i32, i64, i64, vp, i64, vp, sz, vp, vp]
     L.bita_select.restype, L.bita_select.argtypes = C.c_int, [vp, vp, i32, i32, i32, vp, vp, vp, vp]
@@ -405,15 +405,17 @@ def select(tmpl, logits, kmax):
 
 
 def tree_attention(tmpl, q, k_cache, v_cache, k_tree, v_tree, prompt_k, prompt_v, ctx_len, ctx_hint, q_lo=None,
-                   k_tree_lo=None, v_tree_lo=None):
+                   k_tree_lo=None, v_tree_lo=None, two_plane_out=False):
     """q [B][R][Hq][hd]; k/v_cache [B][Hkv][smax][hd]; k/v_tree [B][Hkv][R][hd];
-    prompt_k/v [Hkv][P][hd] or None; q_lo, k_tree_lo, v_tree_lo: optional low bf16 planes.  Returns bf16 [B][R][Hq*hd]."""
+    prompt_k/v [Hkv][P][hd] or None; q_lo, k_tree_lo, v_tree_lo: optional low bf16 planes.  Returns bf16
+    [B][R][Hq*hd], or the pair (hi, lo) of bf16 planes when two_plane_out."""
     B, R, Hq, hd = q.shape
     Hkv, smax = k_cache.shape[1], k_cache.shape[2]
     P = 0 if prompt_k is None else prompt_k.shape[1]
     ws = torch.empty(lib().bita_attention_workspace_bytes(B, R, Hq, hd, int(ctx_hint), P), dtype=torch.uint8, device=q.device)
     out = torch.empty((B, R, Hq * hd), dtype=torch.bfloat16, device=q.device)
+    out_lo = torch.empty_like(out) if two_plane_out else None
     _check(lib().bita_tree_attention(tmpl.handle, _ptr(q), _ptr(q_lo), _ptr(k_cache), _ptr(v_cache), _ptr(k_tree), _ptr(v_tree),
                                      _ptr(k_tree_lo), _ptr(v_tree_lo), _ptr(prompt_k), _ptr(prompt_v), _ptr(ctx_len), B, Hq, Hkv, hd, P, smax,
-                                     int(ctx_hint), _ptr(ws), ws.numel(), _ptr(out), _stream()))
-    return out
+                                     int(ctx_hint), _ptr(ws), ws.numel(), _ptr(out), _ptr(out_lo), _stream()))
+    return (out, out_lo) if two_plane_out else out

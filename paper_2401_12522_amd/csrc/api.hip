@@ -365,7 +365,7 @@ extern "C" int bita_verify_step(bita_model *m, const bita_kv *kv, const bita_tre
         launch_tree_attention(td, q, q_lo, (unsigned char *)kv->k_cache + l * kv_layer_cache,
                               (unsigned char *)kv->v_cache + l * kv_layer_cache, kt, vt, k_lo, v_lo, m->prompt_k[l],
                               m->prompt_v[l], d_ctx_len, batch, c.n_heads, c.n_kv_heads, hd, c.n_prompt, kv->smax,
-                              ap, part_o, part_ml, attn_out, true, pm, s);
+                              ap, part_o, part_ml, attn_out, nullptr, true, pm, s);
         timed_gemm(attn_out, M, nq, m->wo[l], d, partial, d, p_o, s);
         launch_rmsnorm_prep(x, partial, p_o.splits, M, d, m->ffn_norm[l], h, ssq, s);
         // with a single split the gate/up GEMM gates in its own epilogue and writes the slab itself
@@ -430,7 +430,7 @@ extern "C" int bita_tree_attention(const bita_tree_template *t, const void *d_q,
                                    const void *d_k_tree_lo, const void *d_v_tree_lo, const void *d_prompt_k, const void *d_prompt_v, const int32_t *d_ctx_len,
                                    int32_t batch, int32_t n_heads, int32_t n_kv_heads, int32_t head_dim,
                                    int32_t n_prompt, int32_t smax, int32_t ctx_hint, void *d_ws, size_t ws_bytes,
-                                   void *d_out, void *stream) {
+                                   void *d_out, void *d_out_lo, void *stream) {
     if (!t || !d_q || !d_k_cache || !d_v_cache || !d_k_tree || !d_v_tree || !d_ctx_len || !d_ws || !d_out ||
         batch <= 0 || n_heads <= 0 || n_kv_heads <= 0 || n_heads % n_kv_heads || n_prompt < 0 ||
         (n_prompt > 0 && (!d_prompt_k || !d_prompt_v)))
@@ -445,7 +445,7 @@ extern "C" int bita_tree_attention(const bita_tree_template *t, const void *d_q,
     float *part_o = (float *)d_ws, *part_ml = (float *)((unsigned char *)d_ws + align_up(p.part_o_bytes, 256));
     launch_tree_attention(t->dev, d_q, d_q_lo, d_k_cache, d_v_cache, d_k_tree, d_v_tree, d_k_tree_lo, d_v_tree_lo, d_prompt_k, d_prompt_v, d_ctx_len,
                           batch, n_heads, n_kv_heads, head_dim, n_prompt, smax, p, part_o, part_ml, d_out,
-                          false, PageMap{nullptr, 0, 0, 0, 0}, (hipStream_t)stream);
+                          d_out_lo, false, PageMap{nullptr, 0, 0, 0, 0}, (hipStream_t)stream);
     BITA_HIP_CHECK(hipGetLastError());
     return BITA_OK;
 }

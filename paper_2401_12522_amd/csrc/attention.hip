@@ -168,7 +168,7 @@ __global__ __launch_bounds__(ATT_WAVES * 64) __attribute__((amdgpu_waves_per_eu(
     const uint16_t *__restrict__ prompt_k, const uint16_t *__restrict__ prompt_v,
     const int32_t *__restrict__ ctx_len, int batch, int Hq, int Hkv, int P, int smax, int n_splits, int n_mt,
     float scale_log2, float *__restrict__ part_o, float *__restrict__ part_ml, uint16_t *__restrict__ out,
-    int as_fragments, int m_tiles_out, PageMap pm) {
+    uint16_t *__restrict__ out_lo, int as_fragments, int m_tiles_out, PageMap pm) {
     using C = AttCfg<HD, U>;
     constexpr int KSN = C::KSN, NTN = C::NTN, GPR = C::GPR, RPI = C::RPI, NVI = C::NVI;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -580,6 +580,7 @@ __global__ __launch_bounds__(ATT_WAVES * 64) __attribute__((amdgpu_waves_per_eu(
                 *reinterpret_cast<uint2 *>(out + frag_index(1, mrow, k, n_ksteps, m_tiles_out, pack_off)) = pl;
             } else {
                 *reinterpret_cast<uint2 *>(out + (int64_t)mrow * Hq * HD + k) = ph;
+                if (out_lo) *reinterpret_cast<uint2 *>(out_lo + (int64_t)mrow * Hq * HD + k) = pl;
             }
         }
     }
@@ -589,7 +590,7 @@ __global__ __launch_bounds__(ATT_WAVES * 64) __attribute__((amdgpu_waves_per_eu(
 // One thread per 4 head-dim elements; blockDim = (HD/4) * heads_per_block.
 __global__ void attn_merge_kernel(const float *__restrict__ part_o, const float *__restrict__ part_ml,
                                   int R, int Hq, int HD, int n_splits, uint16_t *__restrict__ out,
-                                  int as_fragments, int m_tiles) {
+                                  uint16_t *__restrict__ out_lo, int as_fragments, int m_tiles) {
     const int per_head = HD >> 2;
     const int r = blockIdx.x, b = blockIdx.z;
     const int h = blockIdx.y * (blockDim.x / per_head) + threadIdx.x / per_head, i4 = threadIdx.x % per_head;
@@ -622,6 +623,7 @@ __global__ void attn_merge_kernel(const float *__restrict__ part_o, const float 
         *reinterpret_cast<uint2 *>(out + frag_index(1, mrow, k, n_ksteps, m_tiles, pack_off)) = pl;
     } else {
         *reinterpret_cast<uint2 *>(out + (((int64_t)b * R + r) * Hq + h) * HD + i4 * 4) = ph;
+        if (out_lo) *reinterpret_cast<uint2 *>(out_lo + (((int64_t)b * R + r) * Hq + h) * HD + i4 * 4) = pl;
     }
 }
 
@@ -654,7 +656,7 @@ static void launch_attn_t(const TemplateDev &t, const void *q, const void *q_lo,
                           const void *k_tree, const void *v_tree, const void *k_tree_lo, const void *v_tree_lo,
                           const void *prompt_k, const void *prompt_v, const int32_t *ctx_len, int batch, int Hq,
                           int Hkv, int P, int smax, const AttnPlan &p, float *part_o, float *part_ml, void *out,
-                          bool out_as_fragments, const PageMap &pm, hipStream_t s) {
+                          void *out_lo, bool out_as_fragments, const PageMap &pm, hipStream_t s) {
     using C = AttCfg<HD, U>;
     static bool attr_set = false;
     if (!attr_set) {
@@ -673,7 +675,7 @@ static void launch_attn_t(const TemplateDev &t, const void *q, const void *q_lo,
                        (const uint16_t *)k_tree, (const uint16_t *)v_tree, (const uint16_t *)k_tree_lo,
                        (const uint16_t *)v_tree_lo, (const uint16_t *)prompt_k, (const uint16_t *)prompt_v, ctx_len,
                        batch, Hq, Hkv, P, smax, p.splits, n_mt, scale_log2, part_o, part_ml, (uint16_t *)out,
-                       out_as_fragments ? 1 : 0, (batch * t.rows + 15) / 16, pm);
+                       (uint16_t *)out_lo, out_as_fragments ? 1 : 0, (batch * t.rows + 15) / 16, pm);
 }
 
 void launch_tree_attention(const TemplateDev &t, const void *q, const void *q_lo, const void *k_cache, const void *v_cache,
@@ -681,11 +683,11 @@ void launch_tree_attention(const TemplateDev &t, const void *q, const void *q_lo
                            const void *prompt_k,
                            const void *prompt_v, const int32_t *ctx_len, int batch, int Hq, int Hkv, int hd,
                            int P, int smax, const AttnPlan &p, float *part_o, float *part_ml, void *out,
-                           bool out_as_fragments, const PageMap &pm, hipStream_t s) {
+                           void *out_lo, bool out_as_fragments, const PageMap &pm, hipStream_t s) {
     // grouped-query models: two query heads of a K/V head per workgroup share its chunk loads
     const bool pair = (Hq / Hkv) % 2 == 0;
 #define ATT_LAUNCH_P(HD_, U_, PG_) launch_attn_t<HD_, U_, PG_>(t, q, q_lo, k_cache, v_cache, k_tree, v_tree, k_tree_lo, v_tree_lo, prompt_k, \
-                                                   prompt_v, ctx_len, batch, Hq, Hkv, P, smax, p, part_o, part_ml, out, out_as_fragments, pm, s)
+                                                   prompt_v, ctx_len, batch, Hq, Hkv, P, smax, p, part_o, part_ml, out, out_lo, out_as_fragments, pm, s)
 #define ATT_LAUNCH(HD_, U_) do { if (pm.table) ATT_LAUNCH_P(HD_, U_, true); else ATT_LAUNCH_P(HD_, U_, false); } while (0)
     if (hd == 128) {
         if (pair) ATT_LAUNCH(128, 2); else ATT_LAUNCH(128, 1);
@@ -698,6 +700,6 @@ void launch_tree_attention(const TemplateDev &t, const void *q, const void *q_lo
         const int heads_per_block = (256 / (hd / 4)) < Hq ? (256 / (hd / 4)) : Hq;
         hipLaunchKernelGGL(attn_merge_kernel, dim3(t.rows, (Hq + heads_per_block - 1) / heads_per_block, batch),
                            dim3(heads_per_block * (hd / 4)), 0, s, part_o, part_ml, t.rows,
-                           Hq, hd, p.splits, (uint16_t *)out, out_as_fragments ? 1 : 0, (batch * t.rows + 15) / 16);
+                           Hq, hd, p.splits, (uint16_t *)out, (uint16_t *)out_lo, out_as_fragments ? 1 : 0, (batch * t.rows + 15) / 16);
     }
 }

@@ -149,11 +149,12 @@ void launch_select(const float *logits, int batch, const TemplateDev &t, int voc
 struct PageMap { const int32_t *table; int page_lg, n_pages, max_pages, tbl_cap; };
 struct AttnPlan { int splits; size_t part_o_bytes, part_ml_bytes; };
 AttnPlan attn_plan(int batch, int rows, int n_heads, int hd, int ctx_hint, int n_prompt);
-// k_tree_lo / v_tree_lo: low bf16 plane of the pass rows' K/V (nullable)
+// k_tree_lo / v_tree_lo: low bf16 plane of the pass rows' K/V (nullable); out_lo: low plane of
+// the row-major output (nullable; unused when the output is written as fragments)
 void launch_tree_attention(const TemplateDev &t, const void *q, const void *q_lo, const void *k_cache,
                            const void *v_cache, const void *k_tree, const void *v_tree,
                            const void *k_tree_lo, const void *v_tree_lo,
                            const void *prompt_k, const void *prompt_v, const int32_t *ctx_len,
                            int batch, int n_heads, int n_kv_heads, int hd, int n_prompt, int smax,
-                           const AttnPlan &p, float *part_o, float *part_ml, void *out,
+                           const AttnPlan &p, float *part_o, float *part_ml, void *out, void *out_lo,
                            bool out_as_fragments, const PageMap &pm, hipStream_t s);

@@ -30,8 +30,6 @@
 #include <string.h>
 #include <type_traits>
 
-__device__ uint4 g_zero16 = {0u, 0u, 0u, 0u};   // source for out-of-range A granules
-
 // index of the 1 KiB block holding rows 16t..16t+15, k 32ks..32ks+31 (k-major order)
 __host__ __device__ __forceinline__ int64_t packed_block(int64_t t, int64_t ks, int64_t n_tiles) {
     return ((ks >> 1) * n_tiles + t) * 2 + (ks & 1);
@@ -445,6 +443,20 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
                 reinterpret_cast<uint4 *>(direct.act_frag)[(((int64_t)plane * n_ksteps + (hkg >> 1)) * mt_all + mt0 + i) * 64 +
                                                            (hkg & 1) * 32 + l32] = v;
             }
+            // A feature count that is an odd number of 16-feature halves leaves the second half of
+            // the slab's last k-step without a feature.  Where the grid's columns run past F, the
+            // loop above has stored zeros there (tiles beyond the matrix are not live); where they
+            // end exactly at F, the workgroup that owns the last half clears it here: the down
+            // projection multiplies it by zero-padded weights, and 0 x NaN of stale memory is NaN.
+            const int n_half = F >> 4;
+            if ((n_half & 1) && hk0 + HK == n_half && lane < 32) {
+                for (int pr = wn; pr < 2 * MT; pr += WN) {
+                    const int plane = pr / MT, i = pr % MT;
+                    if (mt0 + i >= mt_all || (PACK && plane == 1 && i == MT - 1)) continue;
+                    reinterpret_cast<uint4 *>(direct.act_frag)[(((int64_t)plane * n_ksteps + (n_half >> 1)) * mt_all + mt0 + i) * 64 +
+                                                               32 + lane] = make_uint4(0u, 0u, 0u, 0u);
+                }
+            }
         }
         return;
     }
@@ -633,7 +645,7 @@ void launch_gemm(const void *a_frag, bool two_planes, int M, int64_t K, const vo
         else launch_gemm_v<1, false>(a_frag, M, K, w, N, out, ldo, p, s, direct);
         return;
     }
-    // Row counts other than the 65..80 of the 64-node tree (Sec. 3.3: 16 or 21 tree rows for
+    // Row counts other than the 65..80 of the 64-node tree (Sec. 4.3.4, Table 4: 16 or 21 tree rows for
     // the efficient tree, 105 rows with a mask group behind each of its nodes): one pass over
     // the weights with 2, 3 or 7 m-tiles, for the planner's two variants.  Beyond 7 m-tiles
     // the weight stream no longer bounds the kernel, and passes of 5 m-tiles (grid z)

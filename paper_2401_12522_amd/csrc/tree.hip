@@ -19,7 +19,8 @@ __global__ void build_tree_kernel(TemplateDev t, const int32_t *__restrict__ roo
         } else if (v < t.n_tree) {
             const int lvl = t.depth[v] - 1 + sh;
             const int row = g * t.n_mask + lvl;
-            tok = (lvl >= 0 && lvl < t.n_mask && row < cand_rows && t.rank[v] < kmax)
+            // g < 0: the previous pass had no mask group to offer (accept writes -1 then): no drafts
+            tok = (g >= 0 && lvl >= 0 && lvl < t.n_mask && row < cand_rows && t.rank[v] < kmax)
                       ? cand[((int64_t)b * cand_rows + row) * kmax + t.rank[v]] : -1;
         } else {
             tok = t.mask_index[v];

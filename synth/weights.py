@@ -3,8 +3,11 @@ both the CPU oracle and the HIP path.
 
 Every matrix, embedding, prompt-prefix tensor and mask embedding is drawn from
 N(0, 0.02) (the paper initialises its learnable embeddings that way, Sec. 4.1.2)
-with a per-tensor seed, then rounded once to bf16.  Norm gains are 1.0.  Matrices
-are stored `[out_features][in_features]`, i.e. y = x @ W.T.
+with a per-tensor seed, then rounded once to bf16.  Norm gains are 1.0 by default
+(`norm_std` = 0); a positive `norm_std` draws every gain as 1 + norm_std * N(0, 1), a
+distinct seeded vector per layer and norm, so that a kernel that ignored a gain, or
+read the wrong one, shows in the parity tests.  Matrices are stored
+`[out_features][in_features]`, i.e. y = x @ W.T.
 """
 import numpy as np
 import torch
@@ -48,9 +51,10 @@ class SynthWeights:
     the oracle reads them back through `numpy()`.
     """
 
-    def __init__(self, cfg, seed=0, device="cpu", std=0.02, prefix_std=None, keep=True):
+    def __init__(self, cfg, seed=0, device="cpu", std=0.02, prefix_std=None, keep=True, norm_std=0.0):
         self.cfg, self.seed, self.device, self.std = cfg, seed, torch.device(device), std
         self.prefix_std = std if prefix_std is None else prefix_std
+        self.norm_std = norm_std
         self.keep = keep
         self._store = {}
 
@@ -59,8 +63,13 @@ class SynthWeights:
         if key in self._store:
             return self._store[key]
         shape = tensor_shape(self.cfg, name)
-        if name.endswith("norm"):
+        if name.endswith("norm") and self.norm_std == 0.0:
             t = torch.ones(shape, dtype=torch.bfloat16, device=self.device)
+        elif name.endswith("norm"):
+            g = torch.Generator(device=self.device)
+            g.manual_seed(tensor_seed(self.seed, layer, name))
+            t = torch.randn(shape, generator=g, device=self.device, dtype=torch.float32)
+            t = (1.0 + self.norm_std * t).to(torch.bfloat16)
         else:
             g = torch.Generator(device=self.device)
             g.manual_seed(tensor_seed(self.seed, layer, name))
@@ -83,6 +92,6 @@ class SynthWeights:
     get = numpy
 
     def clone_cpu(self):
-        other = SynthWeights(self.cfg, self.seed, "cpu", self.std, self.prefix_std)
+        other = SynthWeights(self.cfg, self.seed, "cpu", self.std, self.prefix_std, norm_std=self.norm_std)
         other._store = {k: v.cpu().clone() for k, v in self._store.items()}
         return other

@@ -1,5 +1,5 @@
 """Host-side logic of bench.py, checked on the CPU against the oracle's tree rules
-(Sec. 3.3, Algorithm 1): the planted candidate tables must make the verification accept
+(Sec. 3.2, Algorithm 1): the planted candidate tables must make the verification accept
 exactly the planted number of draft tokens, for every template of the sweep."""
 import os
 import sys

@@ -62,6 +62,7 @@ def test_gemm_two_plane_activation(bita, M, N, K):
 
 def _attention_case(bita, B, Hq, Hkv, hd, P, ctx_lens, tree_parent, attach, n_mask, seed, smax=None,
                     two_plane_q=True):
+    """Returns (worst error of the bf16 output, worst error of output + residual plane)."""
     rng = np.random.default_rng(seed)
     tin = synth.attach_mask_groups(tree_parent, attach, n_mask)
     d = derive_template(tin.parent, tin.is_mask, n_mask)
@@ -83,12 +84,13 @@ def _attention_case(bita, B, Hq, Hkv, hd, P, ctx_lens, tree_parent, attach, n_ma
     tb = lambda a: None if a is None else torch.tensor(a).to(torch.bfloat16).cuda()   # noqa: E731
     out = bita.tree_attention(tmpl, tb(q_hi), tb(kc), tb(vc), tb(kt), tb(vt), tb(pk), tb(pv),
                               torch.tensor(ctx_lens, dtype=torch.int32, device="cuda"), max(ctx_lens),
-                              q_lo=tb(q_lo), k_tree_lo=tb(kt_lo), v_tree_lo=tb(vt_lo))
+                              q_lo=tb(q_lo), k_tree_lo=tb(kt_lo), v_tree_lo=tb(vt_lo), two_plane_out=True)
     torch.cuda.synchronize()
-    out = out.to(torch.float64).cpu().numpy().reshape(B, R, Hq, hd)
+    out, out_lo = (x.to(torch.float64).cpu().numpy().reshape(B, R, Hq, hd) for x in out)
+    out2 = out + out_lo
     if two_plane_q:
         kt, vt = kt + kt_lo, vt + vt_lo                 # what the kernel is given, exactly
-    worst = 0.0
+    worst = worst2 = 0.0
     for b in range(B):
         Lc = ctx_lens[b]
         for r in range(R):
@@ -100,11 +102,18 @@ def _attention_case(bita, B, Hq, Hkv, hd, P, ctx_lens, tree_parent, attach, n_ma
                 vs.insert(0, pv.transpose(1, 0, 2))
             ref = attend_row(q[b, r], np.concatenate(ks), np.concatenate(vs), Hq, Hkv)
             worst = max(worst, np.abs(out[b, r] - ref).max())
-    return worst
+            worst2 = max(worst2, np.abs(out2[b, r] - ref).max())
+    return worst, worst2
 
 
 # bf16 output rounding (2^-9 relative on values of order 1) plus bf16 probabilities: 2e-2 abs
 ATT_TOL = 2e-2
+# Regression bound on the two-plane output (value + rounding residual, the form the step hands to
+# the output projection), about ten times the measured error (3e-7 .. 1.4e-5 over the cases
+# below, 1.4e-6 at the grouped-query benchmark shape).  One key wrongly visible or hidden among a
+# few thousand moves an output by about 1e-3: this bound sees it at every context length of the
+# cases below, the 2e-2 above only at the short ones.
+ATT_TWO_PLANE_REGRESSION = 1e-4
 
 
 @pytest.mark.parametrize("case", [
@@ -123,17 +132,33 @@ ATT_TOL = 2e-2
 ])
 def test_tree_attention_matches_oracle(bita, case):
     parent = synth.random_tree(case["T"], max(case["depth"], 1), 11) if case["T"] > 1 else np.array([-1], np.int32)
-    err = _attention_case(bita, case["B"], case["Hq"], case["Hkv"], case["hd"], case["P"], case["ctx"],
-                          parent, case["attach"], case["n"], seed=5)
+    err, err2 = _attention_case(bita, case["B"], case["Hq"], case["Hkv"], case["hd"], case["P"], case["ctx"],
+                                parent, case["attach"], case["n"], seed=5)
+    print(f"attention {case['Hq']}/{case['Hkv']} heads, ctx {case['ctx']}: bf16 out {err:.2e}, two planes {err2:.2e}", flush=True)
     assert err < ATT_TOL, err
+    assert err2 < ATT_TWO_PLANE_REGRESSION, err2
+
+
+def test_tree_attention_at_the_grouped_query_benchmark_shape(bita):
+    """The kernel-only configuration: 64 query heads on 8 K/V heads, head dim 128, 16 prefix
+    tokens, batch 8 with seeded context lengths uniform in [1024, 4096], 64 tree rows of depth
+    <= 6 plus 4 mask rows, N(0, 1) K/V.  Every row of every sequence against the oracle's
+    attention over its explicit key list."""
+    ctx = [int(x) for x in np.random.default_rng(4).integers(1024, 4097, size=8)]
+    ctx[0], ctx[7] = 4096, 1024                           # both ends of the range are present
+    parent = synth.random_tree(64, 6, 11)
+    err, err2 = _attention_case(bita, 8, 64, 8, 128, 16, ctx, parent, [0], 4, seed=21, smax=4096 + 8)
+    print(f"attention 64/8 heads, batch 8, ctx {ctx}: bf16 out {err:.2e}, two planes {err2:.2e}", flush=True)
+    assert err < ATT_TOL, err
+    assert err2 < ATT_TWO_PLANE_REGRESSION, err2
 
 
 def test_tree_attention_chain_equals_causal(bita):
     """Special case: a chain template is plain causal attention over [cache | chain]."""
-    err = _attention_case(bita, 1, 4, 4, 64, 0, [100], synth.chain_tree(40), [], 4, seed=6)
-    assert err < ATT_TOL, err
-    err = _attention_case(bita, 1, 4, 4, 64, 0, [100], synth.chain_tree(40), [], 4, seed=6, two_plane_q=False)
-    assert err < ATT_TOL, err
+    err, err2 = _attention_case(bita, 1, 4, 4, 64, 0, [100], synth.chain_tree(40), [], 4, seed=6)
+    assert err < ATT_TOL and err2 < ATT_TWO_PLANE_REGRESSION, (err, err2)
+    err, err2 = _attention_case(bita, 1, 4, 4, 64, 0, [100], synth.chain_tree(40), [], 4, seed=6, two_plane_q=False)
+    assert err < ATT_TOL and err2 < ATT_TWO_PLANE_REGRESSION, (err, err2)
 
 
 def test_select_orders_equal_values_by_index(bita):

@@ -12,23 +12,30 @@ from gpu_util import dev_i32, load_cache, round_state
 
 pytestmark = pytest.mark.gpu
 
-LOGIT_TOL = 3e-2
+LOGIT_TOL = 3e-2      # the stated tolerance
 MARGIN = 6e-2
+# Regression bounds beside it, by depth, about ten times the error the path delivers (measured:
+# 1e-4 at one or two layers of the 7B, 13B and 70B widths, 2e-4 at four 70B-shaped layers and at
+# the full 32 layers of the 7B shape; random norm gains and an O(1) prefix change nothing).
+REGRESSION = {1: 1e-3, 2: 1e-3, 4: 2e-3, 32: 3e-3}
 
 
-@pytest.mark.parametrize("name,n_layers,ctx_n,topology", [
-    ("7b", 2, 150, "root"), ("70b", 4, 140, "root"), ("13b", 1, 100, "root"), ("7b", 32, 40, "root"),
-    ("7b", 2, 90, "efficient_per_node"), ("7b", 1, 70, "full_per_node")])
-def test_full_width_step(name, n_layers, ctx_n, topology):
+@pytest.mark.parametrize("name,n_layers,ctx_n,topology,gains", [
+    ("7b", 2, 150, "root", False), ("70b", 4, 140, "root", False), ("13b", 1, 100, "root", False),
+    ("7b", 32, 40, "root", False), ("7b", 2, 90, "efficient_per_node", False), ("7b", 1, 70, "full_per_node", False),
+    ("7b", 2, 150, "root", True), ("70b", 2, 60, "root", True)])
+def test_full_width_step(name, n_layers, ctx_n, topology, gains):
     """Reduced depth for the wide shapes; the 7B shape also at its full depth of 32 layers
     (one step, short context: the oracle's cost is dominated by the 0.9 TFLOP of matmuls).
-    The per-node topologies (Sec. 3.3: a mask group behind every draft node) have 105 rows
+    The per-node topologies (Sec. 3.2: a mask group behind every draft node) have 105 rows
     (efficient tree, n=4, k=5) and 320 rows (64-node full tree): several row slices per GEMM,
-    multi-word ancestor sets."""
+    multi-word ancestor sets.  `gains`: random RMSNorm gains (1 + 0.3 N(0, 1), different for
+    every layer and norm) and an O(1) prompt prefix instead of unit gains and an N(0, 0.02) prefix."""
     import paper_2401_12522_amd as bita
     cfg = synth.get_config(name, n_layers=n_layers)
-    w = synth.SynthWeights(cfg, seed=1, device="cuda")
-    wc = synth.SynthWeights(cfg, seed=1, device="cpu")
+    extra = dict(norm_std=0.3, prefix_std=1.0) if gains else {}
+    w = synth.SynthWeights(cfg, seed=1, device="cuda", **extra)
+    wc = synth.SynthWeights(cfg, seed=1, device="cpu", **extra)
     # the oracle reads the very tensors the GPU drew
     for n in synth.weights.GLOBAL_TENSORS:
         wc._store[(n, None)] = w.torch(n).cpu()
@@ -61,6 +68,7 @@ def test_full_width_step(name, n_layers, ctx_n, topology):
     err = np.abs(lg - ref["logits"]).max()
     print(f"{name} x{n_layers}: logits max-abs err {err:.4f}, max |logit| {np.abs(ref['logits']).max():.2f}", flush=True)
     assert err <= LOGIT_TOL, err
+    assert err <= REGRESSION[n_layers], err
     gpu_greedy = buf.argmax[0].cpu().tolist()
     for r in range(d.T):
         s = np.sort(ref["logits"][r])
