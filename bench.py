@@ -10,6 +10,10 @@ vocab 32000, 16 prompt tokens, 1024-token context, 64-node tree + 4 mask rows, b
 Prints ONE JSON line (see the keys below).  `value` is scored rows per second with every
 input resident in HBM; `hbm_gbps` is the algorithmic bytes of a step (weights + K/V cache
 + prompt prefix) divided by the step time.
+
+With no --workload the line's headline is the 7B-shaped step and a `workloads` entry carries
+the other half of the metric, the LLaMA-2-70B-shaped step (80 layers, 8 K/V heads, 2048-token
+context, 64 steps, compaction included), run in the same process after the first.
 """
 import argparse
 import json
@@ -31,6 +35,13 @@ HBM_PEAK_GBPS = 8000.0
 # gemm_traffic_70b.md), 68 rows, batch 1; counters cannot be collected from inside this process,
 # so the figure is carried as a constant
 GEMM_TRAFFIC_BYTES_PER_LAUNCH = {"7b": 120.9e6, "70b": 459.3e6}
+GEMM_TRAFFIC_SOURCE = {"7b": "profiles/gemm_traffic_7b.md", "70b": "profiles/gemm_traffic_70b.md"}
+# the same kernel's duration as rocprofv3 --kernel-trace --stats sees it (no event pairs between
+# the launches): total GEMM microseconds per step from the committed profile of this workload
+ROCPROF_GEMM = {"7b": ("profiles/llama7b_step_kernel_stats.md", None),
+                "70b": ("profiles/llama70b_step_kernel_stats.md", None)}
+# the second leg of the default run (the metric is quoted on both shapes)
+SECOND_LEG = {"workload": "70b", "steps": 64, "warmup": 8}
 # layer counts of the two oracle passes timed for cpu_baseline (about 10 s of host work at 7B width)
 CPU_SAMPLE_LAYERS = (4, 8)
 
@@ -40,7 +51,9 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=128)
     ap.add_argument("--warmup", type=int, default=8)
-    ap.add_argument("--workload", default="7b", choices=["tiny", "7b", "13b", "70b"])
+    ap.add_argument("--workload", default=None, choices=["tiny", "7b", "13b", "70b"],
+                    help="default: the 7B-shaped step as the headline plus the 70B-shaped step under `workloads`")
+    ap.add_argument("--no-second-leg", action="store_true", help="with no --workload: skip the 70B-shaped leg")
     ap.add_argument("--ctx", type=int, default=None)
     ap.add_argument("--batch", type=int, default=1,
                     help="sequences per step (independent contexts, same template); above 1 the run is "
@@ -120,26 +133,37 @@ def prefill(B, model, kv, cfg, ctx_tokens, chunk=64):
     torch.cuda.synchronize()
 
 
-def cpu_baseline(cfg, wsrc_np, kv_np, tmpl_in, tokens, ctx_len):
-    """Time the oracle on a bounded sample: passes with CPU_SAMPLE_LAYERS[0] and [1] of the
-    model's layers (+ LM head) at full width, extrapolated linearly to the full depth."""
+def cpu_baseline(cfg, wsrc_np, kv_np, tmpl_in, root_token, cand, ctx_len):
+    """Time the oracle's step on a bounded sample: the step's token assignment, the forward with
+    CPU_SAMPLE_LAYERS[0] and [1] of the model's layers (+ LM head) at full width, selection,
+    acceptance walk and K/V commit of those layers; the per-layer cost is extrapolated linearly
+    to the full depth.  The oracle is numpy float64; its matrix products run in numpy's
+    multi-threaded BLAS, whose thread count is reported as `cores`."""
     import oracle
-    from oracle.tree import derive_template, ancestors_or_self
+    from oracle.model import argmax_low, topk_desc
+    from oracle.tree import derive_template, ancestors_or_self, build_tree_tokens, accept_walk, compact_kv
 
     class Src:
         def get(self, name, layer=None):
             return wsrc_np[(name, layer)]
     om = oracle.OracleModel(cfg, Src(), cache_layers=False)
     d = derive_template(tmpl_in.parent, tmpl_in.is_mask, tmpl_in.n_mask)
-    pos = [ctx_len + d.depth[r] for r in range(d.R)]
-    vis = [ancestors_or_self(d.parent, r) for r in range(d.R)]
     ts = []
     na, nb = CPU_SAMPLE_LAYERS
     if cfg.n_layers < nb:
         na, nb = max(1, cfg.n_layers // 2), max(2, cfg.n_layers)
     for nl in (na, nb):
         t0 = time.perf_counter()
-        oracle.forward_rows(om, tokens, d.is_mask, d.mask_index, pos, vis, kv_np[0], kv_np[1], n_layers=nl)
+        tokens = build_tree_tokens(d, root_token, cand, 0, 0)
+        pos = [ctx_len + d.depth[r] for r in range(d.R)]
+        vis = [ancestors_or_self(d.parent, r) for r in range(d.R)]
+        logits, k, v = oracle.forward_rows(om, tokens, d.is_mask, d.mask_index, pos, vis, kv_np[0], kv_np[1], n_layers=nl)
+        greedy = [argmax_low(logits[r]) for r in range(d.T)]
+        for g in range(d.G):
+            for r in d.group_rows[g]:
+                topk_desc(logits[r], d.kmax)
+        path, _ = accept_walk(d, tokens, greedy)
+        compact_kv(kv_np[0][:nl], kv_np[1][:nl], k, v, path)
         ts.append(time.perf_counter() - t0)
     layer = max((ts[1] - ts[0]) / (nb - na), 1e-9)
     head = max(ts[0] - na * layer, 0.0)
@@ -149,18 +173,16 @@ def cpu_baseline(cfg, wsrc_np, kv_np, tmpl_in, tokens, ctx_len):
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
         threads = os.cpu_count() or 1
-    return dict(value=d.R / full, unit="tokens/s", cores=int(threads), kind="oracle",
+    return dict(value=d.R / full, unit="tokens/s", cores=int(threads),
+                kind=f"oracle (numpy float64, matrix products in multi-threaded BLAS on {int(threads)} threads)",
                 ms_per_step=full * 1e3,
-                sample=f"oracle forward of {na} and {nb} of {cfg.n_layers} layers + LM head at full width "
-                       f"({ts[0]:.1f}s + {ts[1]:.1f}s), extrapolated linearly to {cfg.n_layers} layers")
+                sample=f"one oracle step (token assignment, forward, selection, acceptance, K/V commit) with {na} and "
+                       f"{nb} of {cfg.n_layers} layers + LM head at full width ({ts[0]:.1f}s + {ts[1]:.1f}s), the "
+                       f"per-layer time extrapolated linearly to {cfg.n_layers} layers")
 
 
-def main():
-    args = parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
-              file=sys.stderr)
-        sys.exit(2)
+def run_workload(args, workload, steps, warmup, want_cpu_baseline):
+    """One workload from model creation to the result dictionary."""
     import torch
     import synth
     import paper_2401_12522_amd as bita
@@ -176,7 +198,7 @@ def main():
             torch.add(src_t, 1.0, out=dst_t)      # reads n*4 bytes, writes n*4 bytes
         torch.cuda.synchronize()
         del src_t, dst_t
-    cfg = synth.get_config(args.workload)
+    cfg = synth.get_config(workload)
     NB = args.batch
     if NB < 1:
         sys.exit("bench.py: --batch must be at least 1")
@@ -186,9 +208,8 @@ def main():
     if args.page_size and args.mode == "planted":
         print("bench.py: a paged cache runs free (no planted drafts)", file=sys.stderr)
         args.mode = "free"
-    ctx_n = args.ctx or {"tiny": 64, "7b": 1024, "13b": 2048, "70b": 2048}[args.workload]
-    tin = workload_template(synth, cfg, args.workload, args.tree)
-    steps, warmup = args.steps, args.warmup
+    ctx_n = args.ctx or {"tiny": 64, "7b": 1024, "13b": 2048, "70b": 2048}[workload]
+    tin = workload_template(synth, cfg, workload, args.tree)
     R = tin.rows
     children, depth_max = tree_shape(tin)
     total_steps = warmup + steps
@@ -199,7 +220,7 @@ def main():
     w = synth.SynthWeights(cfg, seed=args.seed, device="cuda")
     keep_layers = tuple(range(min(CPU_SAMPLE_LAYERS[1], cfg.n_layers)))
     wsrc_np = {}
-    if not args.no_cpu_baseline:
+    if want_cpu_baseline:
         for l in keep_layers:
             for n in ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down", "attn_norm", "ffn_norm",
                       "prompt_k", "prompt_v"):
@@ -379,9 +400,21 @@ def main():
     g_ms, g_bytes = B.profile_read(n_gemm * prof_steps)
     gemm_avg_us = float(np.mean(g_ms)) * 1e3
     gemm_gbps = float(np.sum(g_bytes)) / (float(np.sum(g_ms)) * 1e-3) / 1e9
+    standard = R == 68 and NB == 1 and not args.page_size
+    prof_file, prof_gemm_us = ROCPROF_GEMM.get(workload, (None, None))
     roofline = {"bound": "hbm", "kernel": "gemm_skinny_kernel (all %d launches of a step)" % n_gemm,
                 "achieved": gemm_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": gemm_gbps / HBM_PEAK_GBPS,
-                "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH.get(args.workload) if (R == 68 and NB == 1) else None,
+                "frac_source": "HIP events recorded by the library around every GEMM launch on the launch stream, "
+                               "%d eager steps run right after the timed graph replays (an event pair adds about "
+                               "3 us to a launch, so this reads lower than rocprofv3)" % prof_steps,
+                "frac_rocprof": (float(np.mean(g_bytes)) * n_gemm / (prof_gemm_us * 1e-6) / 1e9 / HBM_PEAK_GBPS
+                                 if (standard and prof_gemm_us) else None),
+                "frac_rocprof_source": prof_file if (standard and prof_gemm_us) else None,
+                "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH.get(workload) if standard else None,
+                "traffic_source": ("rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of the stand-alone GEMM at this "
+                                   "step's shapes, scaled by a copy kernel, committed in " + GEMM_TRAFFIC_SOURCE[workload]
+                                   + " (a constant in bench.py, not measured by this run)")
+                                  if (standard and workload in GEMM_TRAFFIC_SOURCE) else None,
                 "avg_launch_us": gemm_avg_us,
                 "bytes_per_launch": float(np.mean(g_bytes)),
                 "gemm_ms_per_step": float(np.sum(g_ms)) / prof_steps}
@@ -391,7 +424,7 @@ def main():
         "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": f"llama2-{args.workload}-shaped random-init, ctx {ctx_n}, batch {NB}, "
+        "config": {"workload": f"llama2-{workload}-shaped random-init, ctx {ctx_n}, batch {NB}, "
                                f"{tin.n_tree}-node tree ({args.tree or 'default'}) + {R - tin.n_tree} mask rows, P={cfg.n_prompt}, mode {args.mode}",
                    "rows": R, "batch": NB, "graph": graph is not None, "page_size": args.page_size or None},
         "hbm_gbps": gbps, "hbm_frac_of_peak": gbps / HBM_PEAK_GBPS, "bytes_per_step": bytes_per_step,
@@ -405,12 +438,41 @@ def main():
         "roofline": roofline, "cpu_baseline": None,
     }
 
-    if not args.no_cpu_baseline:
+    if want_cpu_baseline:
         kv_np = ([k_snap[l, 0, :, :ctx0].permute(1, 0, 2).float().cpu().numpy() for l in keep_layers],
                  [v_snap[l, 0, :, :ctx0].permute(1, 0, 2).float().cpu().numpy() for l in keep_layers])
-        tokens = [int(ctx_tokens[-1])] + [int(x) for x in np.random.default_rng(3).integers(0, cfg.vocab, tin.n_tree - 1)] \
-            + list(range(cfg.n_mask))
-        out["cpu_baseline"] = cpu_baseline(cfg, wsrc_np, kv_np, tin, tokens, ctx0)
+        cand = np.random.default_rng(3).integers(0, cfg.vocab, size=(cfg.n_mask, kmax)).astype(np.int32)
+        out["cpu_baseline"] = cpu_baseline(cfg, wsrc_np, kv_np, tin, int(ctx_tokens[-1]), cand, ctx0)
+    return out
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    headline = args.workload or "7b"
+    out = run_workload(args, headline, args.steps, args.warmup, not args.no_cpu_baseline)
+    plain = args.batch == 1 and not args.tree and not args.page_size and args.mode == "planted" and not args.ctx
+    if args.workload is None and not args.no_second_leg and plain:
+        import gc
+        import torch
+        gc.collect()
+        torch.cuda.empty_cache()
+        leg = SECOND_LEG
+        t0 = time.perf_counter()
+        try:
+            res = run_workload(args, leg["workload"], leg["steps"], leg["warmup"], False)
+            keep = ("steps", "warmup", "ms_per_step", "value", "unit", "config", "hbm_gbps", "hbm_frac_of_peak",
+                    "bytes_per_step", "mean_accepted", "generated_tokens_per_s", "planted_resyncs", "one_row_pass_ms",
+                    "speedup_over_one_row_passes", "timed_run_equals_dry_run", "roofline")
+            entry = {k: res[k] for k in keep}
+            entry["includes"] = "build_tree, verify_step, accept, compact_kv per step (one HIP graph)"
+        except Exception as e:                    # the headline stands on its own; say why the leg is absent
+            entry = {"error": f"{type(e).__name__}: {e}"}
+        entry["leg_wall_s"] = time.perf_counter() - t0
+        out["workloads"] = {leg["workload"]: entry}
     print(json.dumps(out))
 
 
