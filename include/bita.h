@@ -277,6 +277,23 @@ int bita_gemm(const void *d_a, const void *d_a_lo, int32_t m_rows, int64_t k, in
               const void *d_w_packed, int64_t n_rows, void *d_ws, size_t ws_bytes, float *d_out,
               void *stream);
 
+/* bita_gemm for callers that cannot allocate or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, kernels and
+ * result (bit for bit) as bita_gemm, minus the workspace: the split-K partial sums and the
+ * re-laid activations live in a static device array of bita_gemm_noalloc_max_scratch_bytes()
+ * = 32 MiB that every GPU the library runs on holds until the process ends.  The call
+ * allocates nothing (no hipMalloc / hipFree, no allocating library routine), only enqueues on
+ * `stream`, and returns BITA_ERR_CAPACITY, with the sizes in bita_last_error(), when the shape
+ * needs more than that (bita_gemm_noalloc_scratch_bytes(m_rows, n_rows, k) says how much a
+ * shape needs).  d_a, d_a_lo, d_w_packed, d_out are device pointers owned by the caller.
+ * All calls on one GPU share that GPU's array, which keeps the last call's contents (nothing in
+ * it needs to start at zero): calls that overlap in time on one GPU, on different streams or
+ * from different threads, race and must be ordered by the caller. */
+size_t bita_gemm_noalloc_max_scratch_bytes(void);
+size_t bita_gemm_noalloc_scratch_bytes(int32_t m_rows, int64_t n_rows, int64_t k);
+int bita_gemm_noalloc(const void *d_a, const void *d_a_lo, int32_t m_rows, int64_t k, int64_t lda,
+                      const void *d_w_packed, int64_t n_rows, float *d_out, void *stream);
+
 /* Measurement aid: while enabled, bita_verify_step brackets each of its GEMM launches with
  * a pair of HIP events on the caller's stream (not usable under graph capture).
  * bita_profile_enable creates the events (up to max_records launches are recorded from the

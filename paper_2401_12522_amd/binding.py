@@ -16,7 +16,8 @@ EXPORTS = [
     "bita_workspace_bytes", "bita_tree_template_create", "bita_tree_template_destroy",
     "bita_tree_template_info", "bita_build_tree", "bita_verify_step", "bita_accept",
     "bita_compact_kv", "bita_prefill_workspace_bytes", "bita_prefill", "bita_attention_workspace_bytes", "bita_tree_attention",
-    "bita_gemm_workspace_bytes", "bita_gemm", "bita_select", "bita_tune_gemm", "bita_profile_enable",
+    "bita_gemm_workspace_bytes", "bita_gemm", "bita_gemm_noalloc_max_scratch_bytes", "bita_gemm_noalloc_scratch_bytes",
+    "bita_gemm_noalloc", "bita_select", "bita_tune_gemm", "bita_profile_enable",
     "bita_profile_disable", "bita_profile_read", "bita_last_error",
 ]
 
@@ -82,6 +83,9 @@ def lib():
     L.bita_tree_attention.argtypes = [vp] * 12 + [i32] * 7 + [vp, sz, vp, vp, vp]
     L.bita_gemm_workspace_bytes.restype, L.bita_gemm_workspace_bytes.argtypes = sz, [i32, i64, i64]
     L.bita_gemm.restype, L.bita_gemm.argtypes = C.c_int, [vp, vp, i32, i64, i64, vp, i64, vp, sz, vp, vp]
+    L.bita_gemm_noalloc_max_scratch_bytes.restype, L.bita_gemm_noalloc_max_scratch_bytes.argtypes = sz, []
+    L.bita_gemm_noalloc_scratch_bytes.restype, L.bita_gemm_noalloc_scratch_bytes.argtypes = sz, [i32, i64, i64]
+    L.bita_gemm_noalloc.restype, L.bita_gemm_noalloc.argtypes = C.c_int, [vp, vp, i32, i64, i64, vp, i64, vp, vp]
     L.bita_select.restype, L.bita_select.argtypes = C.c_int, [vp, vp, i32, i32, i32, vp, vp, vp, vp]
     L.bita_tune_gemm.restype, L.bita_tune_gemm.argtypes = None, [i32, i32]
     L.bita_profile_enable.restype, L.bita_profile_enable.argtypes = C.c_int, [i32]
@@ -389,6 +393,16 @@ def gemm(a, w_packed, n_rows, k=None, a_lo=None):
     ws = torch.empty(lib().bita_gemm_workspace_bytes(m, n_rows, k), dtype=torch.uint8, device=a.device)
     out = torch.empty((m, n_rows), dtype=torch.float32, device=a.device)
     _check(lib().bita_gemm(_ptr(a), _ptr(a_lo), m, k, lda, _ptr(w_packed), n_rows, _ptr(ws), ws.numel(), _ptr(out), _stream()))
+    return out
+
+
+def gemm_noalloc(a, w_packed, n_rows, out, k=None, a_lo=None):
+    """bita_gemm_noalloc: as gemm(), but the library's static scratch replaces the workspace and the
+    caller brings the output (fp32 cuda [M][n_rows]); nothing is allocated by the call."""
+    m, lda = a.shape
+    k = lda if k is None else k
+    assert out.dtype == torch.float32 and out.is_contiguous() and tuple(out.shape) == (m, n_rows)
+    _check(lib().bita_gemm_noalloc(_ptr(a), _ptr(a_lo), m, k, lda, _ptr(w_packed), n_rows, _ptr(out), _stream()))
     return out
 
 

@@ -4,6 +4,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <vector>
 
 static thread_local char g_err[512] = "";
@@ -489,6 +490,76 @@ extern "C" int bita_gemm(const void *d_a, const void *d_a_lo, int32_t m_rows, in
     } else {
         launch_gemm(frag, d_a_lo != nullptr, m_rows, k, d_w_packed, n_rows, (float *)d_ws, n_rows, p, s);
         launch_reduce_partials((const float *)d_ws, p.splits, m_rows, n_rows, n_rows, d_out, RowScale{nullptr, 0, 0.f, 0.f}, s);
+    }
+    BITA_HIP_CHECK(hipGetLastError());
+    return BITA_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// bita_gemm for callers that cannot allocate (HIP graph capture, serving loops, harnesses that
+// forbid hipMalloc): the split-K partial sums and the re-laid activation fragments, which
+// bita_gemm takes from the caller's workspace, live in a static device array instead.  Every GPU
+// holds its own copy of the array at its own address; the address is looked up once per device.
+#define BITA_NOALLOC_SCRATCH_BYTES (32u << 20)
+#define BITA_NOALLOC_MAX_DEVICES 64
+static __device__ __align__(256) unsigned char scratch[BITA_NOALLOC_SCRATCH_BYTES];
+static void *g_scratch_ptr[BITA_NOALLOC_MAX_DEVICES] = {};
+static std::mutex g_scratch_mutex;
+
+// device address of `scratch` on the current device (looked up on the first call per device)
+static int noalloc_scratch(void **ptr) {
+    int dev = -1;
+    BITA_HIP_CHECK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= BITA_NOALLOC_MAX_DEVICES)
+        return bita_set_error(BITA_ERR_UNSUPPORTED, "bita_gemm_noalloc: device ordinal %d outside 0..%d", dev,
+                              BITA_NOALLOC_MAX_DEVICES - 1);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        BITA_HIP_CHECK(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return bita_set_error(BITA_ERR_HIP, "bita_gemm_noalloc: null address for the scratch array on device %d", dev);
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return BITA_OK;
+}
+
+extern "C" size_t bita_gemm_noalloc_max_scratch_bytes(void) { return BITA_NOALLOC_SCRATCH_BYTES; }
+
+extern "C" size_t bita_gemm_noalloc_scratch_bytes(int32_t m_rows, int64_t n_rows, int64_t k) {
+    if (m_rows <= 0 || n_rows <= 0 || k <= 0) return 0;
+    const GemmPlan p = gemm_plan(m_rows, n_rows, k);
+    const size_t part = p.splits > 1 ? align_up((size_t)p.splits * m_rows * n_rows * 4, 256) : 0;
+    return part + frag_bytes(m_rows, k);
+}
+
+extern "C" int bita_gemm_noalloc(const void *d_a, const void *d_a_lo, int32_t m_rows, int64_t k, int64_t lda,
+                                 const void *d_w_packed, int64_t n_rows, float *d_out, void *stream) {
+    if (!d_a || !d_w_packed || !d_out || m_rows <= 0 || k <= 0 || n_rows <= 0 || lda < k)
+        return bita_set_error(BITA_ERR_INVALID_ARG, "bita_gemm_noalloc: bad argument");
+    if (n_rows % 16 || k % 8 || lda % 8)
+        return bita_set_error(BITA_ERR_UNSUPPORTED, "bita_gemm_noalloc: n_rows must be a multiple of 16, k and lda of 8");
+    const GemmPlan p = gemm_plan(m_rows, n_rows, k);
+    const size_t part_bytes = p.splits > 1 ? align_up((size_t)p.splits * m_rows * n_rows * 4, 256) : 0;
+    const size_t need = part_bytes + frag_bytes(m_rows, k);
+    if (need > BITA_NOALLOC_SCRATCH_BYTES)
+        return bita_set_error(BITA_ERR_CAPACITY,
+                              "bita_gemm_noalloc: %d x %lld x %lld needs %zu bytes of scratch (%d k splits), the static "
+                              "buffer holds %u; use bita_gemm with a workspace", m_rows, (long long)n_rows, (long long)k,
+                              need, p.splits, BITA_NOALLOC_SCRATCH_BYTES);
+    void *base = nullptr;
+    if (int rc = noalloc_scratch(&base)) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    float *partial = (float *)base;
+    void *frag = (unsigned char *)base + part_bytes;
+    // nothing in the scratch has to start at zero: the fragment kernel writes every granule the
+    // GEMM reads, and the GEMM writes every partial sum the reduction reads
+    launch_to_fragments(d_a, d_a_lo, m_rows, k, lda, frag, s);
+    if (p.splits == 1) {
+        launch_gemm(frag, d_a_lo != nullptr, m_rows, k, d_w_packed, n_rows, d_out, n_rows, p, s);
+    } else {
+        launch_gemm(frag, d_a_lo != nullptr, m_rows, k, d_w_packed, n_rows, partial, n_rows, p, s);
+        launch_reduce_partials(partial, p.splits, m_rows, n_rows, n_rows, d_out, RowScale{nullptr, 0, 0.f, 0.f}, s);
     }
     BITA_HIP_CHECK(hipGetLastError());
     return BITA_OK;
