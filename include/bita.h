@@ -22,8 +22,8 @@
  *   - Pointers named d_* (and every pointer inside bita_weights / bita_kv) are
  *     DEVICE pointers BORROWED from the caller; the library never frees them.
  *     Pointers without the prefix are HOST pointers, read during the call only.
- *   - `stream` is a hipStream_t passed as void*.  The four step calls only
- *     enqueue work (bita_prefill also waits for the stream, see there): no allocation, no host synchronisation, no host read of
+ *   - `stream` is a hipStream_t passed as void*.  The four step calls and bita_prefill only
+ *     enqueue work: no allocation, no host synchronisation, no host read of
  *     device memory.  Results are valid once the caller has synchronised the
  *     stream.  They may be captured into a HIP graph by the caller.
  *   - Row layout of a pass ("template"): R rows per sequence.  Row 0 is the root
@@ -227,11 +227,16 @@ int bita_compact_kv(const bita_model *m, const bita_kv *kv, const int32_t *d_pat
  *   d_workspace  bita_prefill_workspace_bytes(m, batch, chunk_rows) bytes
  *   d_next_token [B] or NULL    greedy token that follows each sequence's last
  *                               context token (untouched for empty sequences)
- * Host-synchronous: builds its chain templates, enqueues all chunks on `stream`,
- * waits for the stream and frees the templates; not for graph capture.
+ * The chain templates (at most two row counts per call: chunk_rows and the ragged last
+ * chunk) belong to the model handle: bita_prefill_prepare creates them (a device allocation
+ * and a blocking copy each, once per row count; freed by bita_model_destroy).  bita_prefill
+ * itself then only enqueues on `stream`: no allocation, no host synchronisation, so it may
+ * be captured into a HIP graph like the step calls.  Outside capture bita_prefill creates a
+ * missing template itself; on a capturing stream a missing template is INVALID_ARG.
  * Errors: CAPACITY if ctx_hint + n_tokens exceeds smax or max_pos or the
  * workspace is too small (checked before anything is enqueued). */
 size_t bita_prefill_workspace_bytes(const bita_model *m, int32_t batch, int32_t chunk_rows);
+int bita_prefill_prepare(bita_model *m, int32_t n_tokens, int32_t chunk_rows);
 int bita_prefill(bita_model *m, const bita_kv *kv, const int32_t *d_tokens, int32_t n_tokens,
                  const int32_t *d_seq_len, int32_t *d_ctx_len, int32_t batch, int32_t chunk_rows,
                  void *d_workspace, size_t ws_bytes, int32_t *d_next_token, void *stream);
@@ -306,7 +311,11 @@ int  bita_profile_read(int32_t capacity, int32_t *n_records, float *ms, int64_t 
 
 /* Tuning aid: override the GEMM launch heuristic for all later launches of this process
  * (variant = workgroup shape index, splits = split-K factor; a negative value restores the
- * heuristic for that knob).  Not thread-safe; results are unchanged, only speed. */
+ * heuristic for that knob).  Results are unchanged, only speed.
+ * Threads: the step calls, bita_prefill and the kernel-level calls may run from several host
+ * threads at once on different model handles and streams (error text is per thread).  The two
+ * aids, bita_tune_gemm and bita_profile_*, keep process-wide state and must not be called
+ * while another thread is inside the library. */
 void bita_tune_gemm(int32_t variant, int32_t splits);
 
 const char *bita_last_error(void);

@@ -15,7 +15,7 @@ EXPORTS = [
     "bita_packed_bytes", "bita_pack_weight", "bita_model_create", "bita_model_destroy",
     "bita_workspace_bytes", "bita_tree_template_create", "bita_tree_template_destroy",
     "bita_tree_template_info", "bita_build_tree", "bita_verify_step", "bita_accept",
-    "bita_compact_kv", "bita_prefill_workspace_bytes", "bita_prefill", "bita_attention_workspace_bytes", "bita_tree_attention",
+    "bita_compact_kv", "bita_prefill_workspace_bytes", "bita_prefill_prepare", "bita_prefill", "bita_attention_workspace_bytes", "bita_tree_attention",
     "bita_gemm_workspace_bytes", "bita_gemm", "bita_gemm_noalloc_max_scratch_bytes", "bita_gemm_noalloc_scratch_bytes",
     "bita_gemm_noalloc", "bita_select", "bita_tune_gemm", "bita_profile_enable",
     "bita_profile_disable", "bita_profile_read", "bita_last_error",
@@ -75,6 +75,7 @@ def lib():
     L.bita_compact_kv.restype = C.c_int
     L.bita_compact_kv.argtypes = [vp, C.POINTER(_KV), vp, i32, vp, vp, i32, vp]
     L.bita_prefill_workspace_bytes.restype, L.bita_prefill_workspace_bytes.argtypes = sz, [vp, i32, i32]
+    L.bita_prefill_prepare.restype, L.bita_prefill_prepare.argtypes = C.c_int, [vp, i32, i32]
     L.bita_prefill.restype = C.c_int
     L.bita_prefill.argtypes = [vp, C.POINTER(_KV), vp, i32, vp, vp, i32, i32, vp, sz, vp, vp]
     L.bita_attention_workspace_bytes.restype = sz
@@ -349,15 +350,29 @@ def compact_kv(model, kv, ctx_hint, buf, batch, path=None, n_acc=None):
                                  _ptr(kv.ctx_len), batch, _stream()))
 
 
-def prefill(model, kv, ctx_hint, tokens, chunk_rows, seq_len=None, workspace=None):
+def prefill_workspace(model, batch, chunk_rows):
+    """A workspace tensor for prefill() with these sizes."""
+    need = lib().bita_prefill_workspace_bytes(model.handle, batch, chunk_rows)
+    return torch.empty(need, dtype=torch.uint8, device="cuda")
+
+
+def prefill_prepare(model, n_tokens, chunk_rows):
+    """Create the model's chain templates for this chunking ahead of time (needed before a
+    prefill is captured into a graph)."""
+    _check(lib().bita_prefill_prepare(model.handle, int(n_tokens), int(chunk_rows)))
+
+
+def prefill(model, kv, ctx_hint, tokens, chunk_rows, seq_len=None, workspace=None, next_token=None):
     """tokens int32 cuda [B][n]; appends them (row b up to seq_len[b]) to the cache by chunked causal
-    passes.  Returns the greedy token after each sequence's last one, int32 cuda [B]."""
+    passes.  Returns the greedy token after each sequence's last one, int32 cuda [B] (written into
+    next_token when given; with workspace and next_token supplied nothing is allocated here)."""
     batch, n = tokens.shape
     assert tokens.dtype == torch.int32 and tokens.is_contiguous()
     need = lib().bita_prefill_workspace_bytes(model.handle, batch, chunk_rows)
     if workspace is None or workspace.numel() < need:
         workspace = torch.empty(need, dtype=torch.uint8, device=tokens.device)
-    next_token = torch.full((batch,), -1, dtype=torch.int32, device=tokens.device)
+    if next_token is None:
+        next_token = torch.full((batch,), -1, dtype=torch.int32, device=tokens.device)
     d = kv.desc(ctx_hint)
     _check(lib().bita_prefill(model.handle, C.byref(d), _ptr(tokens), n, _ptr(seq_len), _ptr(kv.ctx_len), batch,
                               int(chunk_rows), _ptr(workspace), workspace.numel(), _ptr(next_token), _stream()))

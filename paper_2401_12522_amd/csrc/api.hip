@@ -97,6 +97,7 @@ extern "C" void bita_model_destroy(bita_model *m) {
     if (!m) return;
     if (m->rope_cos) (void)hipFree(m->rope_cos);
     if (m->rope_sin) (void)hipFree(m->rope_sin);
+    for (auto &kv : m->chains) bita_tree_template_destroy(kv.second);
     delete m;
 }
 

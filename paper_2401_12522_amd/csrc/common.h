@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stddef.h>
+#include <map>
+#include <mutex>
 #include <vector>
 #include "../../include/bita.h"
 
@@ -83,6 +85,10 @@ struct bita_model {
     const void *tok_emb, *mask_emb, *final_norm, *lm_head;
     std::vector<const void *> attn_norm, ffn_norm, wqkv, wo, w_gate_up, w_down, prompt_k, prompt_v;
     float *rope_cos = nullptr, *rope_sin = nullptr;     // [max_pos][hd/2]
+    // chain templates of the prefill chunks by row count, created once and kept until the
+    // handle is destroyed (the enqueued kernels read their device arrays)
+    std::mutex chain_mutex;
+    std::map<int, bita_tree_template *> chains;
 };
 
 // ---- kernel launchers (each only enqueues) --------------------------------------

@@ -44,13 +44,38 @@ PrefillWs prefill_layout(const bita_model *m, int batch, int chunk_rows) {
     L.total = off;
     return L;
 }
-int chain_template(int rows, bita_tree_template **out) {
+// The model's chain template of `rows` rows.  Created (device allocation and a blocking copy) the
+// first time a row count is asked for, unless may_create is false: then a missing template is an
+// error, which is how a call under stream capture stays free of allocations.
+int chain_template(bita_model *m, int rows, bool may_create, bita_tree_template **out) {
+    std::lock_guard<std::mutex> lock(m->chain_mutex);
+    auto it = m->chains.find(rows);
+    if (it != m->chains.end()) { *out = it->second; return BITA_OK; }
+    if (!may_create)
+        return bita_set_error(BITA_ERR_INVALID_ARG, "bita_prefill: the stream is capturing and no chain template of %d rows "
+                              "exists yet; call bita_prefill_prepare first", rows);
     std::vector<int32_t> parent(rows);
     std::vector<uint8_t> is_mask(rows, 0);
     for (int i = 0; i < rows; i++) parent[i] = i - 1;
-    return bita_tree_template_create(parent.data(), is_mask.data(), rows, rows, 0, out);
+    bita_tree_template *t = nullptr;
+    if (int rc = bita_tree_template_create(parent.data(), is_mask.data(), rows, rows, 0, &t)) return rc;
+    m->chains[rows] = t;
+    *out = t;
+    return BITA_OK;
 }
 }  // namespace
+
+extern "C" int bita_prefill_prepare(bita_model *m, int32_t n_tokens, int32_t chunk_rows) {
+    if (!m || n_tokens < 0 || chunk_rows <= 0 || chunk_rows > BITA_MAX_ROWS)
+        return bita_set_error(BITA_ERR_INVALID_ARG, "bita_prefill_prepare: null model, n_tokens < 0 or chunk_rows outside 1..%d",
+                              BITA_MAX_ROWS);
+    bita_tree_template *t = nullptr;
+    if (n_tokens >= chunk_rows)
+        if (int rc = chain_template(m, chunk_rows, true, &t)) return rc;
+    if (n_tokens % chunk_rows)
+        if (int rc = chain_template(m, n_tokens % chunk_rows, true, &t)) return rc;
+    return BITA_OK;
+}
 
 extern "C" size_t bita_prefill_workspace_bytes(const bita_model *m, int32_t batch, int32_t chunk_rows) {
     if (!m || batch <= 0 || chunk_rows <= 0 || chunk_rows > BITA_MAX_ROWS) return 0;
@@ -83,23 +108,23 @@ extern "C" int bita_prefill(bita_model *m, const bita_kv *kv, const int32_t *d_t
     int32_t *tok = (int32_t *)(ws + L.tok), *argmax = (int32_t *)(ws + L.argmax);
     int32_t *path = (int32_t *)(ws + L.path), *n_acc = (int32_t *)(ws + L.n_acc);
 
-    // at most two templates: full chunks and the ragged last one
-    bita_tree_template *tmpl[2] = {nullptr, nullptr};
-    int tmpl_rows[2] = {0, 0};
+    // at most two templates (full chunks and the ragged last one), kept in the model handle; a
+    // capturing stream must find them there
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    if (s) (void)hipStreamIsCapturing(s, &cap);
+    (void)hipGetLastError();
+    const bool may_create = cap == hipStreamCaptureStatusNone;
     int rc = BITA_OK;
     for (int done = 0; done < n_tokens && rc == BITA_OK; done += chunk_rows) {
         const int rows = n_tokens - done < chunk_rows ? n_tokens - done : chunk_rows;
-        const int slot = rows == chunk_rows ? 0 : 1;
-        if (tmpl_rows[slot] != rows) {
-            rc = chain_template(rows, &tmpl[slot]);
-            if (rc != BITA_OK) break;
-            tmpl_rows[slot] = rows;
-        }
+        bita_tree_template *tmpl = nullptr;
+        rc = chain_template(m, rows, may_create, &tmpl);
+        if (rc != BITA_OK) break;
         bita_kv chunk_kv = *kv;
         chunk_kv.rows = rows;                           // tree scratch laid out as [L][B][Hkv][rows][hd]
         chunk_kv.ctx_hint = kv->ctx_hint + done;
         prefill_chunk_kernel<<<batch, 256, 0, s>>>(d_tokens, n_tokens, d_seq_len, done, rows, tok, path, n_acc);
-        rc = bita_verify_step(m, &chunk_kv, tmpl[slot], tok, d_ctx_len, batch, ws + L.step, L.tok - L.step, 1,
+        rc = bita_verify_step(m, &chunk_kv, tmpl, tok, d_ctx_len, batch, ws + L.step, L.tok - L.step, 1,
                               argmax, nullptr, nullptr, nullptr, stream);
         if (rc != BITA_OK) break;
         rc = bita_compact_kv(m, &chunk_kv, path, rows, n_acc, d_ctx_len, batch, stream);
@@ -108,13 +133,7 @@ extern "C" int bita_prefill(bita_model *m, const bita_kv *kv, const int32_t *d_t
             prefill_pick_kernel<<<(batch + 255) / 256, 256, 0, s>>>(argmax, d_seq_len, n_tokens, done, rows, batch,
                                                                     d_next_token);
     }
-    // the templates' device arrays are read by the enqueued kernels: drain before freeing them
-    const hipError_t sync = hipStreamSynchronize(s);
-    const hipError_t launch = hipGetLastError();
-    for (int i = 0; i < 2; i++)
-        if (tmpl[i]) bita_tree_template_destroy(tmpl[i]);
     if (rc != BITA_OK) return rc;
-    BITA_HIP_CHECK(sync);
-    BITA_HIP_CHECK(launch);
+    BITA_HIP_CHECK(hipGetLastError());
     return BITA_OK;
 }

@@ -172,3 +172,85 @@ def test_prompt_to_tokens_on_the_device_alone(bita):
     assert upto >= 8, "seed gives an early near-tie; pick another"
     assert emitted[:upto] == ref[:upto]
     assert int(kv.ctx_len[0]) == len(ctx) + sum(lens)
+
+
+def test_prefill_and_first_step_replay_from_one_graph(bita):
+    """bita_prefill allocates nothing and never waits for the stream once the model holds its
+    chain templates: prefill of the prompt and the first step are captured into one HIP graph
+    and replayed on reset state three times, with eager work in between; every replay gives the
+    eager run's bits, and the tokens are the oracle's greedy ones where its margin is decisive."""
+    cfg = synth.get_config("tiny_gqa")
+    tin = synth.attach_mask_groups(synth.random_tree(8, 3, 0), [0], cfg.n_mask)
+    w = synth.SynthWeights(cfg, seed=2, norm_std=0.3, prefix_std=1.0)
+    om = oracle.OracleModel(cfg, w)
+    d = oracle.tree.derive_template(tin.parent, tin.is_mask, tin.n_mask)
+    smax, chunk, n_ctx = 256, 32, 75                     # two full chunks and a ragged one of 11 rows
+    model = bita.Model(cfg, w, max_pos=smax + 64)
+    tmpl = bita.TreeTemplate(tin.parent, tin.is_mask, tin.n_tree, tin.n_mask)
+    kv = bita.KVState(cfg, cfg.n_layers, 1, smax, chunk)
+    kv_step = bita.KVState.__new__(bita.KVState)         # the same memory, laid out for the step's rows
+    kv_step.__dict__.update(kv.__dict__)
+    kv_step.resize_rows(cfg.n_layers, cfg, tmpl.rows)
+    ctx = synth.random_context(cfg.vocab, n_ctx, 5)
+    toks = dev_i32(ctx[None])
+    ws = bita.prefill_workspace(model, 1, chunk)
+    first = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+    buf = bita.StepBuffers(model, tmpl, 1, d.kmax, want_logits=True)
+    shift0 = dev_i32([cfg.n_mask])                       # t = 1: no candidates yet
+
+    def reset():
+        kv.ctx_len.zero_(); kv.k_cache.zero_(); kv.v_cache.zero_(); first.fill_(-1)
+
+    def run():
+        bita.prefill(model, kv, 0, toks, chunk, workspace=ws, next_token=first)
+        bita.decode_step(model, kv_step, n_ctx, tmpl, buf, 1, first, buf.topk_ids, None, shift0)
+
+    bita.prefill_prepare(model, n_ctx, chunk)
+    reset()
+    run()                                                # eager
+    torch.cuda.synchronize()
+    eager = [first.clone(), buf.logits.clone(), buf.bonus.clone(), kv.k_cache.clone(), kv.ctx_len.clone()]
+    assert int(kv.ctx_len[0]) == n_ctx + 1
+    graph = torch.cuda.CUDAGraph()
+    st = torch.cuda.Stream()
+    reset()
+    with torch.cuda.stream(st):
+        with torch.cuda.graph(graph, stream=st):
+            run()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        reset()
+        buf.logits.fill_(7.0)
+        (torch.ones(1 << 20, device="cuda") * 3).sum().item()   # the program's own eager work between replays
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [first, buf.logits, buf.bonus, kv.k_cache, kv.ctx_len]
+        for a, b_ in zip(eager, got):
+            assert torch.equal(a, b_), rep
+    # against the oracle: the token after the prompt
+    _, _, last = _oracle_causal(om, [int(x) for x in ctx])
+    if _margin(last) > MARGIN:
+        assert int(first[0]) == argmax_low(last)
+
+
+def test_prefill_on_a_capturing_stream_needs_its_templates(bita):
+    """A capturing stream that finds no chain template is refused, not served by an allocation."""
+    cfg = synth.get_config("tiny")
+    w = synth.SynthWeights(cfg, seed=1)
+    model = bita.Model(cfg, w, max_pos=128)
+    kv = bita.KVState(cfg, cfg.n_layers, 1, 96, 32)
+    toks = dev_i32(synth.random_context(cfg.vocab, 50, 2)[None])
+    ws = bita.prefill_workspace(model, 1, 32)
+    first = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+    bita.prefill(model, kv, 0, toks, 32, workspace=ws, next_token=first)      # eager: creates 32 and 18
+    torch.cuda.synchronize()
+    kv.ctx_len.zero_()
+    graph, st = torch.cuda.CUDAGraph(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with pytest.raises(bita.BitaError) as e:
+        with torch.cuda.stream(st):
+            with torch.cuda.graph(graph, stream=st):
+                bita.prefill(model, kv, 0, toks, 29, workspace=ws, next_token=first)   # chunks of 29 and 21: unknown
+    assert e.value.code == -1 and "bita_prefill_prepare" in str(e.value)
+    torch.cuda.synchronize()
+    assert int(kv.ctx_len[0]) == 0
