@@ -311,12 +311,17 @@ int  bita_profile_read(int32_t capacity, int32_t *n_records, float *ms, int64_t 
 
 /* Tuning aid: override the GEMM launch heuristic for all later launches of this process
  * (variant = workgroup shape index, splits = split-K factor; a negative value restores the
- * heuristic for that knob).  Results are unchanged, only speed.
+ * heuristic for that knob; variant -2 = the heuristic without tall row passes).  Results are
+ * unchanged, only speed.
  * Threads: the step calls, bita_prefill and the kernel-level calls may run from several host
  * threads at once on different model handles and streams (error text is per thread).  The two
  * aids, bita_tune_gemm and bita_profile_*, keep process-wide state and must not be called
  * while another thread is inside the library. */
 void bita_tune_gemm(int32_t variant, int32_t splits);
+/* What the launch heuristic chooses for an [m_rows] x [n_rows] x [k] GEMM (for tests and
+ * reports): out4 (HOST) = {k splits, workgroup shape index, m-tiles per row pass of a tall
+ * launch (0 = the shape's own row handling: one pass, or passes of 5 m-tiles), k-steps per split}. */
+int bita_gemm_plan_info(int32_t m_rows, int64_t n_rows, int64_t k, int32_t *out4);
 
 const char *bita_last_error(void);
 

@@ -17,7 +17,7 @@ EXPORTS = [
     "bita_tree_template_info", "bita_build_tree", "bita_verify_step", "bita_accept",
     "bita_compact_kv", "bita_prefill_workspace_bytes", "bita_prefill_prepare", "bita_prefill", "bita_attention_workspace_bytes", "bita_tree_attention",
     "bita_gemm_workspace_bytes", "bita_gemm", "bita_gemm_noalloc_max_scratch_bytes", "bita_gemm_noalloc_scratch_bytes",
-    "bita_gemm_noalloc", "bita_select", "bita_tune_gemm", "bita_profile_enable",
+    "bita_gemm_noalloc", "bita_select", "bita_tune_gemm", "bita_gemm_plan_info", "bita_profile_enable",
     "bita_profile_disable", "bita_profile_read", "bita_last_error",
 ]
 
@@ -89,6 +89,7 @@ def lib():
     L.bita_gemm_noalloc.restype, L.bita_gemm_noalloc.argtypes = C.c_int, [vp, vp, i32, i64, i64, vp, i64, vp, vp]
     L.bita_select.restype, L.bita_select.argtypes = C.c_int, [vp, vp, i32, i32, i32, vp, vp, vp, vp]
     L.bita_tune_gemm.restype, L.bita_tune_gemm.argtypes = None, [i32, i32]
+    L.bita_gemm_plan_info.restype, L.bita_gemm_plan_info.argtypes = C.c_int, [i32, i64, i64, vp]
     L.bita_profile_enable.restype, L.bita_profile_enable.argtypes = C.c_int, [i32]
     L.bita_profile_disable.restype, L.bita_profile_disable.argtypes = None, []
     L.bita_profile_read.restype, L.bita_profile_read.argtypes = C.c_int, [i32, vp, vp, vp]
@@ -419,6 +420,13 @@ def gemm_noalloc(a, w_packed, n_rows, out, k=None, a_lo=None):
     assert out.dtype == torch.float32 and out.is_contiguous() and tuple(out.shape) == (m, n_rows)
     _check(lib().bita_gemm_noalloc(_ptr(a), _ptr(a_lo), m, k, lda, _ptr(w_packed), n_rows, _ptr(out), _stream()))
     return out
+
+
+def gemm_plan_info(m_rows, n_rows, k):
+    """{splits, variant, mt_pass, ksteps_per_split} the launch heuristic picks for this GEMM shape."""
+    out = (C.c_int32 * 4)()
+    _check(lib().bita_gemm_plan_info(int(m_rows), int(n_rows), int(k), out))
+    return dict(splits=out[0], variant=out[1], mt_pass=out[2], ksteps_per_split=out[3])
 
 
 def select(tmpl, logits, kmax):

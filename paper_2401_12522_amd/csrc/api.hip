@@ -466,6 +466,13 @@ extern "C" int bita_select(const bita_tree_template *t, const float *d_logits, i
 
 extern "C" void bita_tune_gemm(int32_t variant, int32_t splits) { gemm_force_plan(variant, splits); }
 
+extern "C" int bita_gemm_plan_info(int32_t m_rows, int64_t n_rows, int64_t k, int32_t *out4) {
+    if (!out4 || m_rows <= 0 || n_rows <= 0 || k <= 0) return bita_set_error(BITA_ERR_INVALID_ARG, "bita_gemm_plan_info: bad argument");
+    const GemmPlan p = gemm_plan(m_rows, n_rows, k);
+    out4[0] = p.splits; out4[1] = p.variant; out4[2] = p.mt_pass; out4[3] = p.ksteps_per_split;
+    return BITA_OK;
+}
+
 extern "C" size_t bita_gemm_workspace_bytes(int32_t m_rows, int64_t n_rows, int64_t k) {
     if (m_rows <= 0 || n_rows <= 0 || k <= 0) return 0;
     // split-K partials (never more than 32 splits) + the activations re-laid in fragment order

@@ -108,7 +108,8 @@ __device__ __forceinline__ float row_scale(const RowScale &rs, int m) {
     for (int ch = 0; ch < RMS_MAX_CHUNKS; ch++) tot += ch < rs.chunks ? v[ch] : 0.f;
     return 1.0f / sqrtf(tot * rs.inv_d + rs.eps);
 }
-struct GemmPlan { int splits, ksteps_per_split, variant; };
+// mt_pass: m-tiles per row pass of a tall launch (6..9), 0 = the variant's own row handling
+struct GemmPlan { int splits, ksteps_per_split, variant, mt_pass; };
 // What a GEMM launch with a single split (complete sums in its accumulators) may do instead of
 // storing fp32 partials: apply the deferred RMSNorm row factor and store the result, or apply it
 // and the SwiGLU gating to its tile-interleaved gate/up columns and store the next GEMM's

@@ -28,6 +28,7 @@
 //    (deterministic, no float atomics).
 #include "common.h"
 #include <string.h>
+#include <stdlib.h>
 #include <type_traits>
 
 // index of the 1 KiB block holding rows 16t..16t+15, k 32ks..32ks+31 (k-major order)
@@ -229,24 +230,48 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
             // a k group whose share of the range is shorter than the others' skips the k-steps
             // past its end (wave-uniform)
             if (ks_begin + stage * KC + s >= ks_end) continue;
-            // all LDS reads of the k-step are issued before its first MFMA; fragment f is
-            // waited for with the NF-1-f later reads still in flight
-            constexpr int NF = C::PL * MT - (PACK ? 1 : 0);
-            static_assert(NF <= 16, "lgkmcnt range");
-            bf16x8 a[NF];
-            static_for<0, NF>([&](auto f_c) {
-                constexpr int F = decltype(f_c)::value;
-                a[F] = lds_read_frag<((SLOT * C::NFRAG + F * KC) * 64) * 16>(lds_lane_base + s * 1024);
-            });
-            static_for<0, NF>([&](auto f_c) {
-                constexpr int F = decltype(f_c)::value, i = F % MT;
-                lds_wait_frag<NF - 1 - F>(a[F]);
+            if constexpr (MT <= 5) {
+                // all LDS reads of the k-step are issued before its first MFMA; fragment f is
+                // waited for with the NF-1-f later reads still in flight
+                constexpr int NF = C::PL * MT - (PACK ? 1 : 0);
+                static_assert(NF <= 16, "lgkmcnt range");
+                bf16x8 a[NF];
+                static_for<0, NF>([&](auto f_c) {
+                    constexpr int F = decltype(f_c)::value;
+                    a[F] = lds_read_frag<((SLOT * C::NFRAG + F * KC) * 64) * 16>(lds_lane_base + s * 1024);
+                });
+                static_for<0, NF>([&](auto f_c) {
+                    constexpr int F = decltype(f_c)::value, i = F % MT;
+                    lds_wait_frag<NF - 1 - F>(a[F]);
 #pragma unroll
-                for (int j = 0; j < NW; j++)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                        a[F], __builtin_bit_cast(bf16x8, w[SLOT][j][s]), acc[i][j], 0, 0, 0);
-                __builtin_amdgcn_sched_barrier(0);          // keeps the next fragment's wait behind these MFMAs
-            });
+                    for (int j = 0; j < NW; j++)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                            a[F], __builtin_bit_cast(bf16x8, w[SLOT][j][s]), acc[i][j], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);          // keeps the next fragment's wait behind these MFMAs
+                });
+            } else {
+                // tall passes (6 to 10 m-tiles): the fragments of a k-step are read in batches of
+                // AB, so that the accumulators (MT x NW tiles) leave room for them
+                static_assert(!PACK, "tall passes never pack");
+                constexpr int NF = C::PL * MT, AB = 4, NB = (NF + AB - 1) / AB;
+                static_for<0, NB>([&](auto b_c) {
+                    constexpr int B0 = decltype(b_c)::value * AB, BN = (NF - B0) < AB ? (NF - B0) : AB;
+                    bf16x8 a[BN];
+                    static_for<0, BN>([&](auto f_c) {
+                        constexpr int F = B0 + decltype(f_c)::value;
+                        a[F - B0] = lds_read_frag<((SLOT * C::NFRAG + F * KC) * 64) * 16>(lds_lane_base + s * 1024);
+                    });
+                    static_for<0, BN>([&](auto f_c) {
+                        constexpr int F = B0 + decltype(f_c)::value, i = F % MT;
+                        lds_wait_frag<BN - 1 - (F - B0)>(a[F - B0]);
+#pragma unroll
+                        for (int j = 0; j < NW; j++)
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                                a[F - B0], __builtin_bit_cast(bf16x8, w[SLOT][j][s]), acc[i][j], 0, 0, 0);
+                        __builtin_amdgcn_sched_barrier(0);
+                    });
+                });
+            }
         }
     };
     // One pipeline step for stage c living in slot U: wait for its data (leaving the D-2 newer
@@ -514,10 +539,12 @@ struct GemmVariant { int nw, waves, depth, kgroups; };
 static const GemmVariant g_variants[] = {
     {1, 4, 4, 1}, {2, 4, 4, 1}, {4, 4, 4, 1}, {2, 8, 6, 1}, {4, 8, 6, 1},
     {2, 8, 4, 2}, {4, 8, 4, 2}, {1, 8, 4, 2}, {2, 8, 3, 2}, {2, 16, 3, 2}, {2, 6, 3, 2}, {2, 14, 3, 2},
+    {4, 8, 3, 2},     // 12: tall passes (6 to 9 m-tiles per pass), 16 tiles per k group
 };
 #define GEMM_N_VARIANTS ((int)(sizeof(g_variants) / sizeof(g_variants[0])))
 static int g_force_variant = -1, g_force_splits = -1;
-void gemm_force_plan(int variant, int splits) { g_force_variant = variant; g_force_splits = splits; }
+// variant: >= 0 forces that workgroup shape, -1 the heuristic, -2 the heuristic without tall passes
+void gemm_force_plan(int variant, int splits) { g_force_variant = variant < -2 ? -1 : variant; g_force_splits = splits; }
 
 GemmPlan gemm_plan(int m_rows, int64_t n_rows, int64_t k) {
     GemmPlan p;
@@ -550,8 +577,46 @@ GemmPlan gemm_plan(int m_rows, int64_t n_rows, int64_t k) {
     // workgroups.  The passes fill the CUs, so fewer k splits are needed, and the widest
     // workgroups (16 waves, or 14 on the gate/up-like widths) share each activation fragment
     // among the most weight tiles.
-    const int passes = m_tiles > 7 ? (m_tiles + 4) / 5 : 1;
+    int passes = m_tiles > 7 ? (m_tiles + 4) / 5 : 1;
     if (passes >= 2) p.variant = (NT >= 1024 && NT < 3000) ? 11 : 9;
+    p.mt_pass = 0;
+    // Tall passes (6 to 9 m-tiles per pass, variant 12): fewer passes over the weights and 16
+    // weight tiles per activation fragment, against fewer, fatter workgroups.  What decides is the
+    // traffic through one CU's vector L1 (weights + activation slab of the workgroup's k range) times
+    // the number of rounds the workgroups take on the 256 CUs, plus the split-K partial sums; the
+    // same estimate for both forms, the tall one taken where it predicts at least a fifth less
+    // (measured on the 7B-shaped matrices at 105 to 512 rows: the estimate ranks the forms right
+    // beyond that margin and the choice is then 12 to 36 % faster; inside it they are within 5 %).
+    if (m_tiles >= 6 && g_force_variant == -1) {
+        auto estimate = [&](int mt, int n_pass, int tiles_wg, int *splits_out) {
+            const int64_t wgs_n = (NT + tiles_wg - 1) / tiles_wg;
+            int64_t sp = 256 / (wgs_n * n_pass);
+            if (sp > KS / 8) sp = KS / 8;
+            if (NT < 512 && sp > 8) sp = 8;
+            if (sp > 32) sp = 32;
+            if (g_force_splits > 0) sp = g_force_splits;
+            if (sp < 1) sp = 1;
+            const int64_t per = (KS + sp - 1) / sp;
+            sp = (KS + per - 1) / per;
+            const double per_wg = (double)(tiles_wg + 2 * mt) * 1024.0 * (double)per;
+            const double rounds = (double)((wgs_n * n_pass * sp + 255) / 256);
+            double t = rounds * per_wg / 41e9;                              // ~17 B/clk through one CU's L1
+            if (sp > 1) t += 2.0 * (double)sp * m_rows * (double)n_rows * 4.0 / 4e12;
+            *splits_out = (int)sp;
+            return t;
+        };
+        int sp_now = 1;
+        const GemmVariant &vn = g_variants[m_tiles <= 7 ? 8 : p.variant];
+        const double t_now = estimate(m_tiles <= 7 ? m_tiles : 5, passes, vn.nw * vn.waves / vn.kgroups, &sp_now);
+        double t_best = 0.8 * t_now;
+        for (int cap = 9; cap >= 6; cap--) {
+            const int n_pass = (m_tiles + cap - 1) / cap, mt = (m_tiles + n_pass - 1) / n_pass;
+            if (mt < 6) continue;
+            int sp = 1;
+            const double t = estimate(mt, n_pass, 16, &sp);
+            if (t < t_best) { t_best = t; p.mt_pass = mt; passes = n_pass; p.variant = 12; }
+        }
+    }
     if (g_force_variant >= 0 && g_force_variant < GEMM_N_VARIANTS) p.variant = g_force_variant;
     const GemmVariant &v = g_variants[p.variant];
     const int tiles_wg = v.nw * v.waves / v.kgroups;
@@ -640,6 +705,15 @@ void launch_gemm(const void *a_frag, bool two_planes, int M, int64_t K, const vo
     // direct outputs need complete sums and, for the gating, gate/up tile pairs inside one wave
     if (directp && gemm_direct_output_possible(p, directp->kind)) direct = *directp;
     const int m_tiles = (M + 15) / 16;
+    if (p.mt_pass >= 6 && two_planes) {
+        const bool d = direct.kind != GEMM_OUT_PARTIAL;
+#define TALL(MT_) case MT_: \
+            if (d) launch_gemm_t<MT_, 4, true, 8, 3, 2, true>(a_frag, M, K, w, N, out, ldo, p, s, direct); \
+            else launch_gemm_t<MT_, 4, true, 8, 3, 2, false>(a_frag, M, K, w, N, out, ldo, p, s, direct); \
+            return;
+        switch (p.mt_pass) { TALL(6) TALL(7) TALL(8) TALL(9) }
+#undef TALL
+    }
     if (M <= 16) {
         if (two_planes) launch_gemm_v<1, true>(a_frag, M, K, w, N, out, ldo, p, s, direct);
         else launch_gemm_v<1, false>(a_frag, M, K, w, N, out, ldo, p, s, direct);
@@ -657,12 +731,14 @@ void launch_gemm(const void *a_frag, bool two_planes, int M, int64_t K, const vo
         else launch_gemm_k<7>(a_frag, M, K, w, N, out, ldo, p, s, direct);
         return;
     }
-    if (two_planes) launch_gemm_v<5, true>(a_frag, M, K, w, N, out, ldo, p, s, direct);
-    else launch_gemm_v<5, false>(a_frag, M, K, w, N, out, ldo, p, s, direct);
+    GemmPlan q = p;
+    if (q.variant == 12) q.variant = 9;     // (a single-plane slab has no tall form: passes of 5 m-tiles, same splits)
+    if (two_planes) launch_gemm_v<5, true>(a_frag, M, K, w, N, out, ldo, q, s, direct);
+    else launch_gemm_v<5, false>(a_frag, M, K, w, N, out, ldo, q, s, direct);
 }
 bool gemm_direct_output_possible(const GemmPlan &p, int kind) {
     (void)kind;
-    return p.splits == 1 && (p.variant == 5 || p.variant == 6 || p.variant >= 8);   // even tiles per wave, see launch_gemm_v
+    return p.splits == 1 && (p.variant == 5 || p.variant == 6 || p.variant >= 8);   // (12: four tiles per wave)   // even tiles per wave, see launch_gemm_v
 }
 
 size_t frag_bytes(int m_rows, int64_t k) {                     // two planes

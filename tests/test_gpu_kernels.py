@@ -60,6 +60,39 @@ def test_gemm_two_plane_activation(bita, M, N, K):
     assert np.abs(out - full).max() <= 3e-4 * scale
 
 
+@pytest.mark.parametrize("M,N,K,mt_pass", [(170, 12288, 4096, 6), (105, 57344, 1024, 7), (512, 4096, 11008, 8),
+                                            (265, 22016, 512, 9)])
+def test_gemm_tall_row_passes(bita, M, N, K, mt_pass):
+    """Many-row shapes for which the launch heuristic takes tall row passes (6 to 9 m-tiles per pass
+    and 16 weight tiles per workgroup and k group) instead of passes of 5: with and without a
+    k split, a ragged last m-tile, a last pass shorter than the others."""
+    from paper_2401_12522_amd import binding as BB
+    plan = BB.gemm_plan_info(M, N, K)
+    assert plan["variant"] == 12 and plan["mt_pass"] == mt_pass, plan
+    g = torch.Generator().manual_seed(N + K + M)
+    a32 = torch.randn(M, K, generator=g)
+    hi = a32.to(torch.bfloat16)
+    lo = (a32 - hi.float()).to(torch.bfloat16)
+    w = (torch.randn(N, K, generator=g) * 0.05).to(torch.bfloat16)
+    out = bita.gemm(hi.cuda(), bita.pack_weight(w.cuda()), N, a_lo=lo.cuda()).cpu().numpy()
+    # float64 reference on a seeded sample of 2048 columns (every row): the full product of the
+    # largest case is 46 GFLOP on the host
+    cols = np.sort(np.random.default_rng(M).choice(N, size=min(N, 2048), replace=False))
+    a_sum = (hi.to(torch.float64) + lo.to(torch.float64)).numpy()
+    ref = a_sum @ w[torch.tensor(cols)].to(torch.float64).numpy().T
+    scale = np.abs(ref).max()
+    assert np.isfinite(out).all()
+    assert np.abs(out[:, cols] - ref).max() <= 2e-5 * scale + 1e-6
+    # the columns outside the sample: against the same library run in passes of 5 m-tiles
+    BB.lib().bita_tune_gemm(-2, -1)
+    try:
+        assert BB.gemm_plan_info(M, N, K)["mt_pass"] == 0
+        base = bita.gemm(hi.cuda(), bita.pack_weight(w.cuda()), N, a_lo=lo.cuda()).cpu().numpy()
+    finally:
+        BB.lib().bita_tune_gemm(-1, -1)
+    assert np.abs(out - base).max() <= 2e-5 * scale + 1e-6
+
+
 def _attention_case(bita, B, Hq, Hkv, hd, P, ctx_lens, tree_parent, attach, n_mask, seed, smax=None,
                     two_plane_q=True):
     """Returns (worst error of the bf16 output, worst error of output + residual plane)."""
