@@ -3,6 +3,11 @@ LLaMA-2 configurations, for use under rocprofv3:
 
     python -m paper_2401_12522_amd.gemm_bench 7b-qkv [--rows 68] [--reps 40] [--copy-mb 1024]
 
+`7b-step` / `70b-step` run the five matrices of a layer (and the LM head) one after the other and
+print, beside each, the sum over the launches of one step (layers x four matrices + LM head);
+`--rows` takes a comma-separated list; `--no-tall` restricts many-row launches to passes of 5
+m-tiles (bita_tune_gemm(-2, -1)) for a same-box comparison of the two pass forms.
+
 Each repetition runs on a different copy of the weight matrix (at least 1.5 GB of copies in
 rotation), so that no launch finds its weights in a cache.  --copy-mb also runs a plain
 elementwise kernel that reads and writes that many MB, a launch of known traffic against which
@@ -23,16 +28,42 @@ SHAPES = {
 }
 
 
+LAYERS = {"7b": 32, "70b": 80}
+
+
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("shape", choices=sorted(SHAPES))
-    ap.add_argument("--rows", type=int, default=68)
+    ap.add_argument("shape", choices=sorted(SHAPES) + ["7b-step", "70b-step"])
+    ap.add_argument("--rows", default="68")
     ap.add_argument("--reps", type=int, default=40)
     ap.add_argument("--copy-mb", type=int, default=0)
+    ap.add_argument("--no-tall", action="store_true")
     args = ap.parse_args()
     L = B.lib()
+    if args.no_tall:
+        L.bita_tune_gemm(-2, -1)
+    rows = [int(x) for x in args.rows.split(",")]
+    if args.shape.endswith("-step"):
+        wl = args.shape.split("-")[0]
+        total = {m: 0.0 for m in rows}
+        for name in ("qkv", "o", "gateup", "down", "lm"):
+            for m in rows:
+                us = one(L, f"{wl}-{name}", m, min(args.reps, 12), 0)
+                total[m] += us * (1 if name == "lm" else LAYERS[wl])
+        for m in rows:
+            print(f"{args.shape}: rows {m}: {total[m] / 1e3:.3f} ms for the GEMM launches of one step "
+                  f"({LAYERS[wl]} layers x 4 + LM head; layout and reduction kernels included)")
+        return
+    for m in rows:
+        one(L, args.shape, m, args.reps, args.copy_mb)
+
+
+def one(L, shape, M, reps, copy_mb):
+    class A:
+        pass
+    args = A()
+    args.shape, args.reps, args.copy_mb = shape, reps, copy_mb
     N, K = SHAPES[args.shape]
-    M = args.rows
     nbytes = N * K * 2
     ncopy = max(2, int(1.5e9 // nbytes))
     g = torch.Generator(device="cuda").manual_seed(0)
@@ -64,8 +95,11 @@ def main():
     e1.record()
     torch.cuda.synchronize()
     us = e0.elapsed_time(e1) * 1e3 / args.reps
+    plan = B.gemm_plan_info(M, N, K)
     print(f"{args.shape}: N {N} K {K} rows {M}: {nbytes / 1e6:.1f} MB of weights, {us:.1f} us per call "
-          f"({nbytes / us / 1e6:.2f} TB/s incl. layout and reduction kernels)")
+          f"({nbytes / us / 1e6:.2f} TB/s incl. layout and reduction kernels; workgroup shape {plan['variant']}, "
+          f"{plan['splits']} k splits, {plan['mt_pass'] or '-'} m-tiles per tall pass)", flush=True)
+    return us
 
 
 if __name__ == "__main__":

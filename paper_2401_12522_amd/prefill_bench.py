@@ -41,7 +41,8 @@ def main():
             kv.ctx_len.zero_()
             torch.cuda.synchronize()
             t0 = time.perf_counter()
-            B.prefill(model, kv, 0, toks, chunk, workspace=ws)   # returns after the stream has drained
+            B.prefill(model, kv, 0, toks, chunk, workspace=ws)   # only enqueues: wait for the stream here
+            torch.cuda.synchronize()
             ts.append(time.perf_counter() - t0)
         assert bool((kv.ctx_len == args.ctx).all())
         t = float(np.mean(ts[1:]))
