@@ -81,7 +81,12 @@ def forward_rows(model, tokens, is_mask, mask_index, pos, visible_rows, cache_k,
     """One pass of the decoder over R query rows of one sequence.
 
     tokens[r]      token id of an ordinary row (ignored for mask rows); a negative
-                   id marks an inactive row, embedded as the zero vector.
+                   id marks a row that is absent from this pass (a draft position
+                   for which no candidate exists, Sec. 3.2 / Fig. 3: the mask
+                   predictions that an accept made stale are dropped): it has no
+                   embedding and attends to nothing, so its hidden state, its K/V
+                   and its logits are zero, and no present row ever sees it (its
+                   descendants are absent too).
     is_mask[r]     1 for a mask-token row: it is embedded with mask_emb[mask_index[r]]
                    (Sec. 3.1) and additionally sees the per-layer prompt prefix
                    (Sec. 3.2, tree-based attention).
@@ -116,8 +121,10 @@ def forward_rows(model, tokens, is_mask, mask_index, pos, visible_rows, cache_k,
             q[r] = rope_rotate(q[r], pos[r], cfg.rope_theta)
             k[r] = rope_rotate(k[r], pos[r], cfg.rope_theta)
         pk, pv = model.w("prompt_k", l), model.w("prompt_v", l)     # [Hkv, P, hd]
-        attn = np.empty((R, Hq, hd), F64)
+        attn = np.zeros((R, Hq, hd), F64)
         for r in range(R):
+            if not is_mask[r] and tokens[r] < 0:
+                continue                                   # absent row: nothing to attend with
             parts_k, parts_v = [], []
             if is_mask[r] and cfg.n_prompt > 0:
                 parts_k.append(np.transpose(pk, (1, 0, 2)))

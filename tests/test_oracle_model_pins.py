@@ -144,3 +144,30 @@ def test_topk_and_argmax_tie_rules():
         order = sorted(range(50), key=lambda i: (-r[i], i))[:7]
         assert list(ids) == order
         assert argmax_low(r) == order[0]
+
+
+def test_absent_rows_are_zero_and_invisible():
+    """A tree row without a candidate (negative token) is absent from the pass: zero hidden
+    state, zero K/V, zero logits, and the rows that are present compute exactly what they
+    compute in a pass from which the absent rows are removed."""
+    cfg = synth.get_config("tiny")
+    om = oracle.OracleModel(cfg, synth.SynthWeights(cfg, seed=3, norm_std=0.3, prefix_std=1.0))
+    rng = np.random.default_rng(0)
+    ck = [rng.normal(size=(5, cfg.n_kv_heads, cfg.head_dim)) for _ in range(cfg.n_layers)]
+    cv = [rng.normal(size=(5, cfg.n_kv_heads, cfg.head_dim)) for _ in range(cfg.n_layers)]
+    # root, two children, a grandchild of the second child, one mask row on the root; row 2 and its child 3 absent
+    parent = [-1, 0, 0, 2, 0]
+    is_mask = [0, 0, 0, 0, 1]
+    tokens = [7, 11, -1, -1, 0]
+    pos = [5, 6, 6, 7, 6]
+    vis = [[0], [0, 1], [0, 2], [0, 2, 3], [0, 4]]
+    lg, k, v = oracle.forward_rows(om, tokens, is_mask, [-1, -1, -1, -1, 0], pos, vis, ck, cv)
+    for r in (2, 3):
+        assert np.all(lg[r] == 0)
+        assert all(np.all(k[l][r] == 0) and np.all(v[l][r] == 0) for l in range(cfg.n_layers))
+    keep = [0, 1, 4]
+    lg2, k2, v2 = oracle.forward_rows(om, [7, 11, 0], [0, 0, 1], [-1, -1, 0], [5, 6, 6], [[0], [0, 1], [0, 2]], ck, cv)
+    # (equal up to the summation order of the library matmul at another row count)
+    assert np.allclose(lg[keep], lg2, rtol=1e-11, atol=1e-13)
+    for l in range(cfg.n_layers):
+        assert np.allclose(k[l][keep], k2[l], rtol=1e-11, atol=1e-13) and np.allclose(v[l][keep], v2[l], rtol=1e-11, atol=1e-13)
