@@ -366,7 +366,7 @@ extern "C" int bita_verify_step(bita_model *m, const bita_kv *kv, const bita_tre
                         m->rope_sin, c.max_pos, q, q_lo, kt, vt, k_lo, v_lo, rs_norm, s);
         launch_tree_attention(td, q, q_lo, (unsigned char *)kv->k_cache + l * kv_layer_cache,
                               (unsigned char *)kv->v_cache + l * kv_layer_cache, kt, vt, k_lo, v_lo, m->prompt_k[l],
-                              m->prompt_v[l], d_ctx_len, batch, c.n_heads, c.n_kv_heads, hd, c.n_prompt, kv->smax,
+                              m->prompt_v[l], d_ctx_len, d_token, batch, c.n_heads, c.n_kv_heads, hd, c.n_prompt, kv->smax,
                               ap, part_o, part_ml, attn_out, nullptr, true, pm, s);
         timed_gemm(attn_out, M, nq, m->wo[l], d, partial, d, p_o, s);
         launch_rmsnorm_prep(x, partial, p_o.splits, M, d, m->ffn_norm[l], h, ssq, s);
@@ -445,7 +445,7 @@ extern "C" int bita_tree_attention(const bita_tree_template *t, const void *d_q,
     const size_t need = align_up(p.part_o_bytes, 256) + align_up(p.part_ml_bytes, 256);
     if (ws_bytes < need) return bita_set_error(BITA_ERR_CAPACITY, "bita_tree_attention: workspace %zu < %zu", ws_bytes, need);
     float *part_o = (float *)d_ws, *part_ml = (float *)((unsigned char *)d_ws + align_up(p.part_o_bytes, 256));
-    launch_tree_attention(t->dev, d_q, d_q_lo, d_k_cache, d_v_cache, d_k_tree, d_v_tree, d_k_tree_lo, d_v_tree_lo, d_prompt_k, d_prompt_v, d_ctx_len,
+    launch_tree_attention(t->dev, d_q, d_q_lo, d_k_cache, d_v_cache, d_k_tree, d_v_tree, d_k_tree_lo, d_v_tree_lo, d_prompt_k, d_prompt_v, d_ctx_len, nullptr,
                           batch, n_heads, n_kv_heads, head_dim, n_prompt, smax, p, part_o, part_ml, d_out,
                           d_out_lo, false, PageMap{nullptr, 0, 0, 0, 0}, (hipStream_t)stream);
     BITA_HIP_CHECK(hipGetLastError());

@@ -166,9 +166,9 @@ __global__ __launch_bounds__(ATT_WAVES * 64) __attribute__((amdgpu_waves_per_eu(
     const uint16_t *__restrict__ k_tree, const uint16_t *__restrict__ v_tree,
     const uint16_t *__restrict__ k_tree_lo, const uint16_t *__restrict__ v_tree_lo,
     const uint16_t *__restrict__ prompt_k, const uint16_t *__restrict__ prompt_v,
-    const int32_t *__restrict__ ctx_len, int batch, int Hq, int Hkv, int P, int smax, int n_splits, int n_mt,
-    float scale_log2, float *__restrict__ part_o, float *__restrict__ part_ml, uint16_t *__restrict__ out,
-    uint16_t *__restrict__ out_lo, int as_fragments, int m_tiles_out, PageMap pm) {
+    const int32_t *__restrict__ ctx_len, const int32_t *__restrict__ token, int batch, int Hq, int Hkv, int P, int smax,
+    int n_splits, int n_mt, float scale_log2, float *__restrict__ part_o, float *__restrict__ part_ml,
+    uint16_t *__restrict__ out, uint16_t *__restrict__ out_lo, int as_fragments, int m_tiles_out, PageMap pm) {
     using C = AttCfg<HD, U>;
     constexpr int KSN = C::KSN, NTN = C::NTN, GPR = C::GPR, RPI = C::RPI, NVI = C::NVI;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -237,6 +237,8 @@ __global__ __launch_bounds__(ATT_WAVES * 64) __attribute__((amdgpu_waves_per_eu(
     const int rq = row0 + c;
     const bool row_ok = rq < R;
     const bool row_mask = row_ok && t.is_mask[rq];
+    // a tree row without a candidate (negative token) is absent from the pass: its output is zero
+    const bool row_present = row_ok && (row_mask || !token || token[(int64_t)b * R + rq] >= 0);
     bf16x8 qf[U][2][KSN];
 #pragma unroll
     for (int u = 0; u < U; u++)
@@ -559,11 +561,11 @@ __global__ __launch_bounds__(ATT_WAVES * 64) __attribute__((amdgpu_waves_per_eu(
                     make_float4(o_acc[u][nt][0], o_acc[u][nt][1], o_acc[u][nt][2], o_acc[u][nt][3]);
             if (g == 0) {
                 part_ml[prow * 2] = m_tot;
-                part_ml[prow * 2 + 1] = l_tot;
+                part_ml[prow * 2 + 1] = row_present ? l_tot : 0.f;      // (a zero sum makes the merge write zeros)
             }
             continue;
         }
-        const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+        const float inv = (l_tot > 0.f && row_present) ? 1.0f / l_tot : 0.f;
         const int mrow = b * R + rq, n_ksteps = (Hq * HD) >> 5;
 #pragma unroll
         for (int nt = 0; nt < NTN; nt++) {
@@ -654,7 +656,8 @@ AttnPlan attn_plan(int batch, int rows, int n_heads, int hd, int ctx_hint, int n
 template <int HD, int U, bool PAGED>
 static void launch_attn_t(const TemplateDev &t, const void *q, const void *q_lo, const void *k_cache, const void *v_cache,
                           const void *k_tree, const void *v_tree, const void *k_tree_lo, const void *v_tree_lo,
-                          const void *prompt_k, const void *prompt_v, const int32_t *ctx_len, int batch, int Hq,
+                          const void *prompt_k, const void *prompt_v, const int32_t *ctx_len, const int32_t *token,
+                          int batch, int Hq,
                           int Hkv, int P, int smax, const AttnPlan &p, float *part_o, float *part_ml, void *out,
                           void *out_lo, bool out_as_fragments, const PageMap &pm, hipStream_t s) {
     using C = AttCfg<HD, U>;
@@ -673,7 +676,7 @@ static void launch_attn_t(const TemplateDev &t, const void *q, const void *q_lo,
     hipLaunchKernelGGL((tree_attn_kernel<HD, U, PAGED>), dim3(grid), dim3(ATT_WAVES * 64), smem_bytes, s, t,
                        (const uint16_t *)q, (const uint16_t *)q_lo, (const uint16_t *)k_cache, (const uint16_t *)v_cache,
                        (const uint16_t *)k_tree, (const uint16_t *)v_tree, (const uint16_t *)k_tree_lo,
-                       (const uint16_t *)v_tree_lo, (const uint16_t *)prompt_k, (const uint16_t *)prompt_v, ctx_len,
+                       (const uint16_t *)v_tree_lo, (const uint16_t *)prompt_k, (const uint16_t *)prompt_v, ctx_len, token,
                        batch, Hq, Hkv, P, smax, p.splits, n_mt, scale_log2, part_o, part_ml, (uint16_t *)out,
                        (uint16_t *)out_lo, out_as_fragments ? 1 : 0, (batch * t.rows + 15) / 16, pm);
 }
@@ -681,13 +684,13 @@ static void launch_attn_t(const TemplateDev &t, const void *q, const void *q_lo,
 void launch_tree_attention(const TemplateDev &t, const void *q, const void *q_lo, const void *k_cache, const void *v_cache,
                            const void *k_tree, const void *v_tree, const void *k_tree_lo, const void *v_tree_lo,
                            const void *prompt_k,
-                           const void *prompt_v, const int32_t *ctx_len, int batch, int Hq, int Hkv, int hd,
+                           const void *prompt_v, const int32_t *ctx_len, const int32_t *token, int batch, int Hq, int Hkv, int hd,
                            int P, int smax, const AttnPlan &p, float *part_o, float *part_ml, void *out,
                            void *out_lo, bool out_as_fragments, const PageMap &pm, hipStream_t s) {
     // grouped-query models: two query heads of a K/V head per workgroup share its chunk loads
     const bool pair = (Hq / Hkv) % 2 == 0;
 #define ATT_LAUNCH_P(HD_, U_, PG_) launch_attn_t<HD_, U_, PG_>(t, q, q_lo, k_cache, v_cache, k_tree, v_tree, k_tree_lo, v_tree_lo, prompt_k, \
-                                                   prompt_v, ctx_len, batch, Hq, Hkv, P, smax, p, part_o, part_ml, out, out_lo, out_as_fragments, pm, s)
+                                                   prompt_v, ctx_len, token, batch, Hq, Hkv, P, smax, p, part_o, part_ml, out, out_lo, out_as_fragments, pm, s)
 #define ATT_LAUNCH(HD_, U_) do { if (pm.table) ATT_LAUNCH_P(HD_, U_, true); else ATT_LAUNCH_P(HD_, U_, false); } while (0)
     if (hd == 128) {
         if (pair) ATT_LAUNCH(128, 2); else ATT_LAUNCH(128, 1);

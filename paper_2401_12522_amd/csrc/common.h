@@ -162,6 +162,7 @@ void launch_tree_attention(const TemplateDev &t, const void *q, const void *q_lo
                            const void *v_cache, const void *k_tree, const void *v_tree,
                            const void *k_tree_lo, const void *v_tree_lo,
                            const void *prompt_k, const void *prompt_v, const int32_t *ctx_len,
+                           const int32_t *token /* [B][R] or nullptr: rows with a negative token are absent */,
                            int batch, int n_heads, int n_kv_heads, int hd, int n_prompt, int smax,
                            const AttnPlan &p, float *part_o, float *part_ml, void *out, void *out_lo,
                            bool out_as_fragments, const PageMap &pm, hipStream_t s);
