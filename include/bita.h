@@ -171,11 +171,12 @@ int bita_build_tree(const bita_tree_template *t, const int32_t *d_root_token,
                     int32_t batch, int32_t *d_token, void *stream);
 
 /* One forward pass over B sequences of R rows each (Algorithm 1, the call to F).
- * Row r of sequence b is embedded (tok_emb[token] / mask_emb[index] / zero if
- * inactive), placed at rotary position ctx_len[b] + depth(r), and attends to the
+ * Row r of sequence b is embedded (tok_emb[token] / mask_emb[index]), placed at rotary
+ * position ctx_len[b] + depth(r), and attends to the
  * prompt prefix (mask rows only), to cache slots 0..ctx_len[b]-1 and to its
  * ancestors-or-self among the rows of the pass.  Writes the rows' K/V to
- * kv->k_tree/v_tree.
+ * kv->k_tree/v_tree.  A tree row with a negative token is absent from the pass (no
+ * candidate exists for it): it attends to nothing, and its K/V and logits are zero.
  *   d_argmax   [B][T]            greedy token of every tree row (ties: lowest id)
  *   d_topk_ids [B][G*n][kmax]    top-k of every mask row, value descending, ties by
  *                                lower id (may be NULL if the template has no masks)
