@@ -139,7 +139,7 @@ struct AttCfg {
     static constexpr int KV_BYTES = ATT_CHUNK * HD * 2;       // the K (or V) rows of one chunk
     static constexpr int CHUNK_BYTES = 2 * KV_BYTES;          // one ring slot: [K rows | V rows]
     static constexpr int RING_BYTES = ATT_WAVES * CHUNK_BYTES;       // one buffer per wave
-    static constexpr int MERGE_BYTES = 2 * ATT_WAVES * 16 * 4 + (ATT_WAVES - 1) * NTN * 64 * 16;
+    static constexpr int MERGE_BYTES = 2 * ATT_WAVES * 16 * 4 + ATT_WAVES * NTN * 64 * 16;
     static constexpr int SMEM = RING_BYTES > MERGE_BYTES ? RING_BYTES : MERGE_BYTES;
 };
 
@@ -514,9 +514,11 @@ __global__ __launch_bounds__(ATT_WAVES * 64) __attribute__((amdgpu_waves_per_eu(
     }
     att_wait<0>();
 
-    // ---- merge the wavefronts (disjoint key subsets), head by head; wave 0 sums in wave order ---
+    // ---- merge the wavefronts (disjoint key subsets), head by head: every wave leaves its rescaled
+    //      tiles in LDS, wave nt then sums tile nt of the head dimension over the waves in wave order
+    //      (fixed order, deterministic) and finishes and stores those 16 columns -----------------------
     float *sm = reinterpret_cast<float *>(smem), *sl = sm + ATT_WAVES * 16;
-    float4 *region = reinterpret_cast<float4 *>(smem + 2 * ATT_WAVES * 16 * 4);   // [WAVES-1][NTN][64]
+    float4 *region = reinterpret_cast<float4 *>(smem + 2 * ATT_WAVES * 16 * 4);   // [WAVES][NTN][64]
 #pragma unroll
     for (int u = 0; u < U; u++) {
         const int h = h0 + u;
@@ -536,30 +538,23 @@ __global__ __launch_bounds__(ATT_WAVES * 64) __attribute__((amdgpu_waves_per_eu(
         for (int w = 0; w < ATT_WAVES; w++) l_tot += sl[w * 16 + c] * fast_exp2(sm[w * 16 + c] - m_use);
         const float f = fast_exp2(m_run[u] - m_use);
 #pragma unroll
-        for (int nt = 0; nt < NTN; nt++) o_acc[u][nt] *= f;
-        if (wave > 0) {
-#pragma unroll
-            for (int nt = 0; nt < NTN; nt++)
-                region[((wave - 1) * NTN + nt) * 64 + lane] =
-                    make_float4(o_acc[u][nt][0], o_acc[u][nt][1], o_acc[u][nt][2], o_acc[u][nt][3]);
-        }
+        for (int nt = 0; nt < NTN; nt++)
+            region[(wave * NTN + nt) * 64 + lane] =
+                make_float4(o_acc[u][nt][0] * f, o_acc[u][nt][1] * f, o_acc[u][nt][2] * f, o_acc[u][nt][3] * f);
         __syncthreads();
-        if (wave != 0 || !row_ok) continue;
+        if (wave >= NTN || !row_ok) continue;
+        const int nt = wave;                 // this wave's 16 columns of the head
+        float4 o = region[nt * 64 + lane];
 #pragma unroll
-        for (int w = 1; w < ATT_WAVES; w++)
-#pragma unroll
-            for (int nt = 0; nt < NTN; nt++) {
-                const float4 v = region[((w - 1) * NTN + nt) * 64 + lane];
-                o_acc[u][nt][0] += v.x; o_acc[u][nt][1] += v.y; o_acc[u][nt][2] += v.z; o_acc[u][nt][3] += v.w;
-            }
+        for (int w = 1; w < ATT_WAVES; w++) {
+            const float4 v = region[(w * NTN + nt) * 64 + lane];
+            o.x += v.x; o.y += v.y; o.z += v.z; o.w += v.w;
+        }
         // ---- lane (g, c) holds O[row rq][hd 16nt + 4g .. +4] -----------------------------------
         if (n_splits > 1) {                  // unnormalised partial for attn_merge_kernel
             const int64_t prow = (((int64_t)b * Hq + h) * n_splits + split) * R + rq;
-#pragma unroll
-            for (int nt = 0; nt < NTN; nt++)
-                *reinterpret_cast<float4 *>(part_o + prow * HD + nt * 16 + 4 * g) =
-                    make_float4(o_acc[u][nt][0], o_acc[u][nt][1], o_acc[u][nt][2], o_acc[u][nt][3]);
-            if (g == 0) {
+            *reinterpret_cast<float4 *>(part_o + prow * HD + nt * 16 + 4 * g) = o;
+            if (nt == 0 && g == 0) {
                 part_ml[prow * 2] = m_tot;
                 part_ml[prow * 2 + 1] = row_present ? l_tot : 0.f;      // (a zero sum makes the merge write zeros)
             }
@@ -567,23 +562,21 @@ __global__ __launch_bounds__(ATT_WAVES * 64) __attribute__((amdgpu_waves_per_eu(
         }
         const float inv = (l_tot > 0.f && row_present) ? 1.0f / l_tot : 0.f;
         const int mrow = b * R + rq, n_ksteps = (Hq * HD) >> 5;
+        const float ov[4] = {o.x * inv, o.y * inv, o.z * inv, o.w * inv};
+        uint16_t hi[4], lo[4];
 #pragma unroll
-        for (int nt = 0; nt < NTN; nt++) {
-            uint16_t hi[4], lo[4];
-#pragma unroll
-            for (int e = 0; e < 4; e++) split_bf16(o_acc[u][nt][e] * inv, hi[e], lo[e]);
-            uint2 ph, pl;
-            ph.x = hi[0] | ((uint32_t)hi[1] << 16); ph.y = hi[2] | ((uint32_t)hi[3] << 16);
-            pl.x = lo[0] | ((uint32_t)lo[1] << 16); pl.y = lo[2] | ((uint32_t)lo[3] << 16);
-            const int k = h * HD + nt * 16 + 4 * g;
-            if (as_fragments) {              // two planes, the O-projection's activation slab
-                const int pack_off = frag_pack_offset(batch * R);
-                *reinterpret_cast<uint2 *>(out + frag_index(0, mrow, k, n_ksteps, m_tiles_out, pack_off)) = ph;
-                *reinterpret_cast<uint2 *>(out + frag_index(1, mrow, k, n_ksteps, m_tiles_out, pack_off)) = pl;
-            } else {
-                *reinterpret_cast<uint2 *>(out + (int64_t)mrow * Hq * HD + k) = ph;
-                if (out_lo) *reinterpret_cast<uint2 *>(out_lo + (int64_t)mrow * Hq * HD + k) = pl;
-            }
+        for (int e = 0; e < 4; e++) split_bf16(ov[e], hi[e], lo[e]);
+        uint2 ph, pl;
+        ph.x = hi[0] | ((uint32_t)hi[1] << 16); ph.y = hi[2] | ((uint32_t)hi[3] << 16);
+        pl.x = lo[0] | ((uint32_t)lo[1] << 16); pl.y = lo[2] | ((uint32_t)lo[3] << 16);
+        const int k = h * HD + nt * 16 + 4 * g;
+        if (as_fragments) {                  // two planes, the O-projection's activation slab
+            const int pack_off = frag_pack_offset(batch * R);
+            *reinterpret_cast<uint2 *>(out + frag_index(0, mrow, k, n_ksteps, m_tiles_out, pack_off)) = ph;
+            *reinterpret_cast<uint2 *>(out + frag_index(1, mrow, k, n_ksteps, m_tiles_out, pack_off)) = pl;
+        } else {
+            *reinterpret_cast<uint2 *>(out + (int64_t)mrow * Hq * HD + k) = ph;
+            if (out_lo) *reinterpret_cast<uint2 *>(out_lo + (int64_t)mrow * Hq * HD + k) = pl;
         }
     }
 }
