@@ -161,13 +161,15 @@ __device__ __forceinline__ constexpr int att_swizzle_k(int rho) { return HD == 1
 // copied to LDS (behind the chunk buffers) once per workgroup.
 template <int HD, int U, bool PAGED>
 __global__ __launch_bounds__(ATT_WAVES * 64) __attribute__((amdgpu_waves_per_eu(ATT_WAVES / 4, ATT_WAVES / 4))) void tree_attn_kernel(
-    TemplateDev t, const uint16_t *__restrict__ q, const uint16_t *__restrict__ q_lo,
-    const uint16_t *__restrict__ k_cache, const uint16_t *__restrict__ v_cache,
+    // the first 14 dwords arrive in scalar registers with the wave (kernel-argument preload):
+    // what the workgroup needs to find its work and to issue its first loads comes first
+    const int32_t *__restrict__ ctx_len, int batch, int Hq, int Hkv, int n_mt, int n_splits, int P, int R, int smax,
+    const uint16_t *__restrict__ q, const uint16_t *__restrict__ q_lo,
+    TemplateDev t, const uint16_t *__restrict__ k_cache, const uint16_t *__restrict__ v_cache,
     const uint16_t *__restrict__ k_tree, const uint16_t *__restrict__ v_tree,
     const uint16_t *__restrict__ k_tree_lo, const uint16_t *__restrict__ v_tree_lo,
     const uint16_t *__restrict__ prompt_k, const uint16_t *__restrict__ prompt_v,
-    const int32_t *__restrict__ ctx_len, const int32_t *__restrict__ token, int batch, int Hq, int Hkv, int P, int smax,
-    int n_splits, int n_mt, float scale_log2, float *__restrict__ part_o, float *__restrict__ part_ml,
+    const int32_t *__restrict__ token, float scale_log2, float *__restrict__ part_o, float *__restrict__ part_ml,
     uint16_t *__restrict__ out, uint16_t *__restrict__ out_lo, int as_fragments, int m_tiles_out, PageMap pm) {
     using C = AttCfg<HD, U>;
     constexpr int KSN = C::KSN, NTN = C::NTN, GPR = C::GPR, RPI = C::RPI, NVI = C::NVI;
@@ -188,7 +190,6 @@ __global__ __launch_bounds__(ATT_WAVES * 64) __attribute__((amdgpu_waves_per_eu(
     const int qh = w_in / n_mt;
     const int b = group / Hkv, kvh = group % Hkv, h0 = kvh * qpk + qh * U;   // heads h0 .. h0+U-1
 
-    const int R = t.rows;
     int Lc = ctx_len[b];
     const int32_t *tbl = reinterpret_cast<const int32_t *>(smem + C::SMEM);
     const int page_lg = pm.page_lg, page_mask = (1 << pm.page_lg) - 1;
@@ -234,22 +235,27 @@ __global__ __launch_bounds__(ATT_WAVES * 64) __attribute__((amdgpu_waves_per_eu(
 
     // ---- query fragments (B operand of S^T = K Q^T) stay in registers: lane (g, c) holds
     //      Q[row0 + c][32ks + 8g .. +8] of both planes; rows beyond R are zero
+    //      All loads of this prologue (mask byte, token, query fragments) are unconditional, from
+    //      a clamped row, and their values are first looked at behind the wait for the first chunk:
+    //      one memory round trip instead of one per dependent condition.
     const int rq = row0 + c;
     const bool row_ok = rq < R;
-    const bool row_mask = row_ok && t.is_mask[rq];
-    // a tree row without a candidate (negative token) is absent from the pass: its output is zero
-    const bool row_present = row_ok && (row_mask || !token || token[(int64_t)b * R + rq] >= 0);
+    const int rqc = min(rq, R - 1);
+    const uint32_t mask_byte = t.is_mask[rqc];
+    const int32_t *tok_src = token ? token + (int64_t)b * R + rqc : reinterpret_cast<const int32_t *>(g_att_zero_row);
+    const int32_t tok_val = *tok_src;
+    bool row_mask = false;                               // set behind the first wait
     bf16x8 qf[U][2][KSN];
 #pragma unroll
     for (int u = 0; u < U; u++)
 #pragma unroll
         for (int pl = 0; pl < 2; pl++) {
-            const uint16_t *src = pl ? q_lo : q;
+            const uint16_t *src = (pl && q_lo) ? q_lo : q;
+            const bool live = row_ok && (pl == 0 || q_lo);
 #pragma unroll
             for (int ks = 0; ks < KSN; ks++) {
-                uint4 v = make_uint4(0, 0, 0, 0);
-                if (row_ok && src)
-                    v = *reinterpret_cast<const uint4 *>(src + (((int64_t)b * R + rq) * Hq + h0 + u) * HD + ks * 32 + g * 8);
+                uint4 v = *reinterpret_cast<const uint4 *>(src + (((int64_t)b * R + rqc) * Hq + h0 + u) * HD + ks * 32 + g * 8);
+                if (!live) v = make_uint4(0, 0, 0, 0);
                 qf[u][pl][ks] = __builtin_bit_cast(bf16x8, v);
             }
         }
@@ -508,11 +514,16 @@ __global__ __launch_bounds__(ATT_WAVES * 64) __attribute__((amdgpu_waves_per_eu(
 #pragma unroll
         for (int iv = 0; iv < NVI; iv++) emit(0, iv);
     }
+    att_wait<0>();                                      // the first chunk and the prologue's loads have landed
+    // a tree row without a candidate (negative token) is absent from the pass: its output is zero
+    int row_flags = (row_ok && mask_byte ? 1 : 0) | (row_ok && (mask_byte || tok_val >= 0) ? 2 : 0);
+    asm volatile("" : "+v"(row_flags));                 // (looked at here, not inside the loop)
+    row_mask = (row_flags & 1) != 0;
+    const bool row_present = (row_flags & 2) != 0;
     for (int i = 0; i < n_my; i++) {
-        att_wait<0>();                                  // the chunk has landed
         compute(i, i + 1 < n_my);
+        att_wait<0>();                                  // the next chunk has landed
     }
-    att_wait<0>();
 
     // ---- merge the wavefronts (disjoint key subsets), head by head: every wave leaves its rescaled
     //      tiles in LDS, wave nt then sums tile nt of the head dimension over the waves in wave order
@@ -666,11 +677,12 @@ static void launch_attn_t(const TemplateDev &t, const void *q, const void *q_lo,
     const float scale_log2 = 1.4426950408889634f / sqrtf((float)HD);
     const int groups = batch * Hkv, per_group = (Hq / Hkv / U) * n_mt * p.splits;
     const int grid = 8 * ((groups + 7) / 8) * per_group;
-    hipLaunchKernelGGL((tree_attn_kernel<HD, U, PAGED>), dim3(grid), dim3(ATT_WAVES * 64), smem_bytes, s, t,
-                       (const uint16_t *)q, (const uint16_t *)q_lo, (const uint16_t *)k_cache, (const uint16_t *)v_cache,
+    hipLaunchKernelGGL((tree_attn_kernel<HD, U, PAGED>), dim3(grid), dim3(ATT_WAVES * 64), smem_bytes, s,
+                       ctx_len, batch, Hq, Hkv, n_mt, p.splits, P, t.rows, smax, (const uint16_t *)q, (const uint16_t *)q_lo, t,
+                       (const uint16_t *)k_cache, (const uint16_t *)v_cache,
                        (const uint16_t *)k_tree, (const uint16_t *)v_tree, (const uint16_t *)k_tree_lo,
-                       (const uint16_t *)v_tree_lo, (const uint16_t *)prompt_k, (const uint16_t *)prompt_v, ctx_len, token,
-                       batch, Hq, Hkv, P, smax, p.splits, n_mt, scale_log2, part_o, part_ml, (uint16_t *)out,
+                       (const uint16_t *)v_tree_lo, (const uint16_t *)prompt_k, (const uint16_t *)prompt_v, token,
+                       scale_log2, part_o, part_ml, (uint16_t *)out,
                        (uint16_t *)out_lo, out_as_fragments ? 1 : 0, (batch * t.rows + 15) / 16, pm);
 }
 

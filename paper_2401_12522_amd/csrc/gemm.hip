@@ -106,9 +106,13 @@ struct GemmCfg {
 
 template <int MT, int NW, bool SPLIT, int KC, int D, int WAVES, int KG, bool DIRECT, bool PACK>
 __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
-    const uint4 *__restrict__ A_frag, int planes_stride_f, int M, int m_tiles,
-    const uint4 *__restrict__ Wp, int NT, int KS, float *__restrict__ out, int64_t ldo,
-    int ksteps_per_split, GemmOutput direct) {
+    // The first 14 dwords of the argument block arrive in scalar registers with the wave
+    // (kernel-argument preload); everything the first loads depend on is among them, the grid's
+    // extent included: read through gridDim it costs one dependent scalar load per component
+    // before the first weight load can be issued.
+    const uint4 *__restrict__ A_frag, const uint4 *__restrict__ Wp, int planes_stride_f, int M, int m_tiles,
+    int NT, int KS, int ksteps_per_split, int grid_x, int grid_y, int grid_z,
+    float *__restrict__ out, int64_t ldo, GemmOutput direct) {
     using C = GemmCfg<MT, NW, SPLIT, KC, D, WAVES, KG, PACK>;
     constexpr int WN = C::WN;
     extern __shared__ __attribute__((aligned(16))) uint4 smem_u4[];   // [KG][D][NFRAG][64] + dump slot
@@ -122,9 +126,9 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
     // indices 8 apart and run side by side on that XCD, the later ones finding the weight
     // blocks in its L2 instead of fetching them again.
     int bx = blockIdx.x, by = blockIdx.y, bz = blockIdx.z;
-    if (gridDim.z > 1) {
-        const int X = gridDim.x, Z = gridDim.z, T = X * (int)gridDim.y, Tb = T & ~7;
-        const int L = bx + X * (by + (int)gridDim.y * bz);
+    if (grid_z > 1) {
+        const int X = grid_x, Z = grid_z, T = X * grid_y, Tb = T & ~7;
+        const int L = bx + X * (by + grid_y * bz);
         int pair;
         if (L < Tb * Z) {
             const int q = L >> 3;
@@ -138,11 +142,11 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
         bx = pair % X;
         by = pair / X;
     }
-    else if (gridDim.y > 1) {
+    else if (grid_y > 1) {
         // Split-K launch: workgroups of one k split read the same k range of the activation
         // slab.  With a power-of-two number of splits each split is given to its own XCD(s), so
         // that every k range is fetched into one L2 (or few) instead of all eight.
-        const int X = gridDim.x, Y = gridDim.y, L = bx + X * by;
+        const int X = grid_x, Y = grid_y, L = bx + X * by;
         if ((Y & (Y - 1)) == 0 && ((X * Y) & 7) == 0) {
             if (Y >= 8) {
                 const int per = Y >> 3;                        // splits per XCD
@@ -648,8 +652,8 @@ static void launch_gemm_t(const void *a_frag, int M, int64_t K, const void *w, i
     const int NT = (int)(N / 16), KS = (int)((K + 31) / 32), m_tiles = (M + 15) / 16;
     dim3 grid((NT + C::WN * NW - 1) / (C::WN * NW), p.splits, (m_tiles + MT - 1) / MT);
     hipLaunchKernelGGL((gemm_skinny_kernel<MT, NW, SPLIT, KC, D, WAVES, KG, DIRECT, PACK>), grid, dim3(WAVES * 64), C::SMEM, s,
-                       (const uint4 *)a_frag, KS * m_tiles, M, m_tiles, (const uint4 *)w, NT, KS, out, ldo,
-                       p.ksteps_per_split, direct);
+                       (const uint4 *)a_frag, (const uint4 *)w, KS * m_tiles, M, m_tiles, NT, KS, p.ksteps_per_split,
+                       (int)grid.x, (int)grid.y, (int)grid.z, out, ldo, direct);
 }
 
 template <int MT, bool SPLIT>

@@ -52,11 +52,24 @@ __global__ __launch_bounds__(256) void rmsnorm_prep_kernel(float *__restrict__ x
     float ss = 0.f;
     if (c < (d >> 2)) {
         float4 *xr = reinterpret_cast<float4 *>(x + (int64_t)row * d);
+        // Everything this thread reads is requested before anything is looked at (one memory
+        // round trip): the residual, the gain and the first eight splits (the loads of a group
+        // are independent; indices past the last split re-read it and are left out of the sum).
+        // The partial sums are added in split order.
+        float4 p[8];
+        if (splits > 0) {
+#pragma unroll
+            for (int u = 0; u < 8; u++)
+                p[u] = reinterpret_cast<const float4 *>(partial + ((int64_t)min(u, splits - 1) * M + row) * d)[c];
+        }
         float4 v = xr[c];
-        // eight splits per round trip (the loads of a group are independent; indices past the
-        // last split re-read it and are left out of the sum), summed in split order
-        for (int s0 = 0; s0 < splits; s0 += 8) {
-            float4 p[8];
+        const uint2 gq = reinterpret_cast<const uint2 *>(gain)[c];
+        if (splits > 0) {
+#pragma unroll
+            for (int u = 0; u < 8; u++)
+                if (u < splits) { v.x += p[u].x; v.y += p[u].y; v.z += p[u].z; v.w += p[u].w; }
+        }
+        for (int s0 = 8; s0 < splits; s0 += 8) {
 #pragma unroll
             for (int u = 0; u < 8; u++)
                 p[u] = reinterpret_cast<const float4 *>(partial + ((int64_t)min(s0 + u, splits - 1) * M + row) * d)[c];
@@ -66,7 +79,6 @@ __global__ __launch_bounds__(256) void rmsnorm_prep_kernel(float *__restrict__ x
         }
         if (splits > 0) xr[c] = v;
         ss = v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
-        const uint2 gq = reinterpret_cast<const uint2 *>(gain)[c];
         const float o[4] = {v.x * bf16_to_f32((uint16_t)(gq.x & 0xFFFFu)), v.y * bf16_to_f32((uint16_t)(gq.x >> 16)),
                             v.z * bf16_to_f32((uint16_t)(gq.y & 0xFFFFu)), v.w * bf16_to_f32((uint16_t)(gq.y >> 16))};
         uint16_t hi[4], lo[4];
@@ -91,15 +103,25 @@ __global__ __launch_bounds__(256) void rmsnorm_prep_kernel(float *__restrict__ x
 // k/v into the per-pass tree scratch [B][Hkv][R][hd].  q, k and v are all written as hi and lo
 // bf16 planes; only the hi planes of accepted rows are ever committed to the cache.
 __global__ __launch_bounds__(64) void qkv_rope_kernel(
-    const float *__restrict__ partial, int splits, int M, TemplateDev t, int Hq, int Hkv, int hd,
-    const int32_t *__restrict__ ctx_len, const float *__restrict__ rope_cos,
-    const float *__restrict__ rope_sin, int max_pos, uint16_t *__restrict__ q,
+    // (what the first loads depend on sits in the first 14 dwords, which arrive in registers)
+    const float *__restrict__ partial, const int32_t *__restrict__ ctx_len, const int32_t *__restrict__ depth,
+    const float *__restrict__ rs_ssq, int splits, int M, int R, int Hq, int Hkv, int hd, int max_pos,
+    const float *__restrict__ rope_cos, const float *__restrict__ rope_sin, uint16_t *__restrict__ q,
     uint16_t *__restrict__ q_lo, uint16_t *__restrict__ k_tree, uint16_t *__restrict__ v_tree,
-    uint16_t *__restrict__ k_tree_lo, uint16_t *__restrict__ v_tree_lo, RowScale rs) {
+    uint16_t *__restrict__ k_tree_lo, uint16_t *__restrict__ v_tree_lo, int rs_chunks, float rs_inv_d, float rs_eps) {
     const int row = blockIdx.x, head = blockIdx.y;       // head over Hq + 2*Hkv
-    const int b = row / t.rows, r = row % t.rows;
+    const int b = row / R, r = row % R;
     const int half = hd >> 1, i = threadIdx.x;
     if (i >= half) return;
+    // Two memory round trips: the row's position and the sums behind its norm factor, then the
+    // rotary table entry together with the partial sums (the table is read for value heads too,
+    // and ignored).
+    const int row_ctx = ctx_len[b], row_depth = depth[r];
+    const RowScale rs{rs_ssq, rs_chunks, rs_inv_d, rs_eps};
+    const float sc = row_scale(rs, row);          // RMSNorm's row factor, deferred past the GEMM
+    int pos = row_ctx + row_depth;
+    pos = pos < max_pos ? pos : max_pos - 1;          // host checks capacity; stay in bounds
+    const float tab_c = rope_cos[(int64_t)pos * half + i], tab_s = rope_sin[(int64_t)pos * half + i];
     const int64_t ncols = (int64_t)(Hq + 2 * Hkv) * hd;
     const int64_t col = (int64_t)head * hd + i;
     float lo = 0.f, hi = 0.f;
@@ -115,7 +137,6 @@ __global__ __launch_bounds__(64) void qkv_rope_kernel(
         for (int u = 0; u < 8; u++)
             if (s0 + u < splits) { lo += pl[u]; hi += ph[u]; }
     }
-    const float sc = row_scale(rs, row);          // RMSNorm's row factor, deferred past the GEMM
     lo *= sc;
     hi *= sc;
     uint16_t *dst, *dst_lo = nullptr;
@@ -123,19 +144,16 @@ __global__ __launch_bounds__(64) void qkv_rope_kernel(
         dst = q + ((int64_t)row * Hq + head) * hd;
         dst_lo = q_lo + ((int64_t)row * Hq + head) * hd;
     } else if (head < Hq + Hkv) {
-        const int64_t o = (((int64_t)b * Hkv + (head - Hq)) * t.rows + r) * hd;
+        const int64_t o = (((int64_t)b * Hkv + (head - Hq)) * R + r) * hd;
         dst = k_tree + o;
         dst_lo = k_tree_lo + o;      // the pass keeps the rounding residual of its own K/V rows
     } else {
-        const int64_t o = (((int64_t)b * Hkv + (head - Hq - Hkv)) * t.rows + r) * hd;
+        const int64_t o = (((int64_t)b * Hkv + (head - Hq - Hkv)) * R + r) * hd;
         dst = v_tree + o;
         dst_lo = v_tree_lo + o;
     }
     if (head < Hq + Hkv) {
-        int pos = ctx_len[b] + t.depth[r];
-        pos = pos < max_pos ? pos : max_pos - 1;          // host checks capacity; stay in bounds
-        const float c = rope_cos[(int64_t)pos * half + i], sn = rope_sin[(int64_t)pos * half + i];
-        const float nlo = lo * c - hi * sn, nhi = hi * c + lo * sn;
+        const float nlo = lo * tab_c - hi * tab_s, nhi = hi * tab_c + lo * tab_s;
         lo = nlo;
         hi = nhi;
     }
@@ -302,10 +320,10 @@ void launch_qkv_rope(const float *partial, int splits, int batch, const Template
                      int Hkv, int hd, const int32_t *ctx_len, const float *rope_cos,
                      const float *rope_sin, int max_pos, void *q, void *q_lo, void *k_tree, void *v_tree,
                      void *k_tree_lo, void *v_tree_lo, const RowScale &rs, hipStream_t s) {
-    hipLaunchKernelGGL(qkv_rope_kernel, dim3(batch * t.rows, Hq + 2 * Hkv), dim3(64), 0, s, partial,
-                       splits, batch * t.rows, t, Hq, Hkv, hd, ctx_len, rope_cos, rope_sin, max_pos,
+    hipLaunchKernelGGL(qkv_rope_kernel, dim3(batch * t.rows, Hq + 2 * Hkv), dim3(64), 0, s, partial, ctx_len, t.depth,
+                       rs.ssq, splits, batch * t.rows, t.rows, Hq, Hkv, hd, max_pos, rope_cos, rope_sin,
                        (uint16_t *)q, (uint16_t *)q_lo, (uint16_t *)k_tree, (uint16_t *)v_tree,
-                       (uint16_t *)k_tree_lo, (uint16_t *)v_tree_lo, rs);
+                       (uint16_t *)k_tree_lo, (uint16_t *)v_tree_lo, rs.chunks, rs.inv_d, rs.eps);
 }
 void launch_silu_mul(const float *partial, int splits, int M, int F, void *act_frag, const RowScale &rs,
                      hipStream_t s) {
