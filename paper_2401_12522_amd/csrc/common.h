@@ -94,20 +94,29 @@ struct bita_model {
 // ---- kernel launchers (each only enqueues) --------------------------------------
 #define RMS_MAX_CHUNKS 16          // 1024 columns each: d_model <= 16384
 struct RowScale { const float *ssq; int chunks; float inv_d, eps; };   // ssq == nullptr: no scaling
-// second half of RMSNorm: rsqrt(mean(x^2) + eps) of row m from the per-chunk sums of squares
-__device__ __forceinline__ float row_scale(const RowScale &rs, int m) {
-    if (!rs.ssq) return 1.0f;
-    // all 16 slots of the row are fetched at once (independent loads, one round trip) and summed
-    // in chunk order; slots at or beyond rs.chunks are never written and are left out
+// second half of RMSNorm: rsqrt(mean(x^2) + eps) of row m from the per-chunk sums of squares.
+// In two steps, so that a kernel can request the sums early and look at them late: all 16 slots of
+// the row are fetched at once (independent loads, one round trip) and summed in chunk order;
+// slots at or beyond rs.chunks are never written and are left out.
+struct RowScaleSums { float4 q0, q1, q2, q3; };
+__device__ __forceinline__ RowScaleSums row_scale_fetch(const RowScale &rs, int m) {
+    RowScaleSums r;
+    r.q0 = r.q1 = r.q2 = r.q3 = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (!rs.ssq) return r;
     const float4 *p = reinterpret_cast<const float4 *>(rs.ssq + (int64_t)m * RMS_MAX_CHUNKS);
-    const float4 q0 = p[0], q1 = p[1], q2 = p[2], q3 = p[3];
-    const float v[RMS_MAX_CHUNKS] = {q0.x, q0.y, q0.z, q0.w, q1.x, q1.y, q1.z, q1.w,
-                                     q2.x, q2.y, q2.z, q2.w, q3.x, q3.y, q3.z, q3.w};
+    r.q0 = p[0]; r.q1 = p[1]; r.q2 = p[2]; r.q3 = p[3];
+    return r;
+}
+__device__ __forceinline__ float row_scale_finish(const RowScale &rs, const RowScaleSums &r) {
+    if (!rs.ssq) return 1.0f;
+    const float v[RMS_MAX_CHUNKS] = {r.q0.x, r.q0.y, r.q0.z, r.q0.w, r.q1.x, r.q1.y, r.q1.z, r.q1.w,
+                                     r.q2.x, r.q2.y, r.q2.z, r.q2.w, r.q3.x, r.q3.y, r.q3.z, r.q3.w};
     float tot = 0.f;
 #pragma unroll
     for (int ch = 0; ch < RMS_MAX_CHUNKS; ch++) tot += ch < rs.chunks ? v[ch] : 0.f;
     return 1.0f / sqrtf(tot * rs.inv_d + rs.eps);
 }
+__device__ __forceinline__ float row_scale(const RowScale &rs, int m) { return row_scale_finish(rs, row_scale_fetch(rs, m)); }
 // mt_pass: m-tiles per row pass of a tall launch (6..9), 0 = the variant's own row handling
 struct GemmPlan { int splits, ksteps_per_split, variant, mt_pass; };
 // What a GEMM launch with a single split (complete sums in its accumulators) may do instead of

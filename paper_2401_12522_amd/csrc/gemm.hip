@@ -309,7 +309,23 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
         return c;
     };
 
+    // A launch that finishes its own output needs the row factors of its rows at the end.  The sums
+    // behind them are requested here, ahead of the first stages' loads (every thread fetches, from
+    // a clamped row, and where there is nothing to fetch from the slab instead: no branch around
+    // the loads), and reduced to the one factor right behind those loads, where the wave has to
+    // wait for its first stage anyway: a single register lives through the loop.
+    RowScaleSums my_row_sums;
+    if constexpr (DIRECT) {
+        const bool have = direct.kind != GEMM_OUT_PARTIAL && direct.rs.ssq != nullptr;
+        const float4 *src = have ? reinterpret_cast<const float4 *>(direct.rs.ssq + (int64_t)min(m_base + (tid % (MT * 16)), M - 1) * RMS_MAX_CHUNKS)
+                                 : reinterpret_cast<const float4 *>(A_frag);
+        my_row_sums.q0 = src[0]; my_row_sums.q1 = src[1]; my_row_sums.q2 = src[2]; my_row_sums.q3 = src[3];
+    }
     static_for<0, D - 1>([&](auto u_c) { issue(u_c, decltype(u_c)::value); });
+    float my_row_scale = 0.f;
+    if constexpr (DIRECT) {
+        if (direct.kind != GEMM_OUT_PARTIAL && m_base + (tid % (MT * 16)) < M) my_row_scale = row_scale_finish(direct.rs, my_row_sums);
+    }
     int c;
     if (KG > 1 && (kg & 1)) c = main_loop(std::true_type{});
     else c = main_loop(std::false_type{});
@@ -411,7 +427,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
         float *scale_lds = reinterpret_cast<float *>(smem_u4 + (C::SMEM - 1024) / 16);   // the dump slot
         if constexpr (KG == 1) wait_vmcnt_lds<0>();          // (KG > 1: done before the merge)
         __syncthreads();
-        if (tid < MT * 16) scale_lds[tid] = (m_base + tid < M) ? row_scale(direct.rs, m_base + tid) : 0.f;
+        if (tid < MT * 16) scale_lds[tid] = my_row_scale;
         __syncthreads();
         float sc[MT][4];
 #pragma unroll
