@@ -38,8 +38,8 @@ GEMM_TRAFFIC_BYTES_PER_LAUNCH = {"7b": 120.9e6, "70b": 459.3e6}
 GEMM_TRAFFIC_SOURCE = {"7b": "profiles/gemm_traffic_7b.md", "70b": "profiles/gemm_traffic_70b.md"}
 # the same kernel's duration as rocprofv3 --kernel-trace --stats sees it (no event pairs between
 # the launches): total GEMM microseconds per step from the committed profile of this workload
-ROCPROF_GEMM = {"7b": ("profiles/llama7b_step_kernel_stats.md", 3392.0),
-                "70b": ("profiles/llama70b_step_kernel_stats.md", 22746.0)}
+ROCPROF_GEMM = {"7b": ("profiles/llama7b_step_kernel_stats.md", 3263.0),
+                "70b": ("profiles/llama70b_step_kernel_stats.md", 22169.0)}
 # the second leg of the default run (the metric is quoted on both shapes)
 SECOND_LEG = {"workload": "70b", "steps": 64, "warmup": 8}
 # layer counts of the two oracle passes timed for cpu_baseline (about 10 s of host work at 7B width)
