@@ -36,3 +36,33 @@ def test_host_side_errors_without_gpu_work():
     assert L.bita_accept(None, None, None, 1, None, None, None, None, None, None, None) == -1
     assert L.bita_workspace_bytes(None, 1, 1) == 0
     assert L.bita_tree_template_info(None, 0) == -1
+
+
+def test_build_report_shows_no_register_spill_in_the_gemm():
+    """The build writes every kernel's register and scratch use next to the objects (and refuses
+    to link a skinny GEMM that spills).  Where the report of the library's build is at hand (it
+    does not travel with the library), the GEMM instantiations use no scratch and the two
+    attention forms that are known to spill a few registers outside their loop stay within that."""
+    import json
+    import pytest
+    from paper_2401_12522_amd import build
+    path = os.path.join(build.PKG_DIR, "_build", "libbita_kernel_resources.json")
+    if not os.path.exists(path):
+        pytest.skip("no build report beside the library")
+    res = json.load(open(path))
+    gemm = {k: v for k, v in res.items() if "gemm_skinny_kernel" in k}
+    assert len(gemm) >= 100
+    assert all(v["scratch"] == 0 for v in gemm.values())
+    spilling = {k: v["scratch"] for k, v in res.items() if v.get("scratch", 0) > 0}
+    assert all("tree_attn_kernelILi128ELi2E" in k and s <= 64 for k, s in spilling.items()), spilling
+
+
+def test_resource_remarks_are_parsed():
+    from paper_2401_12522_amd import build
+    tag = "[-Rpass-analysis=kernel-resource-usage]"
+    remarks = [f"a.hip:1:1: remark: Function Name: _Zk1 {tag}", f"a.hip:1:1: remark:     VGPRs: 20 {tag}",
+               f"a.hip:1:1: remark:     ScratchSize [bytes/lane]: 8 {tag}", f"a.hip:1:1: remark:     Occupancy [waves/SIMD]: 4 {tag}",
+               f"a.hip:9:1: remark: Function Name: _Zk2 {tag}", f"a.hip:9:1: remark:     AGPRs: 3 {tag}"]
+    assert build._kernel_resources(remarks) == {"_Zk1": {"vgprs": 20, "scratch": 8, "occupancy": 4}, "_Zk2": {"agprs": 3}}
+    lines = ["x.hip:3:1: warning: something", remarks[0], "    1 | code", "      | ^", "real error"]
+    assert build._without_remarks(lines) == ["x.hip:3:1: warning: something", "real error"]
