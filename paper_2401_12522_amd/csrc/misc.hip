@@ -102,16 +102,18 @@ __global__ __launch_bounds__(256) void rmsnorm_prep_kernel(float *__restrict__ x
 // ctx_len + depth(row) in the half-split pairing, write q [B][R][Hq][hd] and the rows'
 // k/v into the per-pass tree scratch [B][Hkv][R][hd].  q, k and v are all written as hi and lo
 // bf16 planes; only the hi planes of accepted rows are ever committed to the cache.
-__global__ __launch_bounds__(64) void qkv_rope_kernel(
+#define ROPE_HEADS_PER_WG 4      // one wave per head: fewer, larger workgroups to dispatch
+__global__ __launch_bounds__(64 * ROPE_HEADS_PER_WG) void qkv_rope_kernel(
     // (what the first loads depend on sits in the first 14 dwords, which arrive in registers)
     const float *__restrict__ partial, const int32_t *__restrict__ ctx_len, const int32_t *__restrict__ depth,
     const float *__restrict__ rs_ssq, int splits, int M, int R, int Hq, int Hkv, int hd, int max_pos,
     const float *__restrict__ rope_cos, const float *__restrict__ rope_sin, uint16_t *__restrict__ q,
     uint16_t *__restrict__ q_lo, uint16_t *__restrict__ k_tree, uint16_t *__restrict__ v_tree,
     uint16_t *__restrict__ k_tree_lo, uint16_t *__restrict__ v_tree_lo, int rs_chunks, float rs_inv_d, float rs_eps) {
-    const int row = blockIdx.x, head = blockIdx.y;       // head over Hq + 2*Hkv
+    const int row = blockIdx.x, head = blockIdx.y * ROPE_HEADS_PER_WG + (threadIdx.x >> 6);   // head over Hq + 2*Hkv
+    if (head >= Hq + 2 * Hkv) return;
     const int b = row / R, r = row % R;
-    const int half = hd >> 1, i = threadIdx.x;
+    const int half = hd >> 1, i = threadIdx.x & 63;
     if (i >= half) return;
     // Two memory round trips: the row's position and the sums behind its norm factor, then the
     // rotary table entry together with the partial sums (the table is read for value heads too,
@@ -320,7 +322,8 @@ void launch_qkv_rope(const float *partial, int splits, int batch, const Template
                      int Hkv, int hd, const int32_t *ctx_len, const float *rope_cos,
                      const float *rope_sin, int max_pos, void *q, void *q_lo, void *k_tree, void *v_tree,
                      void *k_tree_lo, void *v_tree_lo, const RowScale &rs, hipStream_t s) {
-    hipLaunchKernelGGL(qkv_rope_kernel, dim3(batch * t.rows, Hq + 2 * Hkv), dim3(64), 0, s, partial, ctx_len, t.depth,
+    hipLaunchKernelGGL(qkv_rope_kernel, dim3(batch * t.rows, (Hq + 2 * Hkv + ROPE_HEADS_PER_WG - 1) / ROPE_HEADS_PER_WG),
+                       dim3(64 * ROPE_HEADS_PER_WG), 0, s, partial, ctx_len, t.depth,
                        rs.ssq, splits, batch * t.rows, t.rows, Hq, Hkv, hd, max_pos, rope_cos, rope_sin,
                        (uint16_t *)q, (uint16_t *)q_lo, (uint16_t *)k_tree, (uint16_t *)v_tree,
                        (uint16_t *)k_tree_lo, (uint16_t *)v_tree_lo, rs.chunks, rs.inv_d, rs.eps);
