@@ -390,6 +390,22 @@ def run_workload(args, workload, steps, warmup, want_cpu_baseline):
     bytes_per_step = cfg.weight_bytes() + kv_bytes
     gbps = bytes_per_step / (ms_per_step * 1e-3) / 1e9
 
+    # ---- spread of the step time: the same run once more, an event behind every step -----------
+    # (outside the timed region above; an event between two replays costs a queue packet)
+    reset_state()
+    for t in range(warmup):
+        run(t)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    marks[0].record()
+    for t in range(warmup, total_steps):
+        run(t)
+        marks[t - warmup + 1].record()
+    torch.cuda.synchronize()
+    per_step = np.array([marks[i].elapsed_time(marks[i + 1]) for i in range(steps)])
+    step_ms = {"median": float(np.median(per_step)), "p10": float(np.percentile(per_step, 10)),
+               "p90": float(np.percentile(per_step, 90)), "min": float(per_step.min()), "max": float(per_step.max()),
+               "source": "HIP events behind every step of a second, untimed run of the same %d steps" % steps}
+
     # ---- dominant kernel (the skinny GEMM): HIP events around every launch, eager passes ------
     n_gemm = 4 * cfg.n_layers + 1
     prof_steps = max(1, min(4, steps))
@@ -428,7 +444,7 @@ def run_workload(args, workload, steps, warmup, want_cpu_baseline):
                                f"{tin.n_tree}-node tree ({args.tree or 'default'}) + {R - tin.n_tree} mask rows, P={cfg.n_prompt}, mode {args.mode}",
                    "rows": R, "batch": NB, "graph": graph is not None, "page_size": args.page_size or None},
         "hbm_gbps": gbps, "hbm_frac_of_peak": gbps / HBM_PEAK_GBPS, "bytes_per_step": bytes_per_step,
-        "gpu_ms_per_step": gpu_ms / steps, "mean_accepted": float(np.mean(nacc[warmup:])),
+        "gpu_ms_per_step": gpu_ms / steps, "step_ms": step_ms, "mean_accepted": float(np.mean(nacc[warmup:])),
         "generated_tokens_per_s": float(np.sum(nacc[warmup:])) / wall,
         "planted_resyncs": resyncs if args.mode == "planted" else None,
         "one_row_pass_ms": ar_ms_per_token,
@@ -465,7 +481,7 @@ def main():
         try:
             res = run_workload(args, leg["workload"], leg["steps"], leg["warmup"], False)
             keep = ("steps", "warmup", "ms_per_step", "value", "unit", "config", "hbm_gbps", "hbm_frac_of_peak",
-                    "bytes_per_step", "mean_accepted", "generated_tokens_per_s", "planted_resyncs", "one_row_pass_ms",
+                    "bytes_per_step", "step_ms", "mean_accepted", "generated_tokens_per_s", "planted_resyncs", "one_row_pass_ms",
                     "speedup_over_one_row_passes", "timed_run_equals_dry_run", "roofline")
             entry = {k: res[k] for k in keep}
             entry["includes"] = "build_tree, verify_step, accept, compact_kv per step (one HIP graph)"
